@@ -1,0 +1,148 @@
+"""Counter-based seeded generators for weights and inputs.
+
+splitmix64 (Steele, Lea, Flood 2014; the public-domain finaliser used to seed xoshiro) is applied
+to `key + (counter+1)*golden`, so element i of a tensor depends only on (key, i).  Uniforms take the
+top 53 bits; normals are Box-Muller pairs (cosine, sine) on the counter pair (2j, 2j+1).
+
+Weight recipe: every matrix and embedding table ~ N(0, std 0.02); biases 0, LayerNorm gamma 1 and
+beta 0.  `stress=True` instead draws biases and beta ~ N(0, 0.02) and gamma ~ 1 + N(0, 0.02) so that
+bias/gamma/beta code paths carry signal.  `bf16_grid=True` snaps matrices and embedding tables to
+values representable in bfloat16 (round to nearest even), so a consumer that stores them as
+bfloat16 and one that keeps float32 see identical numbers.
+
+Input recipe: sequence lengths uniform on the inclusive range [len_lo, len_hi]; the attention mask
+is a prefix of ones; token ids are uniform in [0, vocab) at every position, padded ones included.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from .spec import MTSpec, trunk_tensors, task_tensors
+
+_GOLDEN = np.uint64(0x9E3779B97F4A7C15)
+_M1 = np.uint64(0xBF58476D1CE4E5B9)
+_M2 = np.uint64(0x94D049BB133111EB)
+_CHUNK = 1 << 22
+
+
+def splitmix64(key: int, counters: np.ndarray) -> np.ndarray:
+    """Output of splitmix64 for state `key + (counter+1)*golden`, vectorised over uint64 counters."""
+    with np.errstate(over="ignore"):
+        z = np.uint64(key & 0xFFFFFFFFFFFFFFFF) + (counters.astype(np.uint64) + np.uint64(1)) * _GOLDEN
+        z = (z ^ (z >> np.uint64(30))) * _M1
+        z = (z ^ (z >> np.uint64(27))) * _M2
+        z = z ^ (z >> np.uint64(31))
+    return z
+
+
+def _subkey(seed: int, *ids: int) -> int:
+    k = seed & 0xFFFFFFFFFFFFFFFF
+    for i in ids:
+        k = int(splitmix64(k, np.array([i & 0xFFFFFFFFFFFFFFFF], dtype=np.uint64))[0])
+    return k
+
+
+def uniform01(key: int, start: int, n: int) -> np.ndarray:
+    """n doubles in [0,1) for counters start..start+n-1."""
+    c = np.arange(start, start + n, dtype=np.uint64)
+    return (splitmix64(key, c) >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
+
+
+def normal(key: int, n: int, out: np.ndarray | None = None) -> np.ndarray:
+    """n standard normals (float32); elements 2j and 2j+1 are the cosine and sine Box-Muller
+    outputs of the uniforms drawn at counters 2j and 2j+1."""
+    res = np.empty(n, dtype=np.float32) if out is None else out
+    for lo in range(0, n, _CHUNK):            # _CHUNK is even, so pairs never straddle chunks
+        m = min(_CHUNK, n - lo)
+        mp = (m + 1) // 2
+        c = np.arange(lo, lo + 2 * mp, dtype=np.uint64)
+        r = splitmix64(key, c) >> np.uint64(11)
+        u1 = (r[0::2].astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)   # (0,1]
+        u2 = r[1::2].astype(np.float64) * (1.0 / 9007199254740992.0)           # [0,1)
+        rad = np.sqrt(-2.0 * np.log(u1))
+        ang = 2.0 * np.pi * u2
+        pair = np.empty(2 * mp, dtype=np.float32)
+        pair[0::2] = rad * np.cos(ang)
+        pair[1::2] = rad * np.sin(ang)
+        res[lo:lo + m] = pair[:m]
+    return res
+
+
+def round_to_bf16_grid(x: np.ndarray) -> np.ndarray:
+    """Snap float32 values to the nearest bfloat16-representable value (ties to even), in place."""
+    u = x.view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    u += np.uint32(0x7FFF) + lsb
+    u &= np.uint32(0xFFFF0000)
+    return x
+
+
+def _fill(flat: np.ndarray, tensors, seed: int, scope_id: int, std: float, stress: bool, bf16_grid: bool):
+    off = 0
+    index = []
+    for ti, (name, shape) in enumerate(tensors):
+        n = int(np.prod(shape))
+        view = flat[off:off + n]
+        base = name.split(".")[-1]
+        key = _subkey(seed, scope_id, ti)
+        if len(shape) == 2:                       # matrices and embedding tables
+            normal(key, n, out=view)
+            view *= np.float32(std)
+            if bf16_grid:
+                round_to_bf16_grid(view)
+        elif base.endswith("_g"):                 # LayerNorm gamma
+            view[:] = 1.0
+            if stress:
+                view += normal(key, n) * np.float32(std)
+        else:                                     # biases and LayerNorm beta
+            view[:] = 0.0
+            if stress:
+                view += normal(key, n) * np.float32(std)
+        index.append((name, tuple(shape), off))
+        off += n
+    assert off == flat.size
+    return index
+
+
+def _count(tensors) -> int:
+    return int(sum(int(np.prod(s)) for _, s in tensors))
+
+
+def make_trunk_params(spec: MTSpec, *, stress: bool = False, bf16_grid: bool | None = None,
+                      seed: int | None = None, std: float = 0.02):
+    """Flat float32 parameter vector of the trunk scope (canonical order) and its (name, shape, offset) index."""
+    bf16_grid = (spec.precision == "bf16") if bf16_grid is None else bf16_grid
+    tensors = trunk_tensors(spec)
+    flat = np.empty(_count(tensors), dtype=np.float32)
+    index = _fill(flat, tensors, spec.weights_seed if seed is None else seed, 0, std, stress, bf16_grid)
+    return flat, index
+
+
+def make_task_params(spec: MTSpec, t: int, *, stress: bool = False, bf16_grid: bool | None = None,
+                     seed: int | None = None, std: float = 0.02):
+    """Flat float32 parameter vector of task t's scope (canonical order) and its index."""
+    bf16_grid = (spec.precision == "bf16") if bf16_grid is None else bf16_grid
+    tensors = task_tensors(spec, t)
+    flat = np.empty(_count(tensors), dtype=np.float32)
+    index = _fill(flat, tensors, spec.weights_seed if seed is None else seed, 1 + t, std, stress, bf16_grid)
+    return flat, index
+
+
+def make_inputs(spec: MTSpec, *, batch: int | None = None, seq: int | None = None, batch_index: int = 0,
+                len_lo: int | None = None, len_hi: int | None = None, seed: int | None = None):
+    """(input_ids[B,S] int32, attn_mask[B,S] int32, lengths[B] int32) for one synthetic batch."""
+    b = spec.batch if batch is None else batch
+    s = spec.seq if seq is None else seq
+    lo = spec.len_lo if len_lo is None else len_lo
+    hi = spec.len_hi if len_hi is None else len_hi
+    hi = min(hi, s)
+    lo = min(lo, hi)
+    sd = spec.input_seed if seed is None else seed
+    k_len = _subkey(sd, 1, batch_index)
+    k_ids = _subkey(sd, 2, batch_index)
+    lengths = (lo + np.floor(uniform01(k_len, 0, b) * (hi - lo + 1))).astype(np.int32)
+    lengths = np.minimum(lengths, hi).astype(np.int32)
+    ids = np.floor(uniform01(k_ids, 0, b * s) * spec.vocab).astype(np.int32).reshape(b, s)
+    ids = np.minimum(ids, spec.vocab - 1).astype(np.int32)
+    mask = (np.arange(s, dtype=np.int32)[None, :] < lengths[:, None]).astype(np.int32)
+    return ids, mask, lengths

@@ -1,0 +1,117 @@
+"""Shape descriptions of merged multi-task models and the canonical parameter order.
+
+A merged model (paper Section 3.3, Fig. 1(c)) is a linear trunk of shared frozen encoder layers
+plus one branch per task.  Task t reads the trunk after `fork_layer` layers (the x of the paper's
+(x, y) tuples under Table 2) and owns `n_layers` task-specific layers (the y), a pooler and a
+linear head with `n_classes` outputs.
+
+Parameter order (every linear is W[out][in] row-major, y = W x + b):
+  trunk scope : word_emb[V,H] pos_emb[P,H] type_emb[2,H] emb_ln_g[H] emb_ln_b[H], then per layer
+                Wq[H,H] bq[H] Wk bk Wv bv Wo[H,H] bo ln1_g ln1_b W1[F,H] b1[F] W2[H,F] b2[H] ln2_g ln2_b
+  task scope  : n_layers layers in the same order, then Wp[H,H] bp[H] Wc[C,H] bc[C]
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Tuple
+
+
+@dataclass(frozen=True)
+class TaskSpec:
+    fork_layer: int   # x_t: number of shared frozen layers this task reads through
+    n_layers: int     # y_t: task-specific layers
+    n_classes: int    # C_t (1 = regression)
+
+
+@dataclass(frozen=True)
+class MTSpec:
+    name: str
+    vocab: int
+    hidden: int
+    heads: int
+    ffn: int
+    max_pos: int
+    n_trunk_layers: int
+    tasks: Tuple[TaskSpec, ...]
+    precision: str            # "bf16" or "fp32"
+    batch: int
+    seq: int
+    len_lo: int
+    len_hi: int
+    type_vocab: int = 2
+    ln_eps: float = 1e-12
+    gelu: str = "erf"
+    input_seed: int = 1000
+    weights_seed: int = 20210705
+
+    @property
+    def n_tasks(self) -> int:
+        return len(self.tasks)
+
+    @property
+    def n_logits(self) -> int:
+        return sum(t.n_classes for t in self.tasks)
+
+
+def layer_tensors(h: int, f: int) -> List[Tuple[str, Tuple[int, ...]]]:
+    return [("Wq", (h, h)), ("bq", (h,)), ("Wk", (h, h)), ("bk", (h,)), ("Wv", (h, h)), ("bv", (h,)),
+            ("Wo", (h, h)), ("bo", (h,)), ("ln1_g", (h,)), ("ln1_b", (h,)),
+            ("W1", (f, h)), ("b1", (f,)), ("W2", (h, f)), ("b2", (h,)), ("ln2_g", (h,)), ("ln2_b", (h,))]
+
+
+def trunk_tensors(spec: MTSpec) -> List[Tuple[str, Tuple[int, ...]]]:
+    h = spec.hidden
+    out = [("word_emb", (spec.vocab, h)), ("pos_emb", (spec.max_pos, h)), ("type_emb", (spec.type_vocab, h)),
+           ("emb_ln_g", (h,)), ("emb_ln_b", (h,))]
+    for l in range(spec.n_trunk_layers):
+        out += [(f"L{l}.{n}", s) for n, s in layer_tensors(h, spec.ffn)]
+    return out
+
+
+def task_tensors(spec: MTSpec, t: int) -> List[Tuple[str, Tuple[int, ...]]]:
+    h = spec.hidden
+    task = spec.tasks[t]
+    out = []
+    for l in range(task.n_layers):
+        out += [(f"L{l}.{n}", s) for n, s in layer_tensors(h, spec.ffn)]
+    out += [("Wp", (h, h)), ("bp", (h,)), ("Wc", (task.n_classes, h)), ("bc", (task.n_classes,))]
+    return out
+
+
+_GLUE_CLASSES = (2, 2, 2, 3, 2, 2, 2, 1)   # QNLI RTE QQP MNLI SST-2 MRPC CoLA STS-B (Table 1 column order)
+
+
+def _uniform_tasks(x: int, y: int, classes=_GLUE_CLASSES) -> Tuple[TaskSpec, ...]:
+    return tuple(TaskSpec(x, y, c) for c in classes)
+
+
+def _hetero_tasks() -> Tuple[TaskSpec, ...]:
+    ks = (1, 2, 3, 4, 5, 6, 6, 4)     # fine-tuned depth k of the teacher; student keeps 12-k frozen, ceil(k/2) distilled
+    return tuple(TaskSpec(12 - k, (k + 1) // 2, c) for k, c in zip(ks, _GLUE_CLASSES))
+
+
+CONFIGS = {
+    "tiny": MTSpec("tiny", vocab=1000, hidden=64, heads=2, ffn=256, max_pos=32, n_trunk_layers=2,
+                   tasks=(TaskSpec(2, 1, 2), TaskSpec(2, 1, 3)), precision="fp32",
+                   batch=2, seq=16, len_lo=4, len_hi=16, input_seed=1000),
+    "base": MTSpec("base", vocab=30522, hidden=768, heads=12, ffn=3072, max_pos=512, n_trunk_layers=8,
+                   tasks=_uniform_tasks(8, 2), precision="bf16",
+                   batch=32, seq=128, len_lo=16, len_hi=128, input_seed=1001),
+    "hetero": MTSpec("hetero", vocab=30522, hidden=768, heads=12, ffn=3072, max_pos=512, n_trunk_layers=11,
+                     tasks=_hetero_tasks(), precision="bf16",
+                     batch=64, seq=128, len_lo=16, len_hi=128, input_seed=1002),
+    "latency": MTSpec("latency", vocab=30522, hidden=768, heads=12, ffn=3072, max_pos=512, n_trunk_layers=6,
+                      tasks=_uniform_tasks(6, 2), precision="bf16",
+                      batch=8, seq=64, len_lo=8, len_hi=64, input_seed=1003),
+    "large": MTSpec("large", vocab=30522, hidden=1024, heads=16, ffn=4096, max_pos=512, n_trunk_layers=18,
+                    tasks=_uniform_tasks(18, 2), precision="bf16",
+                    batch=128, seq=256, len_lo=64, len_hi=256, input_seed=1004),
+}
+_ORDER = ["tiny", "base", "hetero", "latency", "large"]
+
+
+def get_config(key) -> MTSpec:
+    """Look a workload up by name or by index 0..4 (tiny, base, hetero, latency, large)."""
+    if isinstance(key, int):
+        key = _ORDER[key]
+    return CONFIGS[key]

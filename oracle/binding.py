@@ -1,0 +1,162 @@
+"""ctypes binding of oracle/mt_oracle.c.  Marshalling only; no arithmetic here."""
+from __future__ import annotations
+
+import ctypes as C
+
+import numpy as np
+
+from .build import build
+
+_lib = None
+
+
+class _Cfg(C.Structure):
+    _fields_ = [("vocab", C.c_int32), ("hidden", C.c_int32), ("heads", C.c_int32), ("ffn", C.c_int32),
+                ("max_pos", C.c_int32), ("type_vocab", C.c_int32), ("n_trunk_layers", C.c_int32),
+                ("n_tasks", C.c_int32), ("gelu_tanh", C.c_int32), ("ln_eps", C.c_float)]
+
+
+class _Task(C.Structure):
+    _fields_ = [("fork_layer", C.c_int32), ("n_layers", C.c_int32), ("n_classes", C.c_int32)]
+
+
+def _fp(a):
+    return a.ctypes.data_as(C.POINTER(C.c_float)) if a is not None else None
+
+
+def _ip(a):
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        L.orc_layer_param_count.restype = C.c_int64
+        L.orc_layer_param_count.argtypes = [C.c_int64, C.c_int64]
+        L.orc_trunk_param_count.restype = C.c_int64
+        L.orc_task_param_count.restype = C.c_int64
+        L.orc_gelu.restype = C.c_float
+        L.orc_gelu.argtypes = [C.c_float, C.c_int]
+        L.orc_overhead.restype = C.c_int
+        L.orc_mt_forward.restype = C.c_int
+        L.orc_st_forward.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def layer_param_count(h: int, f: int) -> int:
+    return int(lib().orc_layer_param_count(h, f))
+
+
+def overhead(tasks) -> int:
+    """tasks: iterable of (fork_layer x, n_layers y[, n_classes])."""
+    arr = (_Task * len(tasks))(*[_Task(int(t[0]), int(t[1]), int(t[2]) if len(t) > 2 else 1) for t in tasks])
+    return int(lib().orc_overhead(arr, C.c_int(len(tasks))))
+
+
+def linear(x, w, b=None):
+    x, w = _f32(x), _f32(w)
+    m, k = x.shape
+    n = w.shape[0]
+    assert w.shape[1] == k
+    bb = _f32(b) if b is not None else None
+    y = np.empty((m, n), dtype=np.float32)
+    lib().orc_linear(_fp(x), C.c_int64(m), C.c_int64(k), _fp(w), _fp(bb), C.c_int64(n), _fp(y))
+    return y
+
+
+def layernorm(x, gamma, beta, eps=1e-12, residual=None):
+    x = _f32(x)
+    m, h = x.shape
+    r = _f32(residual) if residual is not None else None
+    g, bt = _f32(gamma), _f32(beta)
+    y = np.empty_like(x)
+    lib().orc_layernorm(_fp(x), _fp(r), C.c_int64(m), C.c_int64(h), _fp(g), _fp(bt), C.c_float(eps), _fp(y))
+    return y
+
+
+def gelu(x, tanh_form=False):
+    x = _f32(x)
+    y = np.empty_like(x)
+    lib().orc_gelu_array(_fp(x), C.c_int64(x.size), C.c_int(int(tanh_form)), _fp(y))
+    return y
+
+
+def softmax_row(s):
+    s = _f32(s).ravel()
+    p = np.empty_like(s)
+    lib().orc_softmax_row(_fp(s), C.c_int64(s.size), _fp(p))
+    return p
+
+
+def attention(q, k, v, mask, heads, want_probs=False):
+    q, k, v, mask = _f32(q), _f32(k), _f32(v), _i32(mask)
+    b, s, h = q.shape
+    ctx = np.empty_like(q)
+    probs = np.empty((b, heads, s, s), dtype=np.float32) if want_probs else None
+    lib().orc_attention(_fp(q), _fp(k), _fp(v), _ip(mask), C.c_int64(b), C.c_int64(s), C.c_int64(h),
+                        C.c_int64(heads), _fp(ctx), _fp(probs))
+    return (ctx, probs) if want_probs else ctx
+
+
+def _cfg_of(spec) -> _Cfg:
+    return _Cfg(spec.vocab, spec.hidden, spec.heads, spec.ffn, spec.max_pos, spec.type_vocab,
+                spec.n_trunk_layers, len(spec.tasks), 1 if spec.gelu == "tanh" else 0, spec.ln_eps)
+
+
+def encoder_layer(spec, layer_params, x, mask):
+    """One encoder layer; layer_params is the flat canonical parameter vector of that layer."""
+    x, mask, lp = _f32(x), _i32(mask), _f32(layer_params)
+    b, s, h = x.shape
+    assert lp.size == layer_param_count(spec.hidden, spec.ffn)
+    cfg = _cfg_of(spec)
+    out = np.empty_like(x)
+    lib().orc_encoder_layer(C.byref(cfg), _fp(lp), _fp(x), _ip(mask), C.c_int64(b), C.c_int64(s), _fp(out))
+    return out
+
+
+class Oracle:
+    """The merged model (mt_forward) and each student on its own (st_forward) for one spec + weights."""
+
+    def __init__(self, spec, trunk_params, task_params):
+        self.spec = spec
+        self.cfg = _cfg_of(spec)
+        self.tasks = (_Task * len(spec.tasks))(*[_Task(t.fork_layer, t.n_layers, t.n_classes) for t in spec.tasks])
+        self.trunk = _f32(trunk_params)
+        self.task_params = [_f32(p) for p in task_params]
+        L = lib()
+        assert self.trunk.size == L.orc_trunk_param_count(C.byref(self.cfg)), "trunk parameter count"
+        for t, p in enumerate(self.task_params):
+            assert p.size == L.orc_task_param_count(C.byref(self.cfg), C.byref(self.tasks[t])), f"task {t} parameter count"
+
+    def mt_forward(self, ids, mask, want_hidden=False):
+        ids, mask = _i32(ids), _i32(mask)
+        b, s = ids.shape
+        sp = self.spec
+        logits = np.empty((b, sp.n_logits), dtype=np.float32)
+        hidden = np.empty((sp.n_trunk_layers + 1, b, s, sp.hidden), dtype=np.float32) if want_hidden else None
+        ptrs = (C.POINTER(C.c_float) * len(self.task_params))(*[_fp(p) for p in self.task_params])
+        rc = lib().orc_mt_forward(C.byref(self.cfg), self.tasks, _fp(self.trunk), ptrs, _ip(ids), _ip(mask),
+                                  C.c_int64(b), C.c_int64(s), _fp(logits), _fp(hidden))
+        if rc != 0:
+            raise ValueError("invalid task table")
+        return (logits, hidden) if want_hidden else logits
+
+    def st_forward(self, t, ids, mask):
+        ids, mask = _i32(ids), _i32(mask)
+        b, s = ids.shape
+        logits = np.empty((b, self.spec.tasks[t].n_classes), dtype=np.float32)
+        rc = lib().orc_st_forward(C.byref(self.cfg), C.byref(self.tasks[t]), _fp(self.trunk), _fp(self.task_params[t]),
+                                  _ip(ids), _ip(mask), C.c_int64(b), C.c_int64(s), _fp(logits))
+        if rc != 0:
+            raise ValueError("invalid task")
+        return logits
