@@ -1,0 +1,149 @@
+#!/usr/bin/env python3
+"""Throughput of the merged multi-task serving forward pass on one MI355X.
+
+One step = one mt_forward over one synthetic batch (embeddings, shared trunk once, all task branches,
+poolers and heads), inputs and weights already resident in HBM.  Prints ONE JSON line:
+sequences/s (whole job), the roofline position of the dominant kernel (the bf16 MFMA GEMM) from
+per-launch HIP events recorded inside the library on the forward's stream, and the CPU oracle timed
+on a bounded sample of the same workload on this host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
+PEAK_FP32_VALU_TFLOPS = 157.3
+
+
+def gemm_flops_per_forward(spec, layer_evals_trunk, branch_layer_evals, B, S):
+    """Executed (dense, padded) FLOPs of the four linear layers, per class, for one forward."""
+    M, H, F = B * S, spec.hidden, spec.ffn
+    L = layer_evals_trunk + branch_layer_evals
+    return {"gemm_qkv": L * 2.0 * M * 3 * H * H, "gemm_out": L * 2.0 * M * H * H,
+            "gemm_ffn1": L * 2.0 * M * F * H, "gemm_ffn2": L * 2.0 * M * H * F}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="base", help="tiny | base | hetero | latency | large")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=8, help="sequences the CPU oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (sequences are independent, so N GPUs would run N "
+              "replicas with no collectives); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import mt_synth as ms
+    import paper_2107_05377_amd as mt
+    from paper_2107_05377_amd import build as mtbuild
+
+    if not os.path.exists(mt.LIB_PATH):
+        mtbuild.build()
+    mt.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    spec = ms.get_config(args.config)
+    B = args.batch or spec.batch
+    S = spec.seq
+    t0 = time.time()
+    model, _ = mt.load_synthetic(spec, max_batch=B, max_seq=S)
+    load_s = time.time() - t0
+    n_batches = 8
+    batches = []
+    for i in range(n_batches):
+        ids, mask, _ = ms.make_inputs(spec, batch=B, batch_index=i)
+        batches.append((torch.from_numpy(ids).cuda(), torch.from_numpy(mask).cuda()))
+    out = torch.zeros((B, model.n_logits), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    for i in range(args.warmup):
+        model.forward(*batches[i % n_batches], out=out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(args.steps):
+        model.forward(*batches[i % n_batches], out=out)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    seq_per_s = B / (ms_per_step * 1e-3)
+    assert torch.isfinite(out).all()
+
+    # ---- per-kernel durations from HIP events around every launch, same stream, same steps
+    model.profile_enable(True)
+    for i in range(args.steps):
+        model.forward(*batches[i % n_batches], out=out)
+    torch.cuda.synchronize()
+    prof = model.profile_read()
+    model.profile_enable(False)
+
+    n_layers = model.layer_count()
+    flops = gemm_flops_per_forward(spec, spec.n_trunk_layers, n_layers - spec.n_trunk_layers, B, S)
+    kernels = {}
+    for k, (ms_tot, n) in prof.items():
+        if n == 0:
+            continue
+        ent = {"launches_per_step": n / args.steps, "ms_per_step": ms_tot / args.steps, "avg_us": 1e3 * ms_tot / n}
+        if k in flops:
+            ent["tflops"] = flops[k] * args.steps / (ms_tot * 1e-3) / 1e12
+        kernels[k] = ent
+    gemm_ms = sum(prof[k][0] for k in flops) / args.steps
+    gemm_launches = sum(prof[k][1] for k in flops) / args.steps
+    gemm_tflops = sum(flops.values()) / (gemm_ms * 1e-3) / 1e12
+    bf16 = spec.precision == "bf16"
+    peak = PEAK_BF16_MFMA_TFLOPS if bf16 else PEAK_FP32_VALU_TFLOPS
+    roofline = {"kernel": "gemm_bf16_kernel" if bf16 else "gemm_f32_kernel", "bound": "mfma" if bf16 else "alu",
+                "achieved": gemm_tflops, "peak": peak, "unit": "TFLOP/s", "frac": gemm_tflops / peak, "traffic": None,
+                "flops_per_launch": sum(flops.values()) / gemm_launches, "avg_launch_us": 1e3 * gemm_ms / gemm_launches,
+                "launches_per_step": gemm_launches, "gemm_ms_per_step": gemm_ms}
+
+    h = spec.hidden
+    per_layer = 8.0 * S * h * h + 4.0 * S * h * spec.ffn + 4.0 * S * S * h
+    flops_per_seq = n_layers * per_layer + spec.n_tasks * 2.0 * h * h
+    e2e_tflops = flops_per_seq * seq_per_s / 1e12
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        n = max(1, min(args.cpu_sample, B))
+        trunk, _ = ms.make_trunk_params(spec)
+        tasks = [ms.make_task_params(spec, t)[0] for t in range(spec.n_tasks)]
+        orc = oracle.Oracle(spec, trunk, tasks)
+        ids, mask, _ = ms.make_inputs(spec, batch=B, batch_index=0)
+        t0 = time.time()
+        ref = orc.mt_forward(ids[:n], mask[:n])
+        dt = time.time() - t0
+        got = model.forward(*batches[0]).cpu().numpy()[:n]
+        cpu = {"value": n / dt, "unit": "sequences/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"first {n} sequences of batch 0 of the same workload, one pass, {dt:.1f} s",
+               "max_abs_dlogit_vs_gpu": float(np.abs(got - ref).max())}
+
+    line = {
+        "metric": "sequences/sec (8-task MT forward, BERT-base, seq128) + % bf16 MFMA peak",
+        "value": seq_per_s, "unit": "sequences/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{spec.name}: H={spec.hidden} A={spec.heads} F={spec.ffn} trunk={spec.n_trunk_layers} "
+                               f"tasks={spec.n_tasks} layers={n_layers} B={B} S={S} len~U[{spec.len_lo},{spec.len_hi}]",
+                   "batch": B, "seq_len": S, "layer_evals": n_layers},
+        "e2e_tflops_dense_padded": e2e_tflops, "e2e_frac_of_peak": e2e_tflops / peak,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "weights_load_s": load_s,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

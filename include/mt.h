@@ -1,0 +1,185 @@
+/*
+ * mt.h - C ABI of the MI355X (gfx950) serving library for merged multi-task BERT models.
+ *
+ * The model is the "final multi-task model" of the paper's Fig. 1(c) / Section 3.3 (Model Merging):
+ * single-task students that share frozen bottom encoder layers are loaded into ONE graph, so the
+ * shared layers (the trunk) run once per batch and every task continues from the trunk layer it
+ * forked at with its own few distilled layers, a pooler and a classifier.  One call returns the
+ * logits of all enabled tasks (Section 5.2: no task's output is available before all are computed).
+ *
+ * Conventions
+ *   - Every function returns MT_OK (0) or a negative MT_ERR_* code; nothing throws or aborts across
+ *     this boundary.  mt_last_error() gives a text for the most recent failure on that model.
+ *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller owns all buffers:
+ *     token ids, masks, logits, the weight arena and the workspace arena.  The library owns only
+ *     host-side metadata inside mt_model.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  mt_forward only
+ *     enqueues work on it: it never synchronises, never allocates, never frees.
+ *   - All argument checks are done on the host before anything is enqueued.
+ *   - Linear layers are y = W x + b with W stored [out][in] row-major.
+ */
+#ifndef MT_H_
+#define MT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MT_ABI_VERSION 1u
+
+enum {
+    MT_OK = 0,
+    MT_ERR_NULL = -1,    /* a required pointer is NULL */
+    MT_ERR_CONFIG = -2,  /* inconsistent or unsupported configuration */
+    MT_ERR_SHAPE = -3,   /* batch / seq / buffer size outside what the model was created or bound for */
+    MT_ERR_STATE = -4,   /* call order: forward before bind/load, load before bind, ... */
+    MT_ERR_BLOB = -5,    /* malformed weight blob */
+    MT_ERR_HIP = -6      /* a HIP runtime call failed */
+};
+
+enum { MT_BF16 = 0, MT_FP32_CHECK = 1 };     /* mt_config.precision */
+enum { MT_GELU_ERF = 0, MT_GELU_TANH = 1 };  /* mt_config.gelu */
+
+typedef struct mt_model mt_model; /* opaque, library-owned host object */
+
+/*
+ * One task of the merged model: the (x, y) tuple printed under Table 2 plus its output width.
+ *   fork_layer  x_t: the task reads the trunk's hidden state after this many shared layers
+ *               (0 = directly after the embeddings); 0 <= x_t <= n_trunk_layers.
+ *   n_layers    y_t >= 0 task-specific encoder layers.
+ *   n_classes   C_t >= 1 logits (1 = regression output, returned unchanged).
+ */
+typedef struct {
+    int32_t fork_layer;
+    int32_t n_layers;
+    int32_t n_classes;
+} mt_task_desc;
+
+/*
+ * Model description.  struct_size/version guard the layout (sizeof(mt_config), MT_ABI_VERSION).
+ * n_trunk_layers must equal max_t fork_layer (the shared depth of the "Layers" column of Table 2).
+ * precision MT_BF16: matrices and embedding tables are stored as bfloat16 (round to nearest even
+ * from the float32 blob), contractions run on bf16 matrix cores with float32 accumulation; it needs
+ * hidden/heads == 64, hidden % 64 == 0 and ffn % 64 == 0.  MT_FP32_CHECK: everything float32 on
+ * the vector ALUs, any shape, meant for validation.
+ * max_batch*max_seq bounds the workspace; max_seq <= max_pos.
+ */
+typedef struct {
+    uint32_t struct_size, version;
+    int32_t vocab, hidden, heads, ffn, max_pos, type_vocab;
+    int32_t n_trunk_layers;
+    int32_t n_tasks;
+    const mt_task_desc* tasks; /* host array [n_tasks], copied by mt_create */
+    int32_t precision;
+    int32_t gelu;
+    float ln_eps;
+    int32_t max_batch, max_seq;
+} mt_config;
+
+/* Validate cfg and build the merged graph's schedule (Section 3.3).  Host only; touches no GPU.
+ * On success *out owns a new model (release with mt_destroy).  Errors: NULL, CONFIG. */
+int mt_create(const mt_config* cfg, mt_model** out);
+void mt_destroy(mt_model* m);
+
+/* Sizes in bytes of the two device arenas the caller must provide to mt_bind. */
+size_t mt_weight_bytes(const mt_model* m);
+size_t mt_workspace_bytes(const mt_model* m);
+
+/* Attach caller-owned device memory.  Both pointers must be 256-byte aligned and at least as large
+ * as the sizes above; they must stay valid until mt_destroy.  Errors: NULL, SHAPE. */
+int mt_bind(mt_model* m, void* d_weights, size_t weight_bytes, void* d_workspace, size_t workspace_bytes);
+
+/*
+ * Load one checkpoint into the graph ("load weights from multiple model checkpoints into one
+ * computation graph", Section 3.3).  scope -1 = embeddings + trunk layers, scope t >= 0 = task t's
+ * layers, pooler and classifier; loading one task never touches another's memory (the per-task
+ * update of Section 5.1).  h_blob is a little-endian HOST buffer:
+ *     char magic[4] = "MTW1"; int32 scope; int32 n_tensors; int32 reserved(0);  then float32 data
+ *   trunk scope: word_emb[V,H] pos_emb[P,H] type_emb[TV,H] emb_ln_g[H] emb_ln_b[H], then per layer
+ *     Wq[H,H] bq[H] Wk bk Wv bv Wo[H,H] bo ln1_g ln1_b W1[F,H] b1[F] W2[H,F] b2[H] ln2_g ln2_b
+ *   task scope : y_t layers in that order, then Wp[H,H] bp[H] Wc[C,H] bc[C]
+ * The call converts on the host, copies on `hip_stream` and waits for the copy, so h_blob may be
+ * released on return.  Errors: NULL, STATE (not bound), BLOB (magic/scope/size mismatch), HIP.
+ */
+int mt_load_weights(mt_model* m, int32_t scope, const void* h_blob, size_t nbytes, void* hip_stream);
+
+/*
+ * The serving forward pass: embeddings, the shared trunk once, then all enabled tasks' branches as
+ * grouped launches, then poolers and classifiers.
+ *   d_input_ids [batch][seq] int32, clamped into [0, vocab) by the kernel;
+ *   d_attn_mask [batch][seq] int32, 1 = real token, 0 = padding; applied to attention keys only;
+ *               position 0 of every sequence must be a real token (the pooler reads it);
+ *   h_task_mask host array [n_tasks] of 0/1, or NULL for all tasks.  Disabled tasks are not computed
+ *               and their logit columns are left untouched; the trunk runs only as deep as the
+ *               deepest enabled fork;
+ *   d_out_logits [batch][C_tot] float32 row-major, C_tot = sum of n_classes, task t's columns start
+ *               at mt_logit_offset(m, t).  Raw logits (no softmax).
+ * Hidden states at padded positions are unspecified and never influence a real token.
+ * Errors: NULL, STATE (not bound / a needed scope not loaded), SHAPE (batch, seq out of range), HIP.
+ */
+int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_mask, int32_t batch, int32_t seq,
+               const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream);
+
+/* Column of task t's first logit, or MT_ERR_SHAPE.  mt_n_logits = C_tot. */
+int mt_logit_offset(const mt_model* m, int32_t task);
+int mt_n_logits(const mt_model* m);
+
+/* The paper's cost measure (Section 4.1, "Overhead" of Table 2): the number of transformer layers
+ * evaluated per request, n_trunk_layers + sum_t n_layers. */
+int mt_layer_count(const mt_model* m);
+
+/* Text of the last error on this model ("" if none).  mt_error_name maps a code to its name. */
+const char* mt_last_error(const mt_model* m);
+const char* mt_error_name(int code);
+
+/*
+ * Copy the float32 hidden state [batch][seq][hidden] the last mt_forward left for
+ *   task < 0 : the trunk after `layer` shared layers (only layers some task forks at are kept);
+ *   task >= 0: task's branch output (after its last own layer; `layer` ignored)
+ * into d_out on `hip_stream`.  For validation.  Errors: NULL, STATE, SHAPE.
+ */
+int mt_read_hidden(mt_model* m, int32_t task, int32_t layer, float* d_out, size_t out_bytes, void* hip_stream);
+
+/*
+ * Per-kernel timing.  While enabled, mt_forward brackets every launch with HIP events on the
+ * forward's stream.  mt_profile_read waits for them, then reports, per kernel class, the number of
+ * launches and their summed duration since the last read, and clears the record.
+ */
+enum {
+    MT_K_EMBED = 0, MT_K_GEMM_QKV, MT_K_ATTN, MT_K_GEMM_OUT, MT_K_LN, MT_K_GEMM_FFN1, MT_K_GEMM_FFN2,
+    MT_K_POOL, MT_K_COUNT
+};
+int mt_profile_enable(mt_model* m, int32_t on);
+int mt_profile_read(mt_model* m, float* h_ms /*[MT_K_COUNT]*/, int32_t* h_launches /*[MT_K_COUNT]*/);
+
+/*
+ * Single operations on device buffers, the same kernels mt_forward launches, exposed so each can be
+ * checked on its own.  `precision` selects the element type of activations/weights named "act":
+ * MT_BF16 -> bfloat16, MT_FP32_CHECK -> float32.  All enqueue on hip_stream and return.
+ */
+/* C[M,N] = epilogue(A[M,K] W[N,K]^T + bias[N]) ; act_kind: 0 none, 1 GELU(erf), 2 GELU(tanh), 3 tanh.
+ * d_residual (float32 [M,N]) may be NULL; if given it is added after the activation.
+ * out_f32 != 0 stores float32, else the act type.  lda/ldc in elements. */
+int mt_op_linear(int32_t precision, const void* d_A, int64_t lda, const void* d_W, const float* d_bias,
+                 const float* d_residual, void* d_C, int64_t ldc, int32_t M, int32_t N, int32_t K,
+                 int32_t act_kind, int32_t out_f32, void* hip_stream);
+/* ctx[b,s,a*d:(a+1)*d] = softmax(q k^T / sqrt(d) + mask) v per head; d_qkv is [B*S][3H] act
+ * (columns Q | K | V), d_ctx [B*S][H] act. */
+int mt_op_attention(int32_t precision, const void* d_qkv, const int32_t* d_mask, void* d_ctx,
+                    int32_t batch, int32_t seq, int32_t hidden, int32_t heads, void* hip_stream);
+/* out = LayerNorm(x) * gamma + beta per row; x float32 [M,H]; writes float32 d_out_f32 (may be NULL)
+ * and bfloat16 d_out_bf16 (may be NULL). */
+int mt_op_layernorm(const float* d_x, const float* d_gamma, const float* d_beta, float eps, float* d_out_f32,
+                    void* d_out_bf16, int32_t M, int32_t H, void* hip_stream);
+
+/* Tuning aid for benchmarks: force one bf16 GEMM tile configuration for all later launches in this
+ * process (0 = choose by shape, the default; 1..6 = a fixed configuration).  Returns the previous value. */
+int mt_debug_set_gemm_tile(int32_t sel);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MT_H_ */

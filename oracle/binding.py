@@ -53,6 +53,11 @@ def _i32(a):
     return np.ascontiguousarray(a, dtype=np.int32)
 
 
+def num_threads() -> int:
+    """Threads the oracle's OpenMP loops will use."""
+    return int(lib().orc_num_threads())
+
+
 def layer_param_count(h: int, f: int) -> int:
     return int(lib().orc_layer_param_count(h, f))
 

@@ -51,6 +51,13 @@ typedef struct {
     int32_t n_classes;   /* C_t */
 } orc_task;
 
+#ifdef _OPENMP
+#include <omp.h>
+int orc_num_threads(void) { return omp_get_max_threads(); }
+#else
+int orc_num_threads(void) { return 1; }
+#endif
+
 /* ---------------------------------------------------------------- elementary operations */
 
 /* y[m][n] = sum_k x[m][k] * W[n][k] + b[n]   (b may be NULL) */

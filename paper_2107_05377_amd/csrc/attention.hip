@@ -1,0 +1,274 @@
+// Masked-softmax attention, one (problem, sequence, head, 128-query tile) per workgroup.
+//
+// bfloat16 path (head width 64): the workgroup stages the head's keys K[S][64] and its values,
+// transposed to Vt[64][S], in LDS once; each of the 4 wavefronts then owns 32 queries.
+// Scores are computed TRANSPOSED, St[key][query] = K Q^T, with v_mfma_f32_32x32x16_bf16: a lane then
+// holds, for ONE query, 4 consecutive keys per 8-key group, so
+//   - a softmax row lives in just two lanes (lane, lane^32): row max and row sum are in-register
+//     reductions plus one cross-lane exchange;
+//   - the probabilities are already in the register layout of the MFMA's second operand for
+//     Ot[d][query] = Vt P^T, so P never goes through LDS;
+//   - the per-query rescale of the running output (online softmax over 128-key chunks) and the final
+//     1/sum are per-lane scalars.
+// Softmax arithmetic is float32 in the log2 domain (exp2 of (score*scale - max)*log2(e)).
+// Padding: a masked key gets the score -10000 (selected, not added, so whatever a padded row holds
+// cannot leak), its V row is zeroed at staging, and 32-key blocks with no real key are skipped
+// altogether (their weights would underflow to exactly zero).  Block 0 is never skipped, so a row
+// always has a non-empty softmax.  Wavefronts whose 32 queries are all padding skip their work:
+// hidden states at padded positions are unspecified by contract.
+//
+// float32 path: plain per-query loops for the validation mode, any head width.
+#include "kernels.h"
+#include "device_util.h"
+
+namespace mt {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kMaskedScore = -10000.0f;
+
+__device__ inline int k_chunk_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+
+__global__ __launch_bounds__(256) void attention_bf16_kernel(AttnGroup g, const int32_t* __restrict__ mask, int B,
+                                                             int S, int H, int Sk, float scale_log2e)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int vt_stride = Sk + 4;                                  // elements; keeps 8-byte reads aligned, spreads banks
+    unsigned char* Ks = lds;                                       // [Sk][128 B], 16-byte chunks XOR-swizzled by row
+    __bf16* Vt = reinterpret_cast<__bf16*>(lds + Sk * 128);        // [64][vt_stride]
+    float* kvalid = reinterpret_cast<float*>(lds + Sk * 128 + 64 * vt_stride * 2);   // [Sk] 1.0 = real key
+    int* blk_any = reinterpret_cast<int*>(kvalid + Sk);            // [Sk/32]
+
+    const int grp = blockIdx.z / B, b = blockIdx.z % B, a = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const size_t ld = (size_t)3 * H;
+    const __bf16* __restrict__ qkv = static_cast<const __bf16*>(g.qkv[grp]) + (size_t)b * S * ld;
+    const int32_t* __restrict__ mrow = mask + (size_t)b * S;
+    const int nblk = Sk / 32;
+
+    // ---- stage key validity
+    for (int k = tid; k < Sk; k += 256) kvalid[k] = (k < S && mrow[k] != 0) ? 1.0f : 0.0f;
+    __syncthreads();
+    if (tid < nblk) {
+        int any = 0;
+        for (int k = 0; k < 32; ++k) any |= (kvalid[tid * 32 + k] != 0.0f);
+        blk_any[tid] = (tid == 0) ? 1 : any;
+    }
+    // ---- stage K (rows = keys, 8 chunks of 8 elements)
+    for (int c = tid; c < Sk * 8; c += 256) {
+        const int key = c >> 3, ch = c & 7;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (key < S) v = *reinterpret_cast<const uint4*>(qkv + (size_t)key * ld + H + a * 64 + ch * 8);
+        *reinterpret_cast<uint4*>(Ks + k_chunk_off(key, ch)) = v;
+    }
+    // ---- stage V transposed: each item is a pair of adjacent keys x one 8-wide chunk of d
+    for (int c = tid; c < (Sk / 2) * 8; c += 256) {
+        const int pair = c >> 3, ch = c & 7;
+        const int k0 = pair * 2, k1 = k0 + 1;
+        uint4 v0 = make_uint4(0, 0, 0, 0), v1 = make_uint4(0, 0, 0, 0);
+        if (kvalid[k0] != 0.0f) v0 = *reinterpret_cast<const uint4*>(qkv + (size_t)k0 * ld + 2 * H + a * 64 + ch * 8);
+        if (kvalid[k1] != 0.0f) v1 = *reinterpret_cast<const uint4*>(qkv + (size_t)k1 * ld + 2 * H + a * 64 + ch * 8);
+        const uint32_t w0[4] = {v0.x, v0.y, v0.z, v0.w}, w1[4] = {v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t lo = (w0[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+            const uint32_t hi = (w1[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+            *reinterpret_cast<uint32_t*>(Vt + (size_t)(ch * 8 + e) * vt_stride + k0) = lo | (hi << 16);
+        }
+    }
+    __syncthreads();
+
+    // ---- this wavefront's 32 queries
+    const int q0 = blockIdx.x * 128 + wave * 32;
+    if (q0 >= S) return;
+    const int q = q0 + l32;
+    const bool q_real = (q < S) && (mrow[q < S ? q : 0] != 0);
+    if (__ballot(q_real) == 0ull) return;
+    const int qc = q < S ? q : S - 1;
+
+    bf16x8 qf[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        qf[kk] = *reinterpret_cast<const bf16x8*>(qkv + (size_t)qc * ld + a * 64 + kk * 16 + half * 8);
+
+    f32x16 o[2];
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[dt][e] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    for (int c0 = 0; c0 < nblk; c0 += 4) {
+        int valid[4];
+        int any = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            valid[j] = (c0 + j < nblk) ? blk_any[c0 + j] : 0;
+            any |= valid[j];
+        }
+        if (!any) continue;
+        f32x16 sc[4];
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (valid[j]) {
+                const int jb = c0 + j;
+                f32x16 acc;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + k_chunk_off(jb * 32 + l32, kk * 2 + half));
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], acc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq) {
+                    const float4 kv = *reinterpret_cast<const float4*>(kvalid + jb * 32 + qq * 8 + half * 4);
+                    const float f[4] = {kv.x, kv.y, kv.z, kv.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float t = (f[e] != 0.0f) ? acc[qq * 4 + e] * scale_log2e : kMaskedScore * kLog2e;
+                        acc[qq * 4 + e] = t;
+                        mloc = fmaxf(mloc, t);
+                    }
+                }
+                sc[j] = acc;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) sc[j][e] = -INFINITY;
+            }
+        }
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+        const float m_new = fmaxf(m_run, mloc);
+        const float alpha = exp2f(m_run - m_new);     // 0 on the first chunk (m_run = -inf)
+        float lsum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float p = exp2f(sc[j][e] - m_new);
+                sc[j][e] = p;
+                lsum += p;
+            }
+        lsum += __shfl_xor(lsum, 32, 64);
+        l_run = l_run * alpha + lsum;
+        m_run = m_new;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
+
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (!valid[j]) continue;
+            const int jb = c0 + j;
+#pragma unroll
+            for (int mf = 0; mf < 2; ++mf) {
+                bf16x8 pf;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pf[e] = (__bf16)sc[j][mf * 8 + e];
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) {
+                    const __bf16* vrow = Vt + (size_t)(dt * 32 + l32) * vt_stride + jb * 32 + mf * 16 + half * 4;
+                    const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vrow);
+                    const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vrow + 8);
+                    const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[dt], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    if (q < S) {
+        const float inv = 1.0f / l_run;
+        __bf16* out = static_cast<__bf16*>(g.ctx[grp]) + ((size_t)b * S + q) * H + a * 64;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+                bf16x4 v = {(__bf16)(o[dt][qq * 4 + 0] * inv), (__bf16)(o[dt][qq * 4 + 1] * inv),
+                            (__bf16)(o[dt][qq * 4 + 2] * inv), (__bf16)(o[dt][qq * 4 + 3] * inv)};
+                *reinterpret_cast<bf16x4*>(out + dt * 32 + qq * 8 + half * 4) = v;
+            }
+    }
+}
+
+// float32 validation path.  One workgroup per (problem, sequence, head); each wavefront takes queries
+// wave, wave+4, ...; lanes run over keys for the scores and over head columns for the context.
+__global__ __launch_bounds__(256) void attention_f32_kernel(AttnGroup g, const int32_t* __restrict__ mask, int B,
+                                                            int S, int H, int A, float scale)
+{
+    extern __shared__ float sprob[];   // [4][S]
+    const int grp = blockIdx.z / B, b = blockIdx.z % B, a = blockIdx.y;
+    const int d = H / A;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t ld = (size_t)3 * H;
+    const float* qkv = static_cast<const float*>(g.qkv[grp]) + (size_t)b * S * ld;
+    const int32_t* mrow = mask + (size_t)b * S;
+    float* p = sprob + wave * S;
+    for (int i = wave; i < S; i += 4) {
+        const float* qi = qkv + (size_t)i * ld + a * d;
+        float mx = -INFINITY;
+        for (int j = lane; j < S; j += 64) {
+            const float* kj = qkv + (size_t)j * ld + H + a * d;
+            float acc = 0.f;
+            for (int c = 0; c < d; ++c) acc = fmaf(qi[c], kj[c], acc);
+            float sc = acc * scale;
+            if (mrow[j] == 0) sc += kMaskedScore;
+            p[j] = sc;
+            mx = fmaxf(mx, sc);
+        }
+        mx = wave_max(mx);
+        float sum = 0.f;
+        for (int j = lane; j < S; j += 64) {
+            const float e = expf(p[j] - mx);
+            p[j] = e;
+            sum += e;
+        }
+        sum = wave_sum(sum);
+        const float inv = 1.0f / sum;
+        for (int c = lane; c < d; c += 64) {
+            float acc = 0.f;
+            for (int j = 0; j < S; ++j) acc = fmaf(p[j], qkv[(size_t)j * ld + 2 * H + a * d + c], acc);
+            static_cast<float*>(g.ctx[grp])[((size_t)b * S + i) * H + a * d + c] = acc * inv;
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_attention_bf16(const AttnGroup& g, int G, const int32_t* mask, int B, int S, int H, int A,
+                                 hipStream_t stream)
+{
+    if (G <= 0 || B <= 0 || S <= 0) return hipSuccess;
+    if (H != A * 64 || G > kMaxGroup || S > 1024) return hipErrorInvalidValue;
+    const int Sk = (S + 31) / 32 * 32;
+    const size_t lds = (size_t)Sk * 128 + (size_t)64 * (Sk + 4) * 2 + (size_t)Sk * 4 + (size_t)(Sk / 32) * 4;
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    static bool attr_set = false;
+    if (lds > 64 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)attention_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((S + 127) / 128, A, B * G), block(256);
+    const float scale_log2e = (1.0f / sqrtf(64.0f)) * kLog2e;
+    hipLaunchKernelGGL(attention_bf16_kernel, grid, block, lds, stream, g, mask, B, S, H, Sk, scale_log2e);
+    return hipGetLastError();
+}
+
+hipError_t launch_attention_f32(const AttnGroup& g, int G, const int32_t* mask, int B, int S, int H, int A,
+                                hipStream_t stream)
+{
+    if (G <= 0 || B <= 0 || S <= 0) return hipSuccess;
+    if (G > kMaxGroup || (size_t)S * 16 > 64 * 1024) return hipErrorInvalidValue;
+    dim3 grid(1, A, B * G), block(256);
+    const float scale = 1.0f / sqrtf((float)(H / A));
+    hipLaunchKernelGGL(attention_f32_kernel, grid, block, (size_t)S * 4 * sizeof(float), stream, g, mask, B, S, H, A, scale);
+    return hipGetLastError();
+}
+
+}  // namespace mt

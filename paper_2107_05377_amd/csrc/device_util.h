@@ -1,0 +1,46 @@
+// Small device helpers shared by the gfx950 kernels: vector types, wavefront reductions, activations.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+namespace mt {
+
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+// Sum / max over the 64 lanes of a wavefront; every lane receives the result.
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ inline float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+// GELU(x) = x * Phi(x).  Exact form through erff; tanh form as the published approximation.
+__device__ inline float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+__device__ inline float gelu_tanh(float x)
+{
+    const float u = 0.79788456080286536f * (x + 0.044715f * x * x * x);
+    return 0.5f * x * (1.0f + tanhf(u));
+}
+
+__device__ inline float apply_act(float v, int act)
+{
+    switch (act) {
+        case 1: return gelu_erf(v);
+        case 2: return gelu_tanh(v);
+        case 3: return tanhf(v);
+        default: return v;
+    }
+}
+
+}  // namespace mt

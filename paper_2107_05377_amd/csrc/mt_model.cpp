@@ -1,0 +1,826 @@
+// Host side of the library: configuration checks, the merged graph's schedule (paper Section 3.3,
+// Fig. 1(c)), arena layouts, checkpoint loading and the enqueue-only forward pass.
+//
+// Schedule.  The trunk (shared frozen layers) runs once up to the deepest fork among the enabled
+// tasks; the hidden state after every layer some task forks at is kept (a "tap").  Branches then
+// advance in lock step: stage s runs layer s of every enabled task that has at least s own layers,
+// as grouped launches with one problem per task, reading either the task's tap (s = 1) or its own
+// state.  Finally one grouped pooler launch and one grouped classifier launch write all logits.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "../../include/mt.h"
+#include "kernels.h"
+
+using namespace mt;
+
+namespace mt {
+extern int g_gemm_bf16_tile_override;
+}
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct LayerW {   // byte offsets into the weight arena
+    size_t Wqkv, bqkv, Wo, bo, ln1g, ln1b, W1, b1, W2, b2, ln2g, ln2b;
+};
+struct TaskW {
+    std::vector<LayerW> layers;
+    size_t Wp, bp, Wc, bc;
+    size_t begin, end;   // the task's private region of the arena
+};
+struct Scratch {   // byte offsets into the workspace; one set for the trunk and one per task
+    size_t qkv, ctx, y, x1f, x1b, u;
+};
+struct ProfRec {
+    int klass;
+    hipEvent_t t0, t1;
+};
+
+}  // namespace
+
+struct mt_model {
+    mt_config cfg;
+    std::vector<mt_task_desc> tasks;
+    bool bf16 = true;
+    size_t esz = 2;   // bytes per matrix / activation element
+    int C_tot = 0;
+    std::vector<int> logit_off;
+
+    // weight arena
+    size_t w_word = 0, w_pos = 0, w_type = 0, w_embg = 0, w_embb = 0, w_trunk_end = 0;
+    std::vector<LayerW> trunk;
+    std::vector<TaskW> taskw;
+    size_t weight_bytes = 0;
+
+    // workspace
+    size_t Mmax = 0;
+    std::vector<int> tap_of_layer;            // layer index 0..D -> tap slot or -1
+    std::vector<size_t> tap_f, tap_b;         // per tap slot
+    size_t pp_f[2] = {0, 0}, pp_b[2] = {0, 0};
+    Scratch trunk_scr{};
+    std::vector<Scratch> task_scr;
+    std::vector<size_t> task_xf, task_xb;
+    size_t pooled = 0;
+    size_t workspace_bytes = 0;
+
+    unsigned char* d_w = nullptr;
+    unsigned char* d_ws = nullptr;
+    bool trunk_loaded = false;
+    std::vector<char> task_loaded;
+
+    int last_B = 0, last_S = 0;
+    std::vector<char> last_enabled;
+
+    bool profiling = false;
+    std::vector<ProfRec> prof;
+    std::vector<hipEvent_t> event_pool;
+
+    std::string err;
+};
+
+namespace {
+
+int fail(mt_model* m, int code, const char* fmt, ...)
+{
+    if (m) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        m->err = buf;
+    }
+    return code;
+}
+
+struct Bump {
+    size_t off = 0;
+    size_t take(size_t bytes)
+    {
+        size_t at = off;
+        off = align_up(off + bytes);
+        return at;
+    }
+};
+
+LayerW layout_layer(Bump& b, size_t H, size_t F, size_t esz)
+{
+    LayerW L;
+    L.Wqkv = b.take(3 * H * H * esz);
+    L.bqkv = b.take(3 * H * 4);
+    L.Wo = b.take(H * H * esz);
+    L.bo = b.take(H * 4);
+    L.ln1g = b.take(H * 4);
+    L.ln1b = b.take(H * 4);
+    L.W1 = b.take(F * H * esz);
+    L.b1 = b.take(F * 4);
+    L.W2 = b.take(H * F * esz);
+    L.b2 = b.take(H * 4);
+    L.ln2g = b.take(H * 4);
+    L.ln2b = b.take(H * 4);
+    return L;
+}
+
+Scratch layout_scratch(Bump& b, size_t M, size_t H, size_t F, size_t esz, bool bf16)
+{
+    Scratch s;
+    s.qkv = b.take(M * 3 * H * esz);
+    s.ctx = b.take(M * H * esz);
+    s.y = b.take(M * H * 4);
+    s.x1f = b.take(M * H * 4);
+    s.x1b = bf16 ? b.take(M * H * 2) : 0;
+    s.u = b.take(M * F * esz);
+    return s;
+}
+
+inline uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Copy n float32 values into the staging image as matrix elements (bf16 or fp32).
+void put_matrix(unsigned char* dst, const float* src, size_t n, bool bf16)
+{
+    if (!bf16) {
+        memcpy(dst, src, n * 4);
+        return;
+    }
+    uint16_t* d = reinterpret_cast<uint16_t*>(dst);
+    const size_t nthreads = n > (1u << 22) ? std::min<size_t>(8, std::max(1u, std::thread::hardware_concurrency())) : 1;
+    if (nthreads <= 1) {
+        for (size_t i = 0; i < n; ++i) d[i] = f32_to_bf16_rne(src[i]);
+        return;
+    }
+    std::vector<std::thread> th;
+    const size_t per = (n + nthreads - 1) / nthreads;
+    for (size_t t = 0; t < nthreads; ++t) {
+        const size_t lo = t * per, hi = std::min(n, lo + per);
+        if (lo >= hi) break;
+        th.emplace_back([=] { for (size_t i = lo; i < hi; ++i) d[i] = f32_to_bf16_rne(src[i]); });
+    }
+    for (auto& t : th) t.join();
+}
+
+// Convert one encoder layer from the blob order into the arena image; returns floats consumed.
+size_t stage_layer(const mt_model* m, const LayerW& L, const float* p, unsigned char* img, size_t img_base)
+{
+    const size_t H = m->cfg.hidden, F = m->cfg.ffn;
+    const float* p0 = p;
+    auto at = [&](size_t off) { return img + (off - img_base); };
+    for (int i = 0; i < 3; ++i) {   // Wq bq Wk bk Wv bv -> one [3H,H] matrix and one [3H] bias
+        put_matrix(at(L.Wqkv) + (size_t)i * H * H * m->esz, p, H * H, m->bf16);
+        p += H * H;
+        memcpy(at(L.bqkv) + (size_t)i * H * 4, p, H * 4);
+        p += H;
+    }
+    put_matrix(at(L.Wo), p, H * H, m->bf16); p += H * H;
+    memcpy(at(L.bo), p, H * 4); p += H;
+    memcpy(at(L.ln1g), p, H * 4); p += H;
+    memcpy(at(L.ln1b), p, H * 4); p += H;
+    put_matrix(at(L.W1), p, F * H, m->bf16); p += F * H;
+    memcpy(at(L.b1), p, F * 4); p += F;
+    put_matrix(at(L.W2), p, H * F, m->bf16); p += H * F;
+    memcpy(at(L.b2), p, H * 4); p += H;
+    memcpy(at(L.ln2g), p, H * 4); p += H;
+    memcpy(at(L.ln2b), p, H * 4); p += H;
+    return (size_t)(p - p0);
+}
+
+size_t layer_floats(size_t H, size_t F) { return 4 * (H * H + H) + 2 * H + (F * H + F) + (H * F + H) + 2 * H; }
+
+struct Launcher {
+    mt_model* m;
+    hipStream_t st;
+    hipError_t first_err = hipSuccess;
+
+    void begin(int klass)
+    {
+        if (!m->profiling || first_err != hipSuccess) return;
+        ProfRec r;
+        r.klass = klass;
+        for (hipEvent_t* e : {&r.t0, &r.t1}) {
+            if (m->event_pool.empty()) {
+                if (hipEventCreate(e) != hipSuccess) { first_err = hipErrorOutOfMemory; return; }
+            } else {
+                *e = m->event_pool.back();
+                m->event_pool.pop_back();
+            }
+        }
+        (void)hipEventRecord(r.t0, st);
+        m->prof.push_back(r);
+    }
+    void end()
+    {
+        if (!m->profiling || first_err != hipSuccess || m->prof.empty()) return;
+        (void)hipEventRecord(m->prof.back().t1, st);
+    }
+    void check(hipError_t e)
+    {
+        if (first_err == hipSuccess && e != hipSuccess) first_err = e;
+    }
+
+    void gemm(int klass, const GemmGroup& g, GemmShape s, bool force_f32_kernel)
+    {
+        begin(klass);
+        if (m->bf16 && !force_f32_kernel) check(launch_gemm_bf16(g, s, st));
+        else check(launch_gemm_f32(g, s, m->bf16 ? 1 : 0, st));
+        end();
+    }
+};
+
+// One encoder layer for n same-shaped problems (n <= kMaxGroup).
+struct LayerIO {
+    const float* in_f;
+    const void* in_b;      // bf16 copy of the input (bf16 mode)
+    const LayerW* w;
+    const Scratch* scr;
+    float* out_f;
+    void* out_b;
+};
+
+void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const int32_t* d_mask, int B, int S)
+{
+    mt_model* m = L.m;
+    const int H = m->cfg.hidden, F = m->cfg.ffn, A = m->cfg.heads, M = B * S;
+    const int n = (int)io.size();
+    unsigned char* W = m->d_w;
+    unsigned char* ws = m->d_ws;
+    const bool bf = m->bf16;
+    const int gelu_act = m->cfg.gelu == MT_GELU_TANH ? ACT_GELU_TANH : ACT_GELU_ERF;
+
+    GemmGroup g;
+    memset(&g, 0, sizeof g);
+    GemmShape s;
+
+    // QKV projection: [M,H] x [3H,H]^T + b -> [M,3H]
+    for (int i = 0; i < n; ++i) {
+        g.A[i] = bf ? io[i].in_b : (const void*)io[i].in_f;
+        g.W[i] = W + io[i].w->Wqkv;
+        g.bias[i] = (const float*)(W + io[i].w->bqkv);
+        g.residual[i] = nullptr;
+        g.C[i] = ws + io[i].scr->qkv;
+        g.N[i] = 3 * H;
+    }
+    s = GemmShape{n, M, 3 * H, H, H, 3 * H, 0, ACT_NONE, bf ? 0 : 1};
+    L.gemm(MT_K_GEMM_QKV, g, s, false);
+
+    // attention
+    AttnGroup ag;
+    memset(&ag, 0, sizeof ag);
+    for (int i = 0; i < n; ++i) {
+        ag.qkv[i] = ws + io[i].scr->qkv;
+        ag.ctx[i] = ws + io[i].scr->ctx;
+    }
+    L.begin(MT_K_ATTN);
+    L.check(bf ? launch_attention_bf16(ag, n, d_mask, B, S, H, A, L.st) : launch_attention_f32(ag, n, d_mask, B, S, H, A, L.st));
+    L.end();
+
+    // output projection + bias + residual -> y (fp32), then LayerNorm -> x1
+    for (int i = 0; i < n; ++i) {
+        g.A[i] = ws + io[i].scr->ctx;
+        g.W[i] = W + io[i].w->Wo;
+        g.bias[i] = (const float*)(W + io[i].w->bo);
+        g.residual[i] = io[i].in_f;
+        g.C[i] = ws + io[i].scr->y;
+        g.N[i] = H;
+    }
+    s = GemmShape{n, M, H, H, H, H, H, ACT_NONE, 1};
+    L.gemm(MT_K_GEMM_OUT, g, s, false);
+
+    LnGroup lg;
+    memset(&lg, 0, sizeof lg);
+    for (int i = 0; i < n; ++i) {
+        lg.x[i] = (const float*)(ws + io[i].scr->y);
+        lg.gamma[i] = (const float*)(W + io[i].w->ln1g);
+        lg.beta[i] = (const float*)(W + io[i].w->ln1b);
+        lg.out_f32[i] = (float*)(ws + io[i].scr->x1f);
+        lg.out_bf16[i] = bf ? (bf16_t*)(ws + io[i].scr->x1b) : nullptr;
+    }
+    L.begin(MT_K_LN);
+    L.check(launch_layernorm(lg, n, M, H, m->cfg.ln_eps, L.st));
+    L.end();
+
+    // FFN1 + bias + GELU -> u
+    for (int i = 0; i < n; ++i) {
+        g.A[i] = bf ? (const void*)(ws + io[i].scr->x1b) : (const void*)(ws + io[i].scr->x1f);
+        g.W[i] = W + io[i].w->W1;
+        g.bias[i] = (const float*)(W + io[i].w->b1);
+        g.residual[i] = nullptr;
+        g.C[i] = ws + io[i].scr->u;
+        g.N[i] = F;
+    }
+    s = GemmShape{n, M, F, H, H, F, 0, gelu_act, bf ? 0 : 1};
+    L.gemm(MT_K_GEMM_FFN1, g, s, false);
+
+    // FFN2 + bias + residual -> y, then LayerNorm -> layer output
+    for (int i = 0; i < n; ++i) {
+        g.A[i] = ws + io[i].scr->u;
+        g.W[i] = W + io[i].w->W2;
+        g.bias[i] = (const float*)(W + io[i].w->b2);
+        g.residual[i] = (const float*)(ws + io[i].scr->x1f);
+        g.C[i] = ws + io[i].scr->y;
+        g.N[i] = H;
+    }
+    s = GemmShape{n, M, H, F, F, H, H, ACT_NONE, 1};
+    L.gemm(MT_K_GEMM_FFN2, g, s, false);
+
+    for (int i = 0; i < n; ++i) {
+        lg.x[i] = (const float*)(ws + io[i].scr->y);
+        lg.gamma[i] = (const float*)(W + io[i].w->ln2g);
+        lg.beta[i] = (const float*)(W + io[i].w->ln2b);
+        lg.out_f32[i] = io[i].out_f;
+        lg.out_bf16[i] = bf ? (bf16_t*)io[i].out_b : nullptr;
+    }
+    L.begin(MT_K_LN);
+    L.check(launch_layernorm(lg, n, M, H, m->cfg.ln_eps, L.st));
+    L.end();
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mt_error_name(int code)
+{
+    switch (code) {
+        case MT_OK: return "MT_OK";
+        case MT_ERR_NULL: return "MT_ERR_NULL";
+        case MT_ERR_CONFIG: return "MT_ERR_CONFIG";
+        case MT_ERR_SHAPE: return "MT_ERR_SHAPE";
+        case MT_ERR_STATE: return "MT_ERR_STATE";
+        case MT_ERR_BLOB: return "MT_ERR_BLOB";
+        case MT_ERR_HIP: return "MT_ERR_HIP";
+        default: return "MT_ERR_UNKNOWN";
+    }
+}
+
+int mt_create(const mt_config* cfg, mt_model** out)
+{
+    if (!cfg || !out) return MT_ERR_NULL;
+    *out = nullptr;
+    if (cfg->struct_size != sizeof(mt_config) || cfg->version != MT_ABI_VERSION) return MT_ERR_CONFIG;
+    if (cfg->n_tasks < 1 || !cfg->tasks) return cfg->tasks ? MT_ERR_CONFIG : MT_ERR_NULL;
+    if (cfg->vocab < 1 || cfg->hidden < 1 || cfg->heads < 1 || cfg->ffn < 1 || cfg->max_pos < 1 || cfg->type_vocab < 1 ||
+        cfg->n_trunk_layers < 0 || cfg->max_batch < 1 || cfg->max_seq < 1)
+        return MT_ERR_CONFIG;
+    if (cfg->hidden % cfg->heads != 0 || cfg->max_seq > cfg->max_pos) return MT_ERR_CONFIG;
+    if (cfg->precision != MT_BF16 && cfg->precision != MT_FP32_CHECK) return MT_ERR_CONFIG;
+    if (cfg->gelu != MT_GELU_ERF && cfg->gelu != MT_GELU_TANH) return MT_ERR_CONFIG;
+    if (!(cfg->ln_eps >= 0.0f)) return MT_ERR_CONFIG;
+    if (cfg->precision == MT_BF16 &&
+        (cfg->hidden != cfg->heads * 64 || cfg->hidden % 64 != 0 || cfg->ffn % 64 != 0 || cfg->max_seq > 1024))
+        return MT_ERR_CONFIG;
+    if (cfg->precision == MT_FP32_CHECK && cfg->max_seq > 4096) return MT_ERR_CONFIG;
+    int deepest = 0;
+    for (int t = 0; t < cfg->n_tasks; ++t) {
+        const mt_task_desc& d = cfg->tasks[t];
+        if (d.fork_layer < 0 || d.fork_layer > cfg->n_trunk_layers || d.n_layers < 0 || d.n_classes < 1) return MT_ERR_CONFIG;
+        deepest = std::max(deepest, d.fork_layer);
+    }
+    if (deepest != cfg->n_trunk_layers) return MT_ERR_CONFIG;   // the trunk is exactly as deep as the deepest fork
+
+    mt_model* m = new (std::nothrow) mt_model();
+    if (!m) return MT_ERR_CONFIG;
+    m->cfg = *cfg;
+    m->tasks.assign(cfg->tasks, cfg->tasks + cfg->n_tasks);
+    m->cfg.tasks = m->tasks.data();
+    m->bf16 = cfg->precision == MT_BF16;
+    m->esz = m->bf16 ? 2 : 4;
+    const size_t H = cfg->hidden, F = cfg->ffn, T = cfg->n_tasks, D = cfg->n_trunk_layers;
+    for (const auto& d : m->tasks) {
+        m->logit_off.push_back(m->C_tot);
+        m->C_tot += d.n_classes;
+    }
+
+    // ---- weight arena: trunk region, then one private region per task
+    Bump wb;
+    m->w_word = wb.take((size_t)cfg->vocab * H * m->esz);
+    m->w_pos = wb.take((size_t)cfg->max_pos * H * m->esz);
+    m->w_type = wb.take((size_t)cfg->type_vocab * H * m->esz);
+    m->w_embg = wb.take(H * 4);
+    m->w_embb = wb.take(H * 4);
+    for (size_t l = 0; l < D; ++l) m->trunk.push_back(layout_layer(wb, H, F, m->esz));
+    m->w_trunk_end = wb.off;
+    m->taskw.resize(T);
+    for (size_t t = 0; t < T; ++t) {
+        TaskW& tw = m->taskw[t];
+        tw.begin = wb.off;
+        for (int l = 0; l < m->tasks[t].n_layers; ++l) tw.layers.push_back(layout_layer(wb, H, F, m->esz));
+        tw.Wp = wb.take(H * H * m->esz);
+        tw.bp = wb.take(H * 4);
+        tw.Wc = wb.take((size_t)m->tasks[t].n_classes * H * m->esz);
+        tw.bc = wb.take((size_t)m->tasks[t].n_classes * 4);
+        tw.end = wb.off;
+    }
+    m->weight_bytes = wb.off;
+
+    // ---- workspace
+    m->Mmax = (size_t)cfg->max_batch * cfg->max_seq;
+    const size_t M = m->Mmax;
+    Bump sb;
+    m->tap_of_layer.assign(D + 1, -1);
+    for (const auto& d : m->tasks) {
+        if (m->tap_of_layer[d.fork_layer] < 0) {
+            m->tap_of_layer[d.fork_layer] = (int)m->tap_f.size();
+            m->tap_f.push_back(sb.take(M * H * 4));
+            m->tap_b.push_back(m->bf16 ? sb.take(M * H * 2) : 0);
+        }
+    }
+    for (int i = 0; i < 2; ++i) {
+        m->pp_f[i] = sb.take(M * H * 4);
+        m->pp_b[i] = m->bf16 ? sb.take(M * H * 2) : 0;
+    }
+    m->trunk_scr = layout_scratch(sb, M, H, F, m->esz, m->bf16);
+    for (size_t t = 0; t < T; ++t) {
+        if (m->tasks[t].n_layers > 0) {
+            m->task_scr.push_back(layout_scratch(sb, M, H, F, m->esz, m->bf16));
+            m->task_xf.push_back(sb.take(M * H * 4));
+            m->task_xb.push_back(m->bf16 ? sb.take(M * H * 2) : 0);
+        } else {
+            m->task_scr.push_back(Scratch{});
+            m->task_xf.push_back(0);
+            m->task_xb.push_back(0);
+        }
+    }
+    m->pooled = sb.take(T * (size_t)cfg->max_batch * H * 4);
+    m->workspace_bytes = sb.off;
+    m->task_loaded.assign(T, 0);
+    m->last_enabled.assign(T, 0);
+    *out = m;
+    return MT_OK;
+}
+
+void mt_destroy(mt_model* m)
+{
+    if (!m) return;
+    for (auto& r : m->prof) {
+        (void)hipEventDestroy(r.t0);
+        (void)hipEventDestroy(r.t1);
+    }
+    for (auto e : m->event_pool) (void)hipEventDestroy(e);
+    delete m;
+}
+
+size_t mt_weight_bytes(const mt_model* m) { return m ? m->weight_bytes : 0; }
+size_t mt_workspace_bytes(const mt_model* m) { return m ? m->workspace_bytes : 0; }
+int mt_logit_offset(const mt_model* m, int32_t task)
+{
+    if (!m) return MT_ERR_NULL;
+    if (task < 0 || task >= (int)m->tasks.size()) return MT_ERR_SHAPE;
+    return m->logit_off[task];
+}
+int mt_n_logits(const mt_model* m) { return m ? m->C_tot : MT_ERR_NULL; }
+int mt_layer_count(const mt_model* m)
+{
+    if (!m) return MT_ERR_NULL;
+    int n = m->cfg.n_trunk_layers;
+    for (const auto& d : m->tasks) n += d.n_layers;
+    return n;
+}
+const char* mt_last_error(const mt_model* m) { return m ? m->err.c_str() : "null model"; }
+
+int mt_bind(mt_model* m, void* d_weights, size_t weight_bytes, void* d_workspace, size_t workspace_bytes)
+{
+    if (!m) return MT_ERR_NULL;
+    if (!d_weights || !d_workspace) return fail(m, MT_ERR_NULL, "mt_bind: null arena");
+    if (weight_bytes < m->weight_bytes || workspace_bytes < m->workspace_bytes)
+        return fail(m, MT_ERR_SHAPE, "mt_bind: arenas too small (need %zu weight bytes, %zu workspace bytes)", m->weight_bytes,
+                    m->workspace_bytes);
+    if (((uintptr_t)d_weights | (uintptr_t)d_workspace) % kAlign)
+        return fail(m, MT_ERR_SHAPE, "mt_bind: arenas must be %zu-byte aligned", kAlign);
+    m->d_w = static_cast<unsigned char*>(d_weights);
+    m->d_ws = static_cast<unsigned char*>(d_workspace);
+    m->trunk_loaded = false;
+    std::fill(m->task_loaded.begin(), m->task_loaded.end(), 0);
+    return MT_OK;
+}
+
+int mt_load_weights(mt_model* m, int32_t scope, const void* h_blob, size_t nbytes, void* hip_stream)
+{
+    if (!m) return MT_ERR_NULL;
+    if (!h_blob) return fail(m, MT_ERR_NULL, "mt_load_weights: null blob");
+    if (!m->d_w) return fail(m, MT_ERR_STATE, "mt_load_weights: call mt_bind first");
+    const int T = (int)m->tasks.size();
+    if (scope < -1 || scope >= T) return fail(m, MT_ERR_BLOB, "mt_load_weights: scope %d out of range", scope);
+    if (nbytes < 16) return fail(m, MT_ERR_BLOB, "mt_load_weights: blob shorter than its header");
+    const unsigned char* hb = static_cast<const unsigned char*>(h_blob);
+    int32_t hdr[3];
+    memcpy(hdr, hb + 4, 12);
+    if (memcmp(hb, "MTW1", 4) != 0) return fail(m, MT_ERR_BLOB, "mt_load_weights: bad magic");
+    if (hdr[0] != scope) return fail(m, MT_ERR_BLOB, "mt_load_weights: blob is for scope %d, not %d", hdr[0], scope);
+    const size_t H = m->cfg.hidden, F = m->cfg.ffn;
+    const size_t lf = layer_floats(H, F);
+    size_t want_floats, want_tensors;
+    if (scope < 0) {
+        want_floats = ((size_t)m->cfg.vocab + m->cfg.max_pos + m->cfg.type_vocab) * H + 2 * H + (size_t)m->cfg.n_trunk_layers * lf;
+        want_tensors = 5 + 16 * (size_t)m->cfg.n_trunk_layers;
+    } else {
+        const mt_task_desc& d = m->tasks[scope];
+        want_floats = (size_t)d.n_layers * lf + H * H + H + (size_t)d.n_classes * H + d.n_classes;
+        want_tensors = 16 * (size_t)d.n_layers + 4;
+    }
+    if ((size_t)hdr[1] != want_tensors) return fail(m, MT_ERR_BLOB, "mt_load_weights: %d tensors, expected %zu", hdr[1], want_tensors);
+    if (nbytes != 16 + want_floats * 4)
+        return fail(m, MT_ERR_BLOB, "mt_load_weights: %zu bytes, expected %zu", nbytes, 16 + want_floats * 4);
+
+    // the blob's float data may be unaligned in principle; copy through memcpy-safe access by aligning once
+    std::vector<float> aligned;
+    const float* p = reinterpret_cast<const float*>(hb + 16);
+    if ((uintptr_t)p % 4) {
+        aligned.resize(want_floats);
+        memcpy(aligned.data(), hb + 16, want_floats * 4);
+        p = aligned.data();
+    }
+
+    const size_t begin = scope < 0 ? 0 : m->taskw[scope].begin;
+    const size_t end = scope < 0 ? m->w_trunk_end : m->taskw[scope].end;
+    void* img_v = nullptr;
+    if (hipHostMalloc(&img_v, end - begin, hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(m, MT_ERR_HIP, "mt_load_weights: cannot allocate %zu bytes of pinned staging", end - begin);
+    }
+    unsigned char* img = static_cast<unsigned char*>(img_v);
+    memset(img, 0, end - begin);
+    auto at = [&](size_t off) { return img + (off - begin); };
+    if (scope < 0) {
+        put_matrix(at(m->w_word), p, (size_t)m->cfg.vocab * H, m->bf16); p += (size_t)m->cfg.vocab * H;
+        put_matrix(at(m->w_pos), p, (size_t)m->cfg.max_pos * H, m->bf16); p += (size_t)m->cfg.max_pos * H;
+        put_matrix(at(m->w_type), p, (size_t)m->cfg.type_vocab * H, m->bf16); p += (size_t)m->cfg.type_vocab * H;
+        memcpy(at(m->w_embg), p, H * 4); p += H;
+        memcpy(at(m->w_embb), p, H * 4); p += H;
+        for (const LayerW& L : m->trunk) p += stage_layer(m, L, p, img, begin);
+    } else {
+        const TaskW& tw = m->taskw[scope];
+        const size_t C = m->tasks[scope].n_classes;
+        for (const LayerW& L : tw.layers) p += stage_layer(m, L, p, img, begin);
+        put_matrix(at(tw.Wp), p, H * H, m->bf16); p += H * H;
+        memcpy(at(tw.bp), p, H * 4); p += H;
+        put_matrix(at(tw.Wc), p, C * H, m->bf16); p += C * H;
+        memcpy(at(tw.bc), p, C * 4); p += C;
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = hipMemcpyAsync(m->d_w + begin, img, end - begin, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipHostFree(img);
+    if (e != hipSuccess) return fail(m, MT_ERR_HIP, "mt_load_weights: copy failed: %s", hipGetErrorString(e));
+    if (scope < 0) m->trunk_loaded = true;
+    else m->task_loaded[scope] = 1;
+    return MT_OK;
+}
+
+int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_mask, int32_t batch, int32_t seq,
+               const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream)
+{
+    if (!m) return MT_ERR_NULL;
+    if (!d_input_ids || !d_attn_mask || !d_out_logits) return fail(m, MT_ERR_NULL, "mt_forward: null device pointer");
+    if (!m->d_w || !m->d_ws) return fail(m, MT_ERR_STATE, "mt_forward: call mt_bind first");
+    if (batch < 1 || seq < 1 || batch > m->cfg.max_batch || seq > m->cfg.max_seq)
+        return fail(m, MT_ERR_SHAPE, "mt_forward: batch %d x seq %d outside 1..%d x 1..%d", batch, seq, m->cfg.max_batch, m->cfg.max_seq);
+    const int T = (int)m->tasks.size();
+    std::vector<int> enabled;
+    int depth = 0, max_y = 0;
+    for (int t = 0; t < T; ++t) {
+        if (h_task_mask && !h_task_mask[t]) continue;
+        if (!m->task_loaded[t]) return fail(m, MT_ERR_STATE, "mt_forward: task %d has no weights loaded", t);
+        enabled.push_back(t);
+        depth = std::max(depth, m->tasks[t].fork_layer);
+        max_y = std::max(max_y, m->tasks[t].n_layers);
+    }
+    if (!m->trunk_loaded) return fail(m, MT_ERR_STATE, "mt_forward: trunk has no weights loaded");
+    std::fill(m->last_enabled.begin(), m->last_enabled.end(), 0);
+    m->last_B = batch;
+    m->last_S = seq;
+    if (enabled.empty()) return MT_OK;
+
+    const int B = batch, S = seq, H = m->cfg.hidden;
+    unsigned char* W = m->d_w;
+    unsigned char* ws = m->d_ws;
+    const bool bf = m->bf16;
+    Launcher L{m, static_cast<hipStream_t>(hip_stream)};
+
+    // ---- embeddings -> X^(0)
+    auto trunk_out = [&](int layer, int pp, float*& of, void*& ob) {
+        const int tap = m->tap_of_layer[layer];
+        if (tap >= 0) {
+            of = (float*)(ws + m->tap_f[tap]);
+            ob = bf ? (void*)(ws + m->tap_b[tap]) : nullptr;
+        } else {
+            of = (float*)(ws + m->pp_f[pp]);
+            ob = bf ? (void*)(ws + m->pp_b[pp]) : nullptr;
+        }
+    };
+    float* cur_f;
+    void* cur_b;
+    trunk_out(0, 0, cur_f, cur_b);
+    L.begin(MT_K_EMBED);
+    L.check(launch_embed_ln(d_input_ids, B, S, H, m->cfg.vocab, W + m->w_word, W + m->w_pos, W + m->w_type, bf ? 1 : 0,
+                            (const float*)(W + m->w_embg), (const float*)(W + m->w_embb), m->cfg.ln_eps, cur_f,
+                            (bf16_t*)cur_b, L.st));
+    L.end();
+
+    // ---- trunk, once, up to the deepest enabled fork
+    std::vector<LayerIO> io(1);
+    for (int l = 0; l < depth; ++l) {
+        float* nf;
+        void* nb;
+        trunk_out(l + 1, (l + 1) & 1, nf, nb);
+        io[0] = LayerIO{cur_f, cur_b, &m->trunk[l], &m->trunk_scr, nf, nb};
+        run_layer_group(L, io, d_attn_mask, B, S);
+        cur_f = nf;
+        cur_b = nb;
+    }
+
+    // ---- branches in lock step, one grouped launch sequence per stage
+    for (int stage = 0; stage < max_y; ++stage) {
+        std::vector<LayerIO> all;
+        for (int t : enabled) {
+            const mt_task_desc& d = m->tasks[t];
+            if (d.n_layers <= stage) continue;
+            LayerIO x;
+            if (stage == 0) {
+                const int tap = m->tap_of_layer[d.fork_layer];
+                x.in_f = (const float*)(ws + m->tap_f[tap]);
+                x.in_b = bf ? (const void*)(ws + m->tap_b[tap]) : nullptr;
+            } else {
+                x.in_f = (const float*)(ws + m->task_xf[t]);
+                x.in_b = bf ? (const void*)(ws + m->task_xb[t]) : nullptr;
+            }
+            x.w = &m->taskw[t].layers[stage];
+            x.scr = &m->task_scr[t];
+            x.out_f = (float*)(ws + m->task_xf[t]);
+            x.out_b = bf ? (void*)(ws + m->task_xb[t]) : nullptr;
+            all.push_back(x);
+        }
+        for (size_t lo = 0; lo < all.size(); lo += kMaxGroup) {
+            std::vector<LayerIO> part(all.begin() + lo, all.begin() + std::min(all.size(), lo + (size_t)kMaxGroup));
+            run_layer_group(L, part, d_attn_mask, B, S);
+        }
+    }
+
+    // ---- poolers and classifiers (float32 inputs in both modes)
+    for (size_t lo = 0; lo < enabled.size(); lo += kMaxGroup) {
+        const int n = (int)std::min(enabled.size() - lo, (size_t)kMaxGroup);
+        GemmGroup g;
+        memset(&g, 0, sizeof g);
+        int maxC = 0;
+        for (int i = 0; i < n; ++i) {
+            const int t = enabled[lo + i];
+            const mt_task_desc& d = m->tasks[t];
+            const float* z = d.n_layers > 0 ? (const float*)(ws + m->task_xf[t])
+                                            : (const float*)(ws + m->tap_f[m->tap_of_layer[d.fork_layer]]);
+            g.A[i] = z;   // row b of the problem is token 0 of sequence b: lda = S*H
+            g.W[i] = W + m->taskw[t].Wp;
+            g.bias[i] = (const float*)(W + m->taskw[t].bp);
+            g.C[i] = ws + m->pooled + (size_t)t * m->cfg.max_batch * H * 4;
+            g.N[i] = H;
+        }
+        GemmShape s{n, B, H, H, (int64_t)S * H, H, 0, ACT_TANH, 1};
+        L.gemm(MT_K_POOL, g, s, true);
+        for (int i = 0; i < n; ++i) {
+            const int t = enabled[lo + i];
+            g.A[i] = g.C[i];
+            g.W[i] = W + m->taskw[t].Wc;
+            g.bias[i] = (const float*)(W + m->taskw[t].bc);
+            g.C[i] = d_out_logits + m->logit_off[t];
+            g.N[i] = m->tasks[t].n_classes;
+            maxC = std::max(maxC, m->tasks[t].n_classes);
+        }
+        GemmShape c{n, B, maxC, H, H, m->C_tot, 0, ACT_NONE, 1};
+        L.gemm(MT_K_POOL, g, c, true);
+    }
+
+    if (L.first_err != hipSuccess) return fail(m, MT_ERR_HIP, "mt_forward: launch failed: %s", hipGetErrorString(L.first_err));
+    for (int t : enabled) m->last_enabled[t] = 1;
+    return MT_OK;
+}
+
+int mt_read_hidden(mt_model* m, int32_t task, int32_t layer, float* d_out, size_t out_bytes, void* hip_stream)
+{
+    if (!m) return MT_ERR_NULL;
+    if (!d_out) return fail(m, MT_ERR_NULL, "mt_read_hidden: null output");
+    if (!m->d_ws || m->last_B == 0) return fail(m, MT_ERR_STATE, "mt_read_hidden: no forward pass has run");
+    const size_t bytes = (size_t)m->last_B * m->last_S * m->cfg.hidden * 4;
+    if (out_bytes < bytes) return fail(m, MT_ERR_SHAPE, "mt_read_hidden: need %zu bytes", bytes);
+    const unsigned char* src;
+    if (task < 0) {
+        if (layer < 0 || layer > m->cfg.n_trunk_layers || m->tap_of_layer[layer] < 0)
+            return fail(m, MT_ERR_SHAPE, "mt_read_hidden: no task forks at trunk layer %d", layer);
+        src = m->d_ws + m->tap_f[m->tap_of_layer[layer]];
+    } else {
+        if (task >= (int)m->tasks.size()) return fail(m, MT_ERR_SHAPE, "mt_read_hidden: task %d out of range", task);
+        if (!m->last_enabled[task]) return fail(m, MT_ERR_STATE, "mt_read_hidden: task %d was not computed", task);
+        const mt_task_desc& d = m->tasks[task];
+        src = d.n_layers > 0 ? m->d_ws + m->task_xf[task] : m->d_ws + m->tap_f[m->tap_of_layer[d.fork_layer]];
+    }
+    hipError_t e = hipMemcpyAsync(d_out, src, bytes, hipMemcpyDeviceToDevice, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(m, MT_ERR_HIP, "mt_read_hidden: %s", hipGetErrorString(e));
+    return MT_OK;
+}
+
+int mt_profile_enable(mt_model* m, int32_t on)
+{
+    if (!m) return MT_ERR_NULL;
+    m->profiling = on != 0;
+    return MT_OK;
+}
+
+int mt_profile_read(mt_model* m, float* h_ms, int32_t* h_launches)
+{
+    if (!m) return MT_ERR_NULL;
+    if (!h_ms || !h_launches) return fail(m, MT_ERR_NULL, "mt_profile_read: null output");
+    for (int k = 0; k < MT_K_COUNT; ++k) {
+        h_ms[k] = 0.f;
+        h_launches[k] = 0;
+    }
+    int rc = MT_OK;
+    for (auto& r : m->prof) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(r.t1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.t0, r.t1);
+        if (e != hipSuccess) rc = fail(m, MT_ERR_HIP, "mt_profile_read: %s", hipGetErrorString(e));
+        else {
+            h_ms[r.klass] += ms;
+            h_launches[r.klass] += 1;
+        }
+        m->event_pool.push_back(r.t0);
+        m->event_pool.push_back(r.t1);
+    }
+    m->prof.clear();
+    return rc;
+}
+
+int mt_debug_set_gemm_tile(int32_t sel)
+{
+    const int prev = mt::g_gemm_bf16_tile_override;
+    mt::g_gemm_bf16_tile_override = (sel >= 0 && sel <= 6) ? sel : 0;
+    return prev;
+}
+
+int mt_op_linear(int32_t precision, const void* d_A, int64_t lda, const void* d_W, const float* d_bias,
+                 const float* d_residual, void* d_C, int64_t ldc, int32_t M, int32_t N, int32_t K, int32_t act_kind,
+                 int32_t out_f32, void* hip_stream)
+{
+    if (!d_A || !d_W || !d_C) return MT_ERR_NULL;
+    if (M < 1 || N < 1 || K < 1 || act_kind < 0 || act_kind > 3) return MT_ERR_SHAPE;
+    GemmGroup g;
+    memset(&g, 0, sizeof g);
+    g.A[0] = d_A;
+    g.W[0] = d_W;
+    g.C[0] = d_C;
+    g.bias[0] = d_bias;
+    g.residual[0] = d_residual;
+    g.N[0] = N;
+    GemmShape s{1, M, N, K, lda, ldc, ldc, act_kind, (precision == MT_BF16) ? (out_f32 ? 1 : 0) : 1};
+    hipError_t e = precision == MT_BF16 ? launch_gemm_bf16(g, s, static_cast<hipStream_t>(hip_stream))
+                                        : launch_gemm_f32(g, s, 0, static_cast<hipStream_t>(hip_stream));
+    if (e == hipErrorInvalidValue) return MT_ERR_SHAPE;
+    return e == hipSuccess ? MT_OK : MT_ERR_HIP;
+}
+
+int mt_op_attention(int32_t precision, const void* d_qkv, const int32_t* d_mask, void* d_ctx, int32_t batch, int32_t seq,
+                    int32_t hidden, int32_t heads, void* hip_stream)
+{
+    if (!d_qkv || !d_mask || !d_ctx) return MT_ERR_NULL;
+    if (batch < 1 || seq < 1 || heads < 1 || hidden % heads) return MT_ERR_SHAPE;
+    AttnGroup g;
+    memset(&g, 0, sizeof g);
+    g.qkv[0] = d_qkv;
+    g.ctx[0] = d_ctx;
+    hipError_t e = precision == MT_BF16
+                       ? launch_attention_bf16(g, 1, d_mask, batch, seq, hidden, heads, static_cast<hipStream_t>(hip_stream))
+                       : launch_attention_f32(g, 1, d_mask, batch, seq, hidden, heads, static_cast<hipStream_t>(hip_stream));
+    if (e == hipErrorInvalidValue) return MT_ERR_SHAPE;
+    return e == hipSuccess ? MT_OK : MT_ERR_HIP;
+}
+
+int mt_op_layernorm(const float* d_x, const float* d_gamma, const float* d_beta, float eps, float* d_out_f32, void* d_out_bf16,
+                    int32_t M, int32_t H, void* hip_stream)
+{
+    if (!d_x || !d_gamma || !d_beta) return MT_ERR_NULL;
+    if (M < 1 || H < 1) return MT_ERR_SHAPE;
+    LnGroup g;
+    memset(&g, 0, sizeof g);
+    g.x[0] = d_x;
+    g.gamma[0] = d_gamma;
+    g.beta[0] = d_beta;
+    g.out_f32[0] = d_out_f32;
+    g.out_bf16[0] = static_cast<bf16_t*>(d_out_bf16);
+    hipError_t e = launch_layernorm(g, 1, M, H, eps, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MT_OK : MT_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,204 @@
+// Row kernels: embedding sum + LayerNorm, and LayerNorm of a pre-summed row.
+// One 64-lane wavefront owns one row; statistics are float32 with a two-pass variance taken from
+// registers, reductions are wavefront shuffles.  Both kernels are HBM-bound: each row is read once
+// and written once (float32 and, for the matrix-core path, a bfloat16 copy).
+#include "kernels.h"
+#include "device_util.h"
+
+namespace mt {
+
+namespace {
+
+constexpr int kRowsPerBlock = 4;   // 4 wavefronts of 64 lanes
+
+template <typename T>
+__device__ inline float4 load4(const T* p);
+template <>
+__device__ inline float4 load4<float>(const float* p) { return *reinterpret_cast<const float4*>(p); }
+template <>
+__device__ inline float4 load4<__bf16>(const __bf16* p)
+{
+    bf16x4 v = *reinterpret_cast<const bf16x4*>(p);
+    return make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
+}
+
+// Normalise NV float4 per lane held in registers and store.
+template <int NV>
+__device__ inline void ln_finish_store(float4 (&v)[NV], int lane, int H, const float* gamma, const float* beta,
+                                       float eps, float* out_f32, __bf16* out_bf16)
+{
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    const float mean = wave_sum(s) / (float)H;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        float a = v[i].x - mean, b = v[i].y - mean, c = v[i].z - mean, d = v[i].w - mean;
+        q += (a * a + b * b) + (c * c + d * d);
+    }
+    const float inv = 1.0f / sqrtf(wave_sum(q) / (float)H + eps);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int col = (i * 64 + lane) * 4;
+        const float4 g = *reinterpret_cast<const float4*>(gamma + col);
+        const float4 b = *reinterpret_cast<const float4*>(beta + col);
+        float4 o;
+        o.x = g.x * ((v[i].x - mean) * inv) + b.x;
+        o.y = g.y * ((v[i].y - mean) * inv) + b.y;
+        o.z = g.z * ((v[i].z - mean) * inv) + b.z;
+        o.w = g.w * ((v[i].w - mean) * inv) + b.w;
+        if (out_f32) *reinterpret_cast<float4*>(out_f32 + col) = o;
+        if (out_bf16) {
+            bf16x4 p = {(__bf16)o.x, (__bf16)o.y, (__bf16)o.z, (__bf16)o.w};
+            *reinterpret_cast<bf16x4*>(out_bf16 + col) = p;
+        }
+    }
+}
+
+// H == NV*256: the whole row lives in registers.
+template <int NV>
+__global__ __launch_bounds__(256) void layernorm_fast(LnGroup g, int M, int H, float eps)
+{
+    const int grp = blockIdx.y;
+    const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= M) return;
+    const float* x = g.x[grp] + (size_t)row * H;
+    float4 v[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) v[i] = *reinterpret_cast<const float4*>(x + (i * 64 + lane) * 4);
+    float* of = g.out_f32[grp] ? g.out_f32[grp] + (size_t)row * H : nullptr;
+    __bf16* ob = g.out_bf16[grp] ? reinterpret_cast<__bf16*>(g.out_bf16[grp]) + (size_t)row * H : nullptr;
+    ln_finish_store<NV>(v, lane, H, g.gamma[grp], g.beta[grp], eps, of, ob);
+}
+
+// Any H: three strided passes over the row (it stays in cache between passes).
+__global__ __launch_bounds__(256) void layernorm_any(LnGroup g, int M, int H, float eps)
+{
+    const int grp = blockIdx.y;
+    const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= M) return;
+    const float* x = g.x[grp] + (size_t)row * H;
+    float s = 0.f;
+    for (int i = lane; i < H; i += 64) s += x[i];
+    const float mean = wave_sum(s) / (float)H;
+    float q = 0.f;
+    for (int i = lane; i < H; i += 64) { float d = x[i] - mean; q += d * d; }
+    const float inv = 1.0f / sqrtf(wave_sum(q) / (float)H + eps);
+    const float* gamma = g.gamma[grp];
+    const float* beta = g.beta[grp];
+    float* of = g.out_f32[grp] ? g.out_f32[grp] + (size_t)row * H : nullptr;
+    __bf16* ob = g.out_bf16[grp] ? reinterpret_cast<__bf16*>(g.out_bf16[grp]) + (size_t)row * H : nullptr;
+    for (int i = lane; i < H; i += 64) {
+        float o = gamma[i] * ((x[i] - mean) * inv) + beta[i];
+        if (of) of[i] = o;
+        if (ob) ob[i] = (__bf16)o;
+    }
+}
+
+template <typename TE, int NV>
+__global__ __launch_bounds__(256) void embed_ln_fast(const int32_t* ids, int M, int S, int H, int vocab,
+                                                     const TE* word, const TE* pos, const TE* type,
+                                                     const float* gamma, const float* beta, float eps,
+                                                     float* out_f32, __bf16* out_bf16)
+{
+    const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= M) return;
+    int id = ids[row];
+    id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+    const int s = row % S;
+    const TE* w = word + (size_t)id * H;
+    const TE* p = pos + (size_t)s * H;
+    float4 v[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int col = (i * 64 + lane) * 4;
+        float4 a = load4<TE>(w + col), b = load4<TE>(p + col), c = load4<TE>(type + col);
+        v[i] = make_float4((a.x + b.x) + c.x, (a.y + b.y) + c.y, (a.z + b.z) + c.z, (a.w + b.w) + c.w);
+    }
+    ln_finish_store<NV>(v, lane, H, gamma, beta, eps, out_f32 ? out_f32 + (size_t)row * H : nullptr,
+                        out_bf16 ? out_bf16 + (size_t)row * H : nullptr);
+}
+
+template <typename TE>
+__global__ __launch_bounds__(256) void embed_ln_any(const int32_t* ids, int M, int S, int H, int vocab,
+                                                    const TE* word, const TE* pos, const TE* type,
+                                                    const float* gamma, const float* beta, float eps,
+                                                    float* out_f32, __bf16* out_bf16)
+{
+    const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= M) return;
+    int id = ids[row];
+    id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+    const int sidx = row % S;
+    const TE* w = word + (size_t)id * H;
+    const TE* p = pos + (size_t)sidx * H;
+    float s = 0.f;
+    for (int i = lane; i < H; i += 64) s += ((float)w[i] + (float)p[i]) + (float)type[i];
+    const float mean = wave_sum(s) / (float)H;
+    float q = 0.f;
+    for (int i = lane; i < H; i += 64) {
+        float d = ((float)w[i] + (float)p[i]) + (float)type[i] - mean;
+        q += d * d;
+    }
+    const float inv = 1.0f / sqrtf(wave_sum(q) / (float)H + eps);
+    for (int i = lane; i < H; i += 64) {
+        float e = ((float)w[i] + (float)p[i]) + (float)type[i];
+        float o = gamma[i] * ((e - mean) * inv) + beta[i];
+        if (out_f32) out_f32[(size_t)row * H + i] = o;
+        if (out_bf16) out_bf16[(size_t)row * H + i] = (__bf16)o;
+    }
+}
+
+template <typename TE>
+hipError_t embed_dispatch(const int32_t* ids, int B, int S, int H, int vocab, const TE* word, const TE* pos,
+                          const TE* type, const float* gamma, const float* beta, float eps, float* of, __bf16* ob,
+                          hipStream_t st)
+{
+    const int M = B * S;
+    dim3 grid((M + kRowsPerBlock - 1) / kRowsPerBlock), block(256);
+    if (H == 768)
+        hipLaunchKernelGGL((embed_ln_fast<TE, 3>), grid, block, 0, st, ids, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+    else if (H == 1024)
+        hipLaunchKernelGGL((embed_ln_fast<TE, 4>), grid, block, 0, st, ids, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+    else if (H == 256)
+        hipLaunchKernelGGL((embed_ln_fast<TE, 1>), grid, block, 0, st, ids, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+    else if (H == 512)
+        hipLaunchKernelGGL((embed_ln_fast<TE, 2>), grid, block, 0, st, ids, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+    else
+        hipLaunchKernelGGL((embed_ln_any<TE>), grid, block, 0, st, ids, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_layernorm(const LnGroup& g, int G, int M, int H, float eps, hipStream_t stream)
+{
+    if (G <= 0 || M <= 0) return hipSuccess;
+    dim3 grid((M + kRowsPerBlock - 1) / kRowsPerBlock, G), block(256);
+    if (H == 768) hipLaunchKernelGGL((layernorm_fast<3>), grid, block, 0, stream, g, M, H, eps);
+    else if (H == 1024) hipLaunchKernelGGL((layernorm_fast<4>), grid, block, 0, stream, g, M, H, eps);
+    else if (H == 512) hipLaunchKernelGGL((layernorm_fast<2>), grid, block, 0, stream, g, M, H, eps);
+    else if (H == 256) hipLaunchKernelGGL((layernorm_fast<1>), grid, block, 0, stream, g, M, H, eps);
+    else hipLaunchKernelGGL(layernorm_any, grid, block, 0, stream, g, M, H, eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_embed_ln(const int32_t* ids, int B, int S, int H, int vocab, const void* word, const void* pos,
+                           const void* type, int emb_bf16, const float* gamma, const float* beta, float eps,
+                           float* out_f32, bf16_t* out_bf16, hipStream_t stream)
+{
+    if (B * S <= 0) return hipSuccess;
+    __bf16* ob = reinterpret_cast<__bf16*>(out_bf16);
+    if (emb_bf16)
+        return embed_dispatch<__bf16>(ids, B, S, H, vocab, (const __bf16*)word, (const __bf16*)pos, (const __bf16*)type,
+                                      gamma, beta, eps, out_f32, ob, stream);
+    return embed_dispatch<float>(ids, B, S, H, vocab, (const float*)word, (const float*)pos, (const float*)type,
+                                 gamma, beta, eps, out_f32, ob, stream);
+}
+
+}  // namespace mt

@@ -1,0 +1,366 @@
+"""Parity of the HIP library against the CPU oracle, through the C ABI, on a real MI355X.
+
+Tolerances.  float32 validation mode: per task max|g-o| <= 1e-4 * max(max|o|, 1e-3).  bf16 mode:
+max |delta logit| <= 2e-2; every (sequence, task) pair whose oracle top-2 margin exceeds 4e-2 must
+have the same argmax (a consequence of the 2e-2 bound); ties break to the lowest index on both sides.
+Single operations: float32 outputs of the bf16 GEMM carry only accumulation-order error (inputs are
+bf16-representable on both sides), bf16 outputs add one rounding of relative size 2^-8.
+"""
+import dataclasses
+import sys
+
+import numpy as np
+import pytest
+
+import mt_synth as ms
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import paper_2107_05377_amd as mt  # noqa: E402
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    mt.lib()    # fails loudly if the HIP library is missing
+
+
+def dev(x, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    return t if dtype is None else t.to(dtype)
+
+
+def bf16_grid(x):
+    return ms.round_to_bf16_grid(np.ascontiguousarray(x, dtype=np.float32).copy())
+
+
+MINI = ms.MTSpec("mini", vocab=50, hidden=32, heads=4, ffn=64, max_pos=24, n_trunk_layers=3,
+                 tasks=(ms.TaskSpec(1, 2, 2), ms.TaskSpec(3, 1, 3), ms.TaskSpec(2, 0, 1), ms.TaskSpec(0, 1, 2)),
+                 precision="fp32", batch=3, seq=12, len_lo=3, len_hi=12, input_seed=77, weights_seed=4242)
+
+# bf16-mode model small enough for the oracle to run whole batches: hetero forks, a task with no own
+# layer, a fork at the embeddings, ragged sequence length (not a multiple of 32), 3 row tiles.
+SMALL = ms.MTSpec("small", vocab=500, hidden=128, heads=2, ffn=256, max_pos=64, n_trunk_layers=3,
+                  tasks=(ms.TaskSpec(3, 2, 2), ms.TaskSpec(1, 1, 3), ms.TaskSpec(2, 0, 1), ms.TaskSpec(0, 1, 2),
+                         ms.TaskSpec(3, 2, 2)),
+                  precision="bf16", batch=7, seq=44, len_lo=5, len_hi=44, input_seed=5, weights_seed=99)
+
+
+# ------------------------------------------------------------------ single operations
+
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
+def test_gemm_bf16_vs_oracle(tile):
+    say(f"gemm_bf16 tile={tile}")
+    rng = np.random.default_rng(10 + tile)
+    M, N, K = 300, 392, 192            # several tiles in M and N with ragged tails in both
+    A = bf16_grid(rng.standard_normal((M, K)))
+    W = bf16_grid(rng.standard_normal((N, K)) * 0.1)
+    bias = rng.standard_normal(N).astype(np.float32)
+    res = rng.standard_normal((M, N)).astype(np.float32)
+    prev = mt.set_gemm_tile(tile)
+    try:
+        dA, dW, db, dr = dev(A, torch.bfloat16), dev(W, torch.bfloat16), dev(bias), dev(res)
+        ref = oracle.linear(A, W, bias)
+        out = mt.op_linear(mt.MT_BF16, dA, dW, db, out_f32=True).cpu().numpy()
+        assert np.abs(out - ref).max() <= 2e-4 * max(1.0, np.abs(ref).max())
+        out = mt.op_linear(mt.MT_BF16, dA, dW, db, residual=dr, out_f32=True).cpu().numpy()
+        assert np.abs(out - (ref.astype(np.float64) + res)).max() <= 2e-4 * max(1.0, np.abs(ref).max())
+        out = mt.op_linear(mt.MT_BF16, dA, dW, db, act=1).float().cpu().numpy()
+        g = oracle.gelu(ref)
+        assert np.abs(out - g).max() <= 2 ** -8 * np.abs(g).max() + 1e-3
+        out = mt.op_linear(mt.MT_BF16, dA, dW, None).float().cpu().numpy()
+        ref0 = oracle.linear(A, W, None)
+        assert np.abs(out - ref0).max() <= 2 ** -8 * np.abs(ref0).max() + 1e-3
+    finally:
+        mt.set_gemm_tile(prev)
+    torch.cuda.synchronize()
+
+
+def test_gemm_bf16_bert_shapes_sampled():
+    """BERT-base shapes in the default (shape-chosen) tile configuration, checked on sampled rows."""
+    rng = np.random.default_rng(3)
+    for (M, N, K) in ((4096, 2304, 768), (4096, 768, 3072), (4096, 3072, 768)):
+        say(f"gemm_bf16 {M}x{N}x{K}")
+        A = bf16_grid(rng.standard_normal((M, K)))
+        W = bf16_grid(rng.standard_normal((N, K)) * 0.02)
+        out = mt.op_linear(mt.MT_BF16, dev(A, torch.bfloat16), dev(W, torch.bfloat16), None, out_f32=True).cpu().numpy()
+        rows = np.concatenate([[0, 1, M - 1], rng.integers(0, M, 29)])
+        ref = oracle.linear(A[rows], W, None)
+        assert np.abs(out[rows] - ref).max() <= 2e-4 * np.abs(ref).max()
+
+
+def test_gemm_f32_vs_oracle():
+    rng = np.random.default_rng(4)
+    for (M, N, K) in ((70, 67, 33), (5, 3, 64), (130, 129, 100)):
+        A = rng.standard_normal((M, K)).astype(np.float32)
+        W = rng.standard_normal((N, K)).astype(np.float32)
+        b = rng.standard_normal(N).astype(np.float32)
+        r = rng.standard_normal((M, N)).astype(np.float32)
+        out = mt.op_linear(mt.MT_FP32_CHECK, dev(A), dev(W), dev(b), residual=dev(r), act=3).cpu().numpy()
+        ref = np.tanh(oracle.linear(A, W, b).astype(np.float64)) + r
+        assert np.abs(out - ref).max() <= 1e-5 * max(1.0, np.abs(ref).max())
+
+
+@pytest.mark.parametrize("B,S,heads", [(3, 128, 2), (2, 40, 1), (2, 200, 2), (1, 512, 1), (4, 64, 3)])
+def test_attention_bf16_vs_oracle(B, S, heads):
+    say(f"attention_bf16 B={B} S={S} heads={heads}")
+    rng = np.random.default_rng(S)
+    H = heads * 64
+    q = bf16_grid(rng.standard_normal((B, S, H)))
+    k = bf16_grid(rng.standard_normal((B, S, H)))
+    v = bf16_grid(rng.standard_normal((B, S, H)))
+    lengths = rng.integers(1, S + 1, B)
+    lengths[0] = S
+    mask = (np.arange(S)[None, :] < lengths[:, None]).astype(np.int32)
+    if B > 1 and lengths[1] > 3:
+        mask[1, 2] = 0          # a hole inside a sequence
+    qkv = np.concatenate([q, k, v], axis=2).reshape(B * S, 3 * H)
+    dqkv = dev(qkv, torch.bfloat16)
+    ctx = mt.op_attention(mt.MT_BF16, dqkv, dev(mask), B, S, H, heads).float().cpu().numpy().reshape(B, S, H)
+    ref = oracle.attention(q, k, v, mask, heads)
+    real = mask.astype(bool)
+    err = np.abs(ctx[real] - ref[real]).max()
+    say(f"  max err {err:.4g}")
+    assert err <= 2e-2
+
+
+def test_attention_f32_vs_oracle():
+    rng = np.random.default_rng(8)
+    for (B, S, H, A) in ((2, 16, 64, 2), (3, 21, 60, 3), (1, 130, 32, 1)):
+        q, k, v = (rng.standard_normal((B, S, H)).astype(np.float32) for _ in range(3))
+        lengths = rng.integers(1, S + 1, B)
+        mask = (np.arange(S)[None, :] < lengths[:, None]).astype(np.int32)
+        qkv = np.concatenate([q, k, v], axis=2).reshape(B * S, 3 * H)
+        ctx = mt.op_attention(mt.MT_FP32_CHECK, dev(qkv), dev(mask), B, S, H, A).cpu().numpy().reshape(B, S, H)
+        ref = oracle.attention(q, k, v, mask, A)
+        assert np.abs(ctx - ref).max() <= 2e-5
+
+
+@pytest.mark.parametrize("H", [768, 1024, 64, 100])
+def test_layernorm_vs_oracle(H):
+    rng = np.random.default_rng(H)
+    M = 37
+    x = (rng.standard_normal((M, H)) * 2 + 0.5).astype(np.float32)
+    g = (1 + 0.1 * rng.standard_normal(H)).astype(np.float32)
+    b = (0.1 * rng.standard_normal(H)).astype(np.float32)
+    of, ob = mt.op_layernorm(dev(x), dev(g), dev(b), 1e-12, want_bf16=True)
+    ref = oracle.layernorm(x, g, b, 1e-12)
+    assert np.abs(of.cpu().numpy() - ref).max() <= 1e-5
+    assert np.abs(ob.float().cpu().numpy() - ref).max() <= 2 ** -8 * np.abs(ref).max()
+
+
+# ------------------------------------------------------------------ whole model, float32 validation mode
+
+def _params(spec, stress, std=0.02):
+    tr, tri = ms.make_trunk_params(spec, stress=stress, std=std)
+    tps = [ms.make_task_params(spec, t, stress=stress, std=std) for t in range(spec.n_tasks)]
+    return tr, tri, tps
+
+
+def _load(spec, tr, tri, tps, **kw):
+    model = mt.Model(mt.make_config(spec, **kw))
+    model.load_params(-1, tr, len(tri))
+    for t, (tp, tpi) in enumerate(tps):
+        model.load_params(t, tp, len(tpi))
+    return model
+
+
+def rel_err_per_task(spec, got, ref):
+    out, col = [], 0
+    for t in spec.tasks:
+        g, o = got[:, col:col + t.n_classes], ref[:, col:col + t.n_classes]
+        out.append(np.abs(g - o).max() / max(np.abs(o).max(), 1e-3))
+        col += t.n_classes
+    return out
+
+
+@pytest.mark.parametrize("spec,stress,std", [(ms.get_config("tiny"), False, 0.02), (ms.get_config("tiny"), True, 0.02),
+                                             (MINI, True, 0.1)])
+def test_fp32_mode_matches_oracle(spec, stress, std):
+    say(f"fp32 mode {spec.name} stress={stress}")
+    tr, tri, tps = _params(spec, stress, std)
+    orc = oracle.Oracle(spec, tr, [p for p, _ in tps])
+    model = _load(spec, tr, tri, tps)
+    ids, mask, _ = ms.make_inputs(spec)
+    ref, hidden = orc.mt_forward(ids, mask, want_hidden=True)
+    got = model.forward(dev(ids), dev(mask)).cpu().numpy()
+    errs = rel_err_per_task(spec, got, ref)
+    say("  rel err per task", errs)
+    assert max(errs) <= 1e-4
+    assert np.all(np.abs(got - ref) <= 1e-4 * np.abs(ref) + 1e-6)
+    # the kept trunk states (taps) agree with the oracle's on real tokens
+    real = mask.astype(bool)
+    for layer in sorted({t.fork_layer for t in spec.tasks}):
+        h = model.read_hidden(-1, layer, *ids.shape).cpu().numpy()
+        assert np.abs(h[real] - hidden[layer][real]).max() <= 2e-5
+    model.close()
+
+
+def test_fp32_mode_base_shapes_one_sequence():
+    """float32 validation mode at BERT-base width (H=768, 12 heads, F=3072), shallow, 2 sequences."""
+    spec = dataclasses.replace(ms.get_config("base"), precision="fp32", n_trunk_layers=1,
+                               tasks=(ms.TaskSpec(1, 1, 2), ms.TaskSpec(1, 0, 3)), batch=2, seq=24, len_lo=5, len_hi=24,
+                               vocab=2000)
+    tr, tri, tps = _params(spec, True)
+    ids, mask, _ = ms.make_inputs(spec)
+    ref = oracle.Oracle(spec, tr, [p for p, _ in tps]).mt_forward(ids, mask)
+    model = _load(spec, tr, tri, tps)
+    got = model.forward(dev(ids), dev(mask)).cpu().numpy()
+    assert max(rel_err_per_task(spec, got, ref)) <= 1e-4
+    model.close()
+
+
+# ------------------------------------------------------------------ whole model, bf16 mode
+
+def argmax_stats(spec, got, ref):
+    """(#pairs, #agree, #pairs with margin > 4e-2, #agree among those) over classification tasks."""
+    n = agree = n_safe = agree_safe = 0
+    col = 0
+    for t in spec.tasks:
+        if t.n_classes >= 2:
+            g, o = got[:, col:col + t.n_classes], ref[:, col:col + t.n_classes]
+            ga, oa = g.argmax(1), o.argmax(1)          # numpy argmax returns the lowest index among ties
+            srt = np.sort(o, axis=1)
+            margin = srt[:, -1] - srt[:, -2]
+            n += len(ga)
+            agree += int((ga == oa).sum())
+            safe = margin > 4e-2
+            n_safe += int(safe.sum())
+            agree_safe += int((ga == oa)[safe].sum())
+        col += t.n_classes
+    return n, agree, n_safe, agree_safe
+
+
+@pytest.mark.parametrize("stress", [False, True])
+def test_bf16_mode_small_model_matches_oracle(stress):
+    spec = SMALL
+    say(f"bf16 small model stress={stress}")
+    tr, tri, tps = _params(spec, stress, 0.05)
+    orc = oracle.Oracle(spec, tr, [p for p, _ in tps])
+    model = _load(spec, tr, tri, tps)
+    for bi in range(2):
+        ids, mask, _ = ms.make_inputs(spec, batch_index=bi)
+        ref = orc.mt_forward(ids, mask)
+        got = model.forward(dev(ids), dev(mask)).cpu().numpy()
+        err = np.abs(got - ref).max()
+        say(f"  batch {bi}: max |dlogit| {err:.4g}")
+        assert err <= 2e-2
+        n, agree, n_safe, agree_safe = argmax_stats(spec, got, ref)
+        assert agree_safe == n_safe
+    # smaller batch and sequence than the maximum, on the same model
+    ids, mask, _ = ms.make_inputs(spec, batch=2, seq=33, batch_index=5)
+    assert np.abs(model.forward(dev(ids), dev(mask)).cpu().numpy() - orc.mt_forward(ids, mask)).max() <= 2e-2
+    model.close()
+
+
+@pytest.fixture(scope="module")
+def base_model():
+    spec = ms.get_config("base")
+    say("building base model (synthetic BERT-base shapes, 8 tasks)")
+    tr, tri, tps = _params(spec, False)
+    model = _load(spec, tr, tri, tps)
+    yield spec, model, tr, [p for p, _ in tps]
+    model.close()
+
+
+def test_bf16_base_full_batch_sampled_sequences(base_model):
+    """The benchmark's launch configuration (B=32, S=128, all 8 tasks); the oracle evaluates sampled
+    sequences one batch-row at a time (sequences are independent, so rows of a sub-batch are exact)."""
+    spec, model, tr, tps = base_model
+    orc = oracle.Oracle(spec, tr, tps)
+    ids, mask, lengths = ms.make_inputs(spec)
+    got = model.forward(dev(ids), dev(mask)).cpu().numpy()
+    assert np.isfinite(got).all()
+    rows = [0, int(np.argmin(lengths)), int(np.argmax(lengths)), 17]
+    say("  oracle on rows", rows, "lengths", lengths[rows])
+    ref = orc.mt_forward(ids[rows], mask[rows])
+    err = np.abs(got[rows] - ref).max()
+    n, agree, n_safe, agree_safe = argmax_stats(spec, got[rows], ref)
+    say(f"  max |dlogit| {err:.4g}; argmax agree {agree}/{n}; with margin>4e-2: {agree_safe}/{n_safe}")
+    assert err <= 2e-2
+    assert agree_safe == n_safe
+
+
+def test_bf16_base_invariants_at_full_size(base_model):
+    spec, model, _, _ = base_model
+    ids, mask, lengths = ms.make_inputs(spec, batch_index=1)
+    d_ids, d_mask = dev(ids), dev(mask)
+    base = model.forward(d_ids, d_mask).cpu().numpy()
+    # determinism
+    assert np.array_equal(model.forward(d_ids, d_mask).cpu().numpy(), base)
+    # token ids under the mask are irrelevant
+    ids2 = ids.copy()
+    ids2[mask == 0] = (ids2[mask == 0] * 7 + 3) % spec.vocab
+    assert np.array_equal(model.forward(dev(ids2), d_mask).cpu().numpy(), base)
+    # each sequence alone gives its row of the batched run
+    for b in (0, 5):
+        one = model.forward(dev(ids[b:b + 1]), dev(mask[b:b + 1])).cpu().numpy()
+        assert np.abs(one[0] - base[b]).max() <= 1e-5
+    # truncating the padding away changes nothing
+    L = int(lengths[:4].max())
+    L = (L + 7) // 8 * 8
+    cut = model.forward(dev(ids[:4, :L]), dev(mask[:4, :L])).cpu().numpy()
+    assert np.abs(cut - base[:4]).max() <= 1e-5
+    # task mask: disabled tasks' columns stay untouched, enabled ones are unchanged
+    out = torch.full((ids.shape[0], model.n_logits), 7.0, device="cuda")
+    tm = [1, 0, 1, 1, 0, 0, 1, 0]
+    model.forward(d_ids, d_mask, out=out, task_mask=tm)
+    o = out.cpu().numpy()
+    col = 0
+    for t, task in enumerate(spec.tasks):
+        sl = slice(col, col + task.n_classes)
+        if tm[t]:
+            assert np.array_equal(o[:, sl], base[:, sl])
+        else:
+            assert (o[:, sl] == 7.0).all()
+        col += task.n_classes
+
+
+def test_bf16_base_task_isolation(base_model):
+    """Reloading one task's checkpoint leaves every other task's logits bit-identical (Section 5.1)."""
+    spec, model, _, tps = base_model
+    ids, mask, _ = ms.make_inputs(spec, batch=4, batch_index=2)
+    d_ids, d_mask = dev(ids), dev(mask)
+    before = model.forward(d_ids, d_mask).cpu().numpy()
+    new, newi = ms.make_task_params(spec, 3, seed=777)
+    model.load_params(3, new, len(newi))
+    after = model.forward(d_ids, d_mask).cpu().numpy()
+    lo, hi = model.logit_offset(3), model.logit_offset(3) + 3
+    assert np.array_equal(after[:, :lo], before[:, :lo]) and np.array_equal(after[:, hi:], before[:, hi:])
+    assert np.abs(after[:, lo:hi] - before[:, lo:hi]).max() > 1e-3
+    old, oldi = ms.make_task_params(spec, 3)
+    model.load_params(3, old, len(oldi))
+    assert np.array_equal(model.forward(d_ids, d_mask).cpu().numpy(), before)
+
+
+def test_bf16_vs_fp32_mode_argmax_over_many_sequences(base_model):
+    """Argmax agreement over 1024 sequences x 7 classification tasks between the bf16 path and the
+    float32 validation path of the same library (itself held to 1e-4 of the oracle above)."""
+    spec, model, tr, tps = base_model
+    f32 = mt.Model(mt.make_config(spec, precision=mt.MT_FP32_CHECK))
+    f32.load_params(-1, tr, len(ms.trunk_tensors(spec)))
+    for t, p in enumerate(tps):
+        f32.load_params(t, p, len(ms.task_tensors(spec, t)))
+    n = agree = n_safe = agree_safe = 0
+    worst = 0.0
+    for bi in range(32):
+        ids, mask, _ = ms.make_inputs(spec, batch_index=100 + bi)
+        d_ids, d_mask = dev(ids), dev(mask)
+        a = model.forward(d_ids, d_mask).cpu().numpy()
+        b = f32.forward(d_ids, d_mask).cpu().numpy()
+        worst = max(worst, float(np.abs(a - b).max()))
+        s = argmax_stats(spec, a, b)
+        n, agree, n_safe, agree_safe = n + s[0], agree + s[1], n_safe + s[2], agree_safe + s[3]
+    say(f"  bf16 vs fp32 mode: max |dlogit| {worst:.4g}; argmax agree {agree}/{n} = {agree / n:.5f}; "
+        f"margin>4e-2: {agree_safe}/{n_safe}")
+    f32.close()
+    assert worst <= 2e-2
+    assert agree_safe == n_safe
+    assert agree / n >= 0.999
