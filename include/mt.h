@@ -161,11 +161,18 @@ int mt_profile_read(mt_model* m, float* h_ms /*[MT_K_COUNT]*/, int32_t* h_launch
  * MT_BF16 -> bfloat16, MT_FP32_CHECK -> float32.  All enqueue on hip_stream and return.
  */
 /* C[M,N] = epilogue(A[M,K] W[N,K]^T + bias[N]) ; act_kind: 0 none, 1 GELU(erf), 2 GELU(tanh), 3 tanh.
- * d_residual (float32 [M,N]) may be NULL; if given it is added after the activation.
+ * d_residual (float32 [M,N]) may be NULL; if given it is added after the activation (bf16 precision:
+ * only together with out_f32 != 0, and then act_kind must be 0 - the two forms the model uses).
  * out_f32 != 0 stores float32, else the act type.  lda/ldc in elements. */
 int mt_op_linear(int32_t precision, const void* d_A, int64_t lda, const void* d_W, const float* d_bias,
                  const float* d_residual, void* d_C, int64_t ldc, int32_t M, int32_t N, int32_t K,
                  int32_t act_kind, int32_t out_f32, void* hip_stream);
+/* The grouped form: G same-shaped problems in one launch, problem g using base pointer + g*stride
+ * (strides in elements of the respective type; 0 shares the operand between problems), G <= 32. */
+int mt_op_linear_batched(int32_t precision, int32_t G, const void* d_A, int64_t strideA, int64_t lda, const void* d_W,
+                         int64_t strideW, const float* d_bias, int64_t strideBias, const float* d_residual,
+                         int64_t strideRes, void* d_C, int64_t strideC, int64_t ldc, int32_t M, int32_t N, int32_t K,
+                         int32_t act_kind, int32_t out_f32, void* hip_stream);
 /* ctx[b,s,a*d:(a+1)*d] = softmax(q k^T / sqrt(d) + mask) v per head; d_qkv is [B*S][3H] act
  * (columns Q | K | V), d_ctx [B*S][H] act. */
 int mt_op_attention(int32_t precision, const void* d_qkv, const int32_t* d_mask, void* d_ctx,
@@ -176,7 +183,7 @@ int mt_op_layernorm(const float* d_x, const float* d_gamma, const float* d_beta,
                     void* d_out_bf16, int32_t M, int32_t H, void* hip_stream);
 
 /* Tuning aid for benchmarks: force one bf16 GEMM tile configuration for all later launches in this
- * process (0 = choose by shape, the default; 1..6 = a fixed configuration).  Returns the previous value. */
+ * process (0 = choose by shape, the default; 1..12 = a fixed configuration).  Returns the previous value. */
 int mt_debug_set_gemm_tile(int32_t sel);
 
 #ifdef __cplusplus

@@ -25,7 +25,7 @@ KERNEL_CLASSES = ["embed", "gemm_qkv", "attn", "gemm_out", "ln", "gemm_ffn1", "g
 EXPORTS = ["mt_create", "mt_destroy", "mt_weight_bytes", "mt_workspace_bytes", "mt_bind", "mt_load_weights",
            "mt_forward", "mt_logit_offset", "mt_n_logits", "mt_layer_count", "mt_last_error", "mt_error_name",
            "mt_read_hidden", "mt_profile_enable", "mt_profile_read", "mt_op_linear", "mt_op_attention",
-           "mt_op_layernorm", "mt_debug_set_gemm_tile"]
+           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile"]
 
 
 class mt_task_desc(C.Structure):
@@ -73,6 +73,7 @@ def lib():
         L.mt_profile_enable.argtypes = [vp, i32]
         L.mt_profile_read.argtypes = [vp, vp, vp]
         L.mt_op_linear.argtypes = [i32, vp, i64, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, vp]
+        L.mt_op_linear_batched.argtypes = [i32, i32, vp, i64, i64, vp, i64, vp, i64, vp, i64, vp, i64, i64, i32, i32, i32, i32, i32, vp]
         L.mt_op_attention.argtypes = [i32, vp, vp, vp, i32, i32, i32, i32, vp]
         L.mt_op_layernorm.argtypes = [vp, vp, vp, C.c_float, vp, vp, i32, i32, vp]
         L.mt_debug_set_gemm_tile.argtypes = [i32]
@@ -210,6 +211,22 @@ def op_linear(precision, A, W, bias=None, residual=None, act=0, out_f32=False, l
                             _ptr(out), n, m, n, k, act, 1 if out_f32 else 0, _stream())
     if rc != MT_OK:
         raise MTError(rc, "mt_op_linear")
+    return out
+
+
+def op_linear_batched(precision, A, W, bias=None, residual=None, act=0, out_f32=False, out=None):
+    """Grouped form: A [G,M,K] (or [M,K], shared by all problems), W [G,N,K], bias [G,N], residual [G,M,N] -> C [G,M,N]."""
+    import torch
+    g, n, k = W.shape
+    shared = A.dim() == 2
+    m = A.shape[-2]
+    dt = torch.float32 if (out_f32 or precision == MT_FP32_CHECK) else torch.bfloat16
+    if out is None:
+        out = torch.empty((g, m, n), dtype=dt, device=W.device)
+    rc = lib().mt_op_linear_batched(precision, g, _ptr(A), 0 if shared else m * k, k, _ptr(W), n * k, _ptr(bias), n,
+                                    _ptr(residual), m * n, _ptr(out), m * n, n, m, n, k, act, 1 if out_f32 else 0, _stream())
+    if rc != MT_OK:
+        raise MTError(rc, "mt_op_linear_batched")
     return out
 
 

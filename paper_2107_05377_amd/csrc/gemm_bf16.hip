@@ -3,20 +3,28 @@
 // Both operands are K-contiguous, which is the native MFMA operand order, so no transposition is
 // needed anywhere.  Accumulation is float32 (v_mfma_f32_32x32x16_bf16).
 //
-// Tiling: a BM x BN output tile per workgroup, K consumed in slices of 64 through double-buffered
-// LDS.  Global loads of slice k+1 are issued into registers before the MFMAs of slice k and written
-// to the other LDS buffer afterwards, so one barrier per slice suffices.  LDS rows are 128 bytes
-// (8 chunks of 16 bytes); chunk c of row r is stored at chunk c ^ (r & 7) so that the 16-byte
-// fragment reads of 32 consecutive rows spread over all banks.
+// Tiling.  A BM x BN output tile per workgroup, K consumed in slices of BK (32 or 64) elements
+// through a ring of STAGES LDS stages.  Slices are fetched with global_load_lds_dwordx4: every lane
+// moves 16 bytes from global memory straight into LDS, no staging registers and no LDS stores.  One
+// such wavefront instruction fills 1024 contiguous LDS bytes (8 rows of 128 B or 16 rows of 64 B),
+// lane l landing in 16-byte slot l of that span; a lane therefore FETCHES the chunk that belongs in
+// its slot under the swizzle  slot = chunk ^ key(row), key = (row / rows-per-256-bytes) mod
+// chunks-per-row, which spreads the 16-byte fragment reads of 16 consecutive rows over all banks.
 //
-// Operand roles: the weight fragment is the first MFMA operand and the activation fragment the
-// second, so a lane ends up with 4 consecutive output columns n of one output row m.  That makes
-// bias loads, residual loads and stores 8- or 16-byte vectors along the row-major output.
+// Pipeline.  One barrier per slice, placed at the start of the slice's last 16-wide K step, when all
+// of a wavefront's fragment reads of that slice are in registers: after it the stage is free and is
+// refilled with the slice STAGES ahead, the refill instructions being spread over the following K
+// steps between MFMAs.  Fragments are double-buffered in registers so LDS latency hides behind the
+// MFMAs of the previous step.
 //
-// Workgroup -> tile mapping: consecutive workgroup ids go to different XCDs (8 of them, each with
-// its own L2), so ids are first regrouped such that each XCD owns a contiguous range of tiles, and
-// within a problem tiles are walked in bands of 8 row-tiles so that concurrently resident tiles
-// share weight columns and activation rows in that XCD's L2.
+// Operand roles.  The weight fragment is the first MFMA operand and the activation fragment the
+// second, so a lane ends up with 4 consecutive output columns n of one output row m: bias loads,
+// residual loads and stores are 8- or 16-byte vectors along the row-major output.
+//
+// Workgroup -> tile mapping.  Consecutive workgroup ids go to different XCDs (8, each with its own
+// L2), so ids are regrouped such that each XCD owns a contiguous range of tiles, and within a
+// problem tiles are walked in bands of row-tiles so that concurrently resident tiles share weight
+// columns and activation rows in that XCD's L2.
 #include "kernels.h"
 #include "device_util.h"
 
@@ -24,31 +32,107 @@ namespace mt {
 
 namespace {
 
-constexpr int BK = 64;              // K slice (elements)
-constexpr int ROW_BYTES = BK * 2;   // 128
 constexpr int kXcds = 8;
+constexpr bool kInterleave = true;
 constexpr int kBand = 8;            // row-tiles per raster band
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES>
 struct GemmCfg {
-    static constexpr int NT = WAVES_M * WAVES_N * 64;
+    static constexpr int ROW_BYTES = BK * 2;
+    static constexpr int CH = BK / 8;                       // 16-byte chunks per row
+    static constexpr int KK = BK / 16;                      // MFMA K steps per slice
+    static constexpr int RPI = 1024 / ROW_BYTES;            // rows filled by one wavefront load instruction
+    static constexpr int KEY_SHIFT = (BK == 64) ? 1 : 2;    // rows per 256 bytes of LDS = 2 or 4
+    static constexpr int NW = WAVES_M * WAVES_N;
+    static constexpr int NT = NW * 64;
     static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     static constexpr int TMI = WM / 32, TNI = WN / 32;
-    static constexpr int A_CHUNKS = BM * 8 / NT, W_CHUNKS = BN * 8 / NT;
+    static constexpr int A_LOADS = BM / RPI / NW, W_LOADS = BN / RPI / NW;   // load instructions per wavefront per slice
+    static constexpr int LPS = A_LOADS + W_LOADS;
+    static constexpr int LPP = (LPS + KK - 1) / KK;         // load instructions per K step ("part"), last part may be short
     static constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
-    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+    static_assert(BK == 32 || BK == 64, "BK");
     static_assert(BM % (WAVES_M * 32) == 0 && BN % (WAVES_N * 32) == 0, "wave tile must be a multiple of 32x32");
-    static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0, "tile rows must split evenly over threads");
+    static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "rows must split evenly over wavefront loads");
+    static_assert(STAGES >= 2 && STAGES <= 4, "STAGES");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds 160 KB");
 };
 
-__device__ inline int lds_chunk_off(int row, int chunk) { return row * ROW_BYTES + ((chunk ^ (row & 7)) << 4); }
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void wait_lgkmcnt0() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool OUT_F32>
-__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmGroup g, GemmShape s, int tiles_m,
+// wait until at most y*LPS of this wavefront's loads are outstanding (y = slices allowed in flight)
+template <int LPS>
+__device__ __forceinline__ void wait_slices(int y)
+{
+    if (y >= 2) wait_vmcnt<2 * LPS>();
+    else if (y == 1) wait_vmcnt<LPS>();
+    else wait_vmcnt<0>();
+}
+
+// Fast GELU(x) = x * Phi(x) for the bf16 epilogue: erf through the Abramowitz-Stegun 7.1.26 rational
+// (|error| <= 1.5e-7 before rounding), far below the bf16 rounding of the stored result.
+__device__ __forceinline__ float gelu_erf_fast(float x)
+{
+    const float ax = fabsf(x);
+    const float y = ax * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, y, 1.0f));
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    p *= t;
+    const float e = __builtin_amdgcn_exp2f(-y * y * 1.4426950408889634f);
+    const float erf_abs = fmaf(-p, e, 1.0f);          // erf(|x|/sqrt2)
+    return 0.5f * fmaf(ax, erf_abs, x);               // 0.5*(x + |x| erf(|x|/sqrt2)) = x*Phi(x)
+}
+
+template <int ACT>
+__device__ __forceinline__ float epi_act(float v)
+{
+    if constexpr (ACT == ACT_GELU_ERF) return gelu_erf_fast(v);
+    else if constexpr (ACT == ACT_GELU_TANH) return gelu_tanh(v);
+    else if constexpr (ACT == ACT_TANH) return tanhf(v);
+    else return v;
+}
+
+// Interleave hint for one K step: NF fragment reads and NL global->LDS loads are slotted between the
+// step's NM MFMAs so that no long run of non-MFMA instructions stalls the matrix pipe.
+template <int NM, int NF, int NL>
+__device__ __forceinline__ void interleave_step()
+{
+    constexpr int a = NF < NM ? NF : NM;
+    constexpr int b = (NL < NM - a) ? NL : (NM - a);
+#pragma unroll
+    for (int i = 0; i < a; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    if constexpr (NF > a) __builtin_amdgcn_sched_group_barrier(0x100, NF - a, 0);
+#pragma unroll
+    for (int i = 0; i < b; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+    if constexpr (NL > b) __builtin_amdgcn_sched_group_barrier(0x020, NL - b, 0);
+    if constexpr (NM - a - b > 0) __builtin_amdgcn_sched_group_barrier(0x008, NM - a - b, 0);
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int MINW, bool OUT_F32, int ACT>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64, MINW) void gemm_bf16_kernel(GemmGroup g, GemmShape s, int tiles_m,
                                                                           int tiles_n)
 {
-    using Cfg = GemmCfg<BM, BN, WAVES_M, WAVES_N>;
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    using Cfg = GemmCfg<BM, BN, WAVES_M, WAVES_N, BK, STAGES>;
+    constexpr int TMI = Cfg::TMI, TNI = Cfg::TNI, KK = Cfg::KK, ROW_BYTES = Cfg::ROW_BYTES, LPS = Cfg::LPS, LPP = Cfg::LPP;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     // ---- workgroup id -> (problem, row-tile, col-tile)
     const int total = s.G * tiles_m * tiles_n;
@@ -61,7 +145,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmGr
     }
     const int per_problem = tiles_m * tiles_n;
     const int grp = tile / per_problem;
-    int t = tile - grp * per_problem;
+    const int t = tile - grp * per_problem;
     int tm, tn;
     {
         const int band_sz = kBand * tiles_n;
@@ -73,149 +157,272 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmGr
     }
     const int m0 = tm * BM, n0 = tn * BN;
 
-    const __bf16* __restrict__ A = static_cast<const __bf16*>(g.A[grp]);
-    const __bf16* __restrict__ W = static_cast<const __bf16*>(g.W[grp]);
+    const unsigned char* __restrict__ A = static_cast<const unsigned char*>(g.A[grp]);
+    const unsigned char* __restrict__ W = static_cast<const unsigned char*>(g.W[grp]);
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm0 = (wave / WAVES_N) * Cfg::WM, wn0 = (wave % WAVES_N) * Cfg::WN;
     const int l32 = lane & 31, half = lane >> 5;
 
-    // ---- per-thread global source pointers and LDS destinations for the staging copies
-    const __bf16* a_src[Cfg::A_CHUNKS];
-    const __bf16* w_src[Cfg::W_CHUNKS];
-    int a_dst[Cfg::A_CHUNKS], w_dst[Cfg::W_CHUNKS];
+    // ---- per-lane byte offsets of the 16-byte chunks this lane fetches (one per load instruction)
+    // load i of a wavefront covers tile rows (wave + i*NW)*RPI .. +RPI-1; A loads first, then W loads
+    uint32_t ld_off[LPS];
 #pragma unroll
-    for (int i = 0; i < Cfg::A_CHUNKS; ++i) {
-        const int c = tid + i * Cfg::NT, row = c >> 3, ch = c & 7;
-        const int gm = min(m0 + row, s.M - 1);
-        a_src[i] = A + (size_t)gm * s.lda + ch * 8;
-        a_dst[i] = lds_chunk_off(row, ch);
-    }
-#pragma unroll
-    for (int i = 0; i < Cfg::W_CHUNKS; ++i) {
-        const int c = tid + i * Cfg::NT, row = c >> 3, ch = c & 7;
-        const int gn = min(n0 + row, s.N - 1);
-        w_src[i] = W + (size_t)gn * s.K + ch * 8;
-        w_dst[i] = BM * ROW_BYTES + lds_chunk_off(row, ch);
+    for (int i = 0; i < LPS; ++i) {
+        const bool isA = i < Cfg::A_LOADS;
+        const int row = (wave + (isA ? i : i - Cfg::A_LOADS) * Cfg::NW) * Cfg::RPI + lane / Cfg::CH;
+        const int chunk = (lane % Cfg::CH) ^ ((row >> Cfg::KEY_SHIFT) & (Cfg::CH - 1));
+        if (isA) ld_off[i] = (uint32_t)min(m0 + row, s.M - 1) * (uint32_t)(s.lda * 2) + chunk * 16;
+        else ld_off[i] = (uint32_t)min(n0 + row, s.N - 1) * (uint32_t)(s.K * 2) + chunk * 16;
     }
 
-    f32x16 acc[Cfg::TMI][Cfg::TNI];
+    f32x16 acc[TMI][TNI];
 #pragma unroll
-    for (int i = 0; i < Cfg::TMI; ++i)
+    for (int i = 0; i < TMI; ++i)
 #pragma unroll
-        for (int j = 0; j < Cfg::TNI; ++j)
+        for (int j = 0; j < TNI; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    uint4 a_reg[Cfg::A_CHUNKS], w_reg[Cfg::W_CHUNKS];
-    auto load_global = [&](int k0) {
+    // fragment read offsets inside a stage: row r = l32 of a 32-row block, K step kk -> slot (2kk+half) ^ key(r)
+    int fa_off[KK], fw_off[KK];
 #pragma unroll
-        for (int i = 0; i < Cfg::A_CHUNKS; ++i) a_reg[i] = *reinterpret_cast<const uint4*>(a_src[i] + k0);
-#pragma unroll
-        for (int i = 0; i < Cfg::W_CHUNKS; ++i) w_reg[i] = *reinterpret_cast<const uint4*>(w_src[i] + k0);
-    };
-    auto store_lds = [&](int buf) {
-        unsigned char* base = lds + buf * Cfg::STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < Cfg::A_CHUNKS; ++i) *reinterpret_cast<uint4*>(base + a_dst[i]) = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < Cfg::W_CHUNKS; ++i) *reinterpret_cast<uint4*>(base + w_dst[i]) = w_reg[i];
-    };
-
-    const int KT = s.K / BK;
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-
-    for (int kt = 0; kt < KT; ++kt) {
-        const bool more = kt + 1 < KT;
-        if (more) load_global((kt + 1) * BK);
-        const unsigned char* sa = lds + (kt & 1) * Cfg::STAGE_BYTES;
-        const unsigned char* sw = sa + BM * ROW_BYTES;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 af[Cfg::TMI], wf[Cfg::TNI];
-#pragma unroll
-            for (int i = 0; i < Cfg::TMI; ++i)
-                af[i] = *reinterpret_cast<const bf16x8*>(sa + lds_chunk_off(wm0 + i * 32 + l32, kk * 2 + half));
-#pragma unroll
-            for (int j = 0; j < Cfg::TNI; ++j)
-                wf[j] = *reinterpret_cast<const bf16x8*>(sw + lds_chunk_off(wn0 + j * 32 + l32, kk * 2 + half));
-#pragma unroll
-            for (int i = 0; i < Cfg::TMI; ++i)
-#pragma unroll
-                for (int j = 0; j < Cfg::TNI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[i][j], 0, 0, 0);
-        }
-        if (more) store_lds((kt + 1) & 1);
-        __syncthreads();
+    for (int kk = 0; kk < KK; ++kk) {
+        const int o = l32 * ROW_BYTES + (((kk * 2 + half) ^ ((l32 >> Cfg::KEY_SHIFT) & (Cfg::CH - 1))) << 4);
+        fa_off[kk] = wm0 * ROW_BYTES + o;
+        fw_off[kk] = (BM + wn0) * ROW_BYTES + o;
     }
 
-    // ---- epilogue: lane holds, for tile (i,j): row m = ..+l32, columns n = ..+8*q+4*half+{0..3}, q=0..3
-    const float* __restrict__ bias = g.bias[grp];
+    const int KT = s.K / BK;
+
+    // issue load instructions [part*LPP, part*LPP+LPP) of slice kt_ (caller guarantees kt_ < KT)
+#define MT_ISSUE_PART(kt_, part_)                                                                                  \
+    do {                                                                                                           \
+        const unsigned char* a_k = A + (size_t)(kt_) * ROW_BYTES;                                                  \
+        const unsigned char* w_k = W + (size_t)(kt_) * ROW_BYTES;                                                  \
+        unsigned char* sbase = lds + ((kt_) % STAGES) * Cfg::STAGE_BYTES;                                          \
+        _Pragma("unroll") for (int i_ = (part_) * LPP; i_ < (part_) * LPP + LPP; ++i_) {                           \
+            if (i_ >= LPS) {} else if (i_ < Cfg::A_LOADS)                                                                               \
+                __builtin_amdgcn_global_load_lds((gptr_t)(a_k + ld_off[i_]),                                       \
+                                                 (lptr_t)(sbase + (wave + i_ * Cfg::NW) * 1024), 16, 0, 0);        \
+            else                                                                                                   \
+                __builtin_amdgcn_global_load_lds((gptr_t)(w_k + ld_off[i_]),                                       \
+                                                 (lptr_t)(sbase + BM * ROW_BYTES + (wave + (i_ - Cfg::A_LOADS) * Cfg::NW) * 1024), 16, 0, 0); \
+        }                                                                                                          \
+    } while (0)
+
+#define MT_LOAD_FRAGS(buf_, kt_, kk_)                                                                              \
+    do {                                                                                                           \
+        const unsigned char* sb = lds + ((kt_) % STAGES) * Cfg::STAGE_BYTES;                                       \
+        _Pragma("unroll") for (int i = 0; i < TMI; ++i)                                                            \
+            af[buf_][i] = *reinterpret_cast<const bf16x8*>(sb + fa_off[kk_] + i * 32 * ROW_BYTES);                 \
+        _Pragma("unroll") for (int j = 0; j < TNI; ++j)                                                            \
+            wf[buf_][j] = *reinterpret_cast<const bf16x8*>(sb + fw_off[kk_] + j * 32 * ROW_BYTES);                 \
+    } while (0)
+
+#define MT_MFMAS(buf_)                                                                                             \
+    do {                                                                                                           \
+        _Pragma("unroll") for (int i = 0; i < TMI; ++i)                                                            \
+            _Pragma("unroll") for (int j = 0; j < TNI; ++j)                                                        \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf_][j], af[buf_][i], acc[i][j], 0, 0, 0); \
+    } while (0)
+
+    bf16x8 af[2][TMI], wf[2][TNI];
+
+    // prologue: slices 0..STAGES-2 in flight, wait for slice 0, then start refilling like a sync point would
+#pragma unroll
+    for (int p = 0; p < STAGES - 1; ++p)
+        if (p < KT) {
+#pragma unroll
+            for (int part = 0; part < KK; ++part) MT_ISSUE_PART(p, part);
+        }
+    wait_slices<LPS>(min(STAGES - 2, KT - 1));
+    __builtin_amdgcn_s_barrier();
+    if (STAGES - 1 < KT) MT_ISSUE_PART(STAGES - 1, 0);
+    MT_LOAD_FRAGS(0, 0, 0);
+
+    // steady state: every refill exists, no conditionals inside
+    const int KT_main = max(0, KT - STAGES);
+    int kt = 0;
+    for (; kt < KT_main; ++kt) {
+#pragma unroll
+        for (int kk = 0; kk < KK - 1; ++kk) {
+            MT_LOAD_FRAGS((kk + 1) & 1, kt, kk + 1);
+            MT_ISSUE_PART(kt + STAGES - 1, kk + 1);
+            MT_MFMAS(kk & 1);
+            if constexpr (kInterleave) interleave_step<TMI * TNI, TMI + TNI, LPP>();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // sync point: this wavefront's reads of slice kt are in registers; slice kt+1 must have landed
+        wait_lgkmcnt0();
+        wait_vmcnt<LPS*(STAGES - 2)>();
+        __builtin_amdgcn_s_barrier();
+        MT_ISSUE_PART(kt + STAGES, 0);          // stage kt % STAGES was just vacated by everyone
+        MT_LOAD_FRAGS(0, kt + 1, 0);
+        MT_MFMAS((KK - 1) & 1);
+        if constexpr (kInterleave) interleave_step<TMI * TNI, TMI + TNI, LPP>();
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // drain: the last min(KT, STAGES) slices; only slice KT-1 may still lack its parts 1..KK-1
+    if (kt + STAGES - 1 < KT) {
+#pragma unroll
+        for (int part = 1; part < KK; ++part) MT_ISSUE_PART(kt + STAGES - 1, part);
+    }
+    for (; kt < KT; ++kt) {
+#pragma unroll
+        for (int kk = 0; kk < KK - 1; ++kk) {
+            MT_LOAD_FRAGS((kk + 1) & 1, kt, kk + 1);
+            MT_MFMAS(kk & 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (kt + 1 < KT) {
+            wait_lgkmcnt0();
+            wait_slices<LPS>(KT - 1 - (kt + 1));
+            __builtin_amdgcn_s_barrier();
+            MT_LOAD_FRAGS(0, kt + 1, 0);
+        }
+        MT_MFMAS((KK - 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#undef MT_ISSUE_PART
+#undef MT_LOAD_FRAGS
+#undef MT_MFMAS
+
+    // ---- epilogue.  A lane holds, for block (i,j): row m = ..+l32, columns n = ..+8*q+4*half+{0..3}, q=0..3.
+    // Storing that layout directly would touch 32 rows with 16 bytes each per instruction, and would
+    // re-load the bias for every block.  Instead every wavefront parks its raw float32 accumulators
+    // in its own slice of the now idle LDS ring and reads them back row-contiguously, 4 consecutive
+    // columns per lane: the lane's 4 bias values are loaded once, bias / activation / residual are
+    // applied in a short rolled loop, and the stores cover whole row segments.
+    constexpr int ROWB = Cfg::WN * 4;                         // bytes per parked row
+    constexpr int NCH = ROWB / 16;                            // 16-byte chunks per row = lanes per row on the way out
+    constexpr int RPW = ROWB >= 256 ? 1 : 256 / ROWB;         // rows per 256 bytes: swizzle key = (row / RPW) mod NCH
+    constexpr int REGION = (Cfg::LDS_BYTES / Cfg::NW) & ~1023;
+    constexpr int RPP = (REGION / ROWB >= Cfg::WM) ? Cfg::WM : ((REGION / ROWB >= 64) ? 64 : 32);   // rows per pass
+    static_assert(REGION / ROWB >= 32 && Cfg::WM % RPP == 0, "LDS ring too small to park a 32-row block");
+    static_assert(NCH <= 64 && 64 % NCH == 0, "row must split evenly over lanes");
+    constexpr int ROWS_PER_INST = 64 / NCH;
+    unsigned char* park = lds + wave * REGION;
+    const int c = lane % NCH;
+    const int n = n0 + wn0 + c * 4;
+    const bool n_ok = n < s.N;                                // N % 4 == 0, so the lane's 4 columns are all in or all out
+    float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (g.bias[grp] && n_ok) bv = *reinterpret_cast<const float4*>(g.bias[grp] + n);
     const float* __restrict__ res = g.residual[grp];
-    const int act = s.act;
+    unsigned char* __restrict__ Cout = static_cast<unsigned char*>(g.C[grp]);     // hoisted: read the argument block once
+    const size_t ldc_b = (size_t)s.ldc * (OUT_F32 ? 4 : 2), ldr_b = (size_t)s.ldr * 4;
+    const int M = s.M;
+
+    constexpr int NIT = RPP / ROWS_PER_INST;                 // read-back iterations per pass
+    constexpr int UNR = NIT >= 4 ? 4 : 1;                      // LDS reads in flight per lane
+    // residual rows of a pass are fetched up front so that their HBM latency overlaps the parking:
+    // as many as the register budget allows (the rest are fetched late, UNR at a time)
+    constexpr int PF = !OUT_F32 ? 0 : (MINW >= 2 ? (NIT < 8 ? NIT : 8) : (NIT < 32 ? NIT : 32));
+
+    __builtin_amdgcn_s_barrier();      // every wavefront has taken its last fragments out of the ring
 #pragma unroll
-    for (int i = 0; i < Cfg::TMI; ++i) {
-        const int m = m0 + wm0 + i * 32 + l32;
-        if (m >= s.M) continue;
+    for (int p = 0; p < Cfg::WM / RPP; ++p) {
+        float4 rpf[PF > 0 ? PF : 1];
+        if constexpr (PF > 0) {
+            if (res) {
+                const int nc = n_ok ? n : 0;
 #pragma unroll
-        for (int j = 0; j < Cfg::TNI; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn0 + j * 32 + q * 8 + half * 4;
-                if (n >= s.N) continue;
-                float v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e];
-                if (bias) {
-                    const float4 b = *reinterpret_cast<const float4*>(bias + n);
-                    v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
+                for (int u = 0; u < PF; ++u) {
+                    const int mc = min(m0 + wm0 + p * RPP + u * ROWS_PER_INST + lane / NCH, M - 1);
+                    rpf[u] = *reinterpret_cast<const float4*>(reinterpret_cast<const unsigned char*>(res) + mc * ldr_b + nc * 4);
                 }
-                if (act != ACT_NONE) {
+            }
+        }
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = apply_act(v[e], act);
+        for (int ii = 0; ii < RPP / 32; ++ii) {
+            const int ml = ii * 32 + l32;
+            const int key = (ml / RPW) & (NCH - 1);
+#pragma unroll
+            for (int j = 0; j < TNI; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int chunk = (j * 32 + q * 8 + half * 4) >> 2;
+                    const f32x16& a = acc[p * (RPP / 32) + ii][j];
+                    *reinterpret_cast<float4*>(park + ml * ROWB + ((chunk ^ key) << 4)) =
+                        make_float4(a[q * 4 + 0], a[q * 4 + 1], a[q * 4 + 2], a[q * 4 + 3]);
                 }
-                if (res) {
-                    const float4 r = *reinterpret_cast<const float4*>(res + (size_t)m * s.ldr + n);
-                    v[0] += r.x; v[1] += r.y; v[2] += r.z; v[3] += r.w;
-                }
+        }
+        // the same wavefront reads back what it wrote: LDS operations of one wavefront execute in order
+#pragma unroll
+        for (int it = 0; it < NIT; it += UNR) {
+            float4 v[UNR], rv[UNR];
+            int mm[UNR];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {                             // unconditional, in-bounds reads first
+                const int ml = (it + u) * ROWS_PER_INST + lane / NCH;
+                const int key = (ml / RPW) & (NCH - 1);
+                v[u] = *reinterpret_cast<const float4*>(park + ml * ROWB + ((c ^ key) << 4));
+                mm[u] = m0 + wm0 + p * RPP + ml;
                 if constexpr (OUT_F32) {
-                    float* C = static_cast<float*>(g.C[grp]);
-                    *reinterpret_cast<float4*>(C + (size_t)m * s.ldc + n) = make_float4(v[0], v[1], v[2], v[3]);
+                    if (res) {
+                        if (it + u < PF) rv[u] = rpf[(it + u) < PF ? (it + u) : 0];
+                        else {
+                            const int mc = min(mm[u], M - 1);
+                            const int nc = n_ok ? n : 0;
+                            rv[u] = *reinterpret_cast<const float4*>(reinterpret_cast<const unsigned char*>(res) + mc * ldr_b + nc * 4);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                float4 o;
+                o.x = epi_act<ACT>(v[u].x + bv.x);
+                o.y = epi_act<ACT>(v[u].y + bv.y);
+                o.z = epi_act<ACT>(v[u].z + bv.z);
+                o.w = epi_act<ACT>(v[u].w + bv.w);
+                const bool ok = n_ok && mm[u] < M;
+                if constexpr (OUT_F32) {
+                    if (res) { o.x += rv[u].x; o.y += rv[u].y; o.z += rv[u].z; o.w += rv[u].w; }
+                    if (ok) *reinterpret_cast<float4*>(Cout + mm[u] * ldc_b + n * 4) = o;
                 } else {
-                    __bf16* C = static_cast<__bf16*>(g.C[grp]);
-                    bf16x4 o = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
-                    *reinterpret_cast<bf16x4*>(C + (size_t)m * s.ldc + n) = o;
+                    bf16x4 ob = {(__bf16)o.x, (__bf16)o.y, (__bf16)o.z, (__bf16)o.w};
+                    if (ok) *reinterpret_cast<bf16x4*>(Cout + mm[u] * ldc_b + n * 2) = ob;
                 }
             }
         }
     }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
-hipError_t launch_cfg(const GemmGroup& g, const GemmShape& s, hipStream_t stream)
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int MINW, bool OUT_F32, int ACT>
+hipError_t launch_one(const GemmGroup& g, const GemmShape& s, hipStream_t stream)
 {
-    using Cfg = GemmCfg<BM, BN, WAVES_M, WAVES_N>;
+    using Cfg = GemmCfg<BM, BN, WAVES_M, WAVES_N, BK, STAGES>;
     const int tiles_m = (s.M + BM - 1) / BM, tiles_n = (s.N + BN - 1) / BN;
     const int total = s.G * tiles_m * tiles_n;
-    static bool attr_set[2] = {false, false};
-    auto kf = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, true>;
-    auto kb = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, false>;
-    if (Cfg::LDS_BYTES > 64 * 1024) {
-        const int which = s.out_f32 ? 0 : 1;
-        if (!attr_set[which]) {
-            hipError_t e = hipFuncSetAttribute(s.out_f32 ? (const void*)kf : (const void*)kb,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
-            if (e != hipSuccess) return e;
-            attr_set[which] = true;
-        }
+    auto kfn = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, OUT_F32, ACT>;
+    static bool attr_set = false;
+    if (Cfg::LDS_BYTES > 64 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
     }
-    dim3 grid(total), block(Cfg::NT);
-    if (s.out_f32) hipLaunchKernelGGL(kf, grid, block, Cfg::LDS_BYTES, stream, g, s, tiles_m, tiles_n);
-    else hipLaunchKernelGGL(kb, grid, block, Cfg::LDS_BYTES, stream, g, s, tiles_m, tiles_n);
+    hipLaunchKernelGGL(kfn, dim3(total), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, g, s, tiles_m, tiles_n);
     return hipGetLastError();
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int MINW>
+hipError_t launch_cfg(const GemmGroup& g, const GemmShape& s, hipStream_t stream)
+{
+    // Instantiated epilogues: float32 output without activation (residual sums feeding LayerNorm) and
+    // bf16 output with none / GELU(erf) / GELU(tanh).
+    if (s.out_f32) {
+        if (s.act != ACT_NONE) return hipErrorInvalidValue;
+        return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, true, ACT_NONE>(g, s, stream);
+    }
+    switch (s.act) {
+        case ACT_NONE: return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, false, ACT_NONE>(g, s, stream);
+        case ACT_GELU_ERF: return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, false, ACT_GELU_ERF>(g, s, stream);
+        case ACT_GELU_TANH: return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, false, ACT_GELU_TANH>(g, s, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace
@@ -225,21 +432,34 @@ int g_gemm_bf16_tile_override = 0;   // 0 = choose by shape; set through mt_debu
 hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t stream)
 {
     if (s.G <= 0 || s.M <= 0 || s.N <= 0) return hipSuccess;
-    if (s.K % BK != 0 || s.K < BK || s.N % 4 != 0 || s.lda % 8 != 0 || s.ldc % 4 != 0 || s.ldr % 4 != 0 || s.G > kMaxGroup)
+    if (s.K % 64 != 0 || s.K < 64 || s.N % 4 != 0 || s.lda % 8 != 0 || s.ldc % 4 != 0 || s.ldr % 4 != 0 ||
+        s.G > kMaxGroup || (!s.out_f32 && g.residual[0] != nullptr))
+        return hipErrorInvalidValue;
+    // per-lane chunk offsets are 32-bit
+    if ((uint64_t)s.M * (uint64_t)s.lda * 2 >= (1ull << 32) || (uint64_t)s.N * (uint64_t)s.K * 2 >= (1ull << 32))
         return hipErrorInvalidValue;
     int sel = g_gemm_bf16_tile_override;
     if (sel == 0) {
-        // Enough 256x128 tiles to fill 256 CUs at least ~3 times over -> larger tile; otherwise 128x128.
-        const long t256 = (long)s.G * ((s.M + 255) / 256) * ((s.N + 127) / 128);
-        sel = (t256 >= 768) ? 2 : 1;
+        // Measured on MI355X (BERT-base/large shapes): many tiles -> 256x256 with 8 wavefronts; few wide
+        // tiles (N >= 2048) still prefer it; narrow outputs with few tiles -> 128x128, two workgroups per CU.
+        const long t256 = (long)s.G * ((s.M + 255) / 256) * ((s.N + 255) / 256);
+        if (t256 >= 1024) sel = 9;
+        else if (t256 >= 128 && s.N >= 2048) sel = 9;
+        else sel = (s.K >= 2048) ? 1 : 6;
     }
     switch (sel) {
-        case 2: return launch_cfg<256, 128, 2, 2>(g, s, stream);
-        case 3: return launch_cfg<256, 256, 2, 2>(g, s, stream);
-        case 4: return launch_cfg<256, 256, 2, 4>(g, s, stream);
-        case 5: return launch_cfg<128, 256, 2, 2>(g, s, stream);
-        case 6: return launch_cfg<128, 128, 1, 4>(g, s, stream);
-        default: return launch_cfg<128, 128, 2, 2>(g, s, stream);
+        case 2: return launch_cfg<256, 128, 2, 2, 32, 3, 2>(g, s, stream);   // 72 KB LDS: two workgroups per CU
+        case 3: return launch_cfg<256, 256, 2, 2, 32, 4, 1>(g, s, stream);   // 128 KB LDS, 128x128 per wavefront
+        case 4: return launch_cfg<256, 256, 2, 4, 64, 2, 2>(g, s, stream);   // 8 wavefronts
+        case 5: return launch_cfg<128, 256, 2, 2, 32, 3, 2>(g, s, stream);
+        case 6: return launch_cfg<128, 128, 2, 2, 64, 2, 2>(g, s, stream);   // 64 KB LDS: two workgroups per CU
+        case 7: return launch_cfg<256, 256, 2, 2, 64, 2, 1>(g, s, stream);
+        case 8: return launch_cfg<256, 128, 2, 2, 64, 3, 1>(g, s, stream);
+        case 9: return launch_cfg<256, 256, 2, 4, 32, 4, 2>(g, s, stream);
+        case 10: return launch_cfg<256, 128, 2, 2, 64, 2, 1>(g, s, stream);
+        case 11: return launch_cfg<256, 128, 4, 2, 32, 3, 2>(g, s, stream);  // 8 wavefronts of 64x64, 72 KB
+        case 12: return launch_cfg<128, 128, 2, 2, 32, 3, 2>(g, s, stream);  // 48 KB: three workgroups per CU
+        default: return launch_cfg<128, 128, 2, 2, 32, 4, 2>(g, s, stream);  // 64 KB LDS
     }
 }
 

@@ -766,7 +766,7 @@ int mt_profile_read(mt_model* m, float* h_ms, int32_t* h_launches)
 int mt_debug_set_gemm_tile(int32_t sel)
 {
     const int prev = mt::g_gemm_bf16_tile_override;
-    mt::g_gemm_bf16_tile_override = (sel >= 0 && sel <= 6) ? sel : 0;
+    mt::g_gemm_bf16_tile_override = (sel >= 0 && sel <= 12) ? sel : 0;
     return prev;
 }
 
@@ -787,6 +787,33 @@ int mt_op_linear(int32_t precision, const void* d_A, int64_t lda, const void* d_
     GemmShape s{1, M, N, K, lda, ldc, ldc, act_kind, (precision == MT_BF16) ? (out_f32 ? 1 : 0) : 1};
     hipError_t e = precision == MT_BF16 ? launch_gemm_bf16(g, s, static_cast<hipStream_t>(hip_stream))
                                         : launch_gemm_f32(g, s, 0, static_cast<hipStream_t>(hip_stream));
+    if (e == hipErrorInvalidValue) return MT_ERR_SHAPE;
+    return e == hipSuccess ? MT_OK : MT_ERR_HIP;
+}
+
+int mt_op_linear_batched(int32_t precision, int32_t G, const void* d_A, int64_t strideA, int64_t lda, const void* d_W,
+                         int64_t strideW, const float* d_bias, int64_t strideBias, const float* d_residual,
+                         int64_t strideRes, void* d_C, int64_t strideC, int64_t ldc, int32_t M, int32_t N, int32_t K,
+                         int32_t act_kind, int32_t out_f32, void* hip_stream)
+{
+    if (!d_A || !d_W || !d_C) return MT_ERR_NULL;
+    if (G < 1 || G > kMaxGroup || M < 1 || N < 1 || K < 1 || act_kind < 0 || act_kind > 3) return MT_ERR_SHAPE;
+    const bool bf = precision == MT_BF16;
+    const size_t esz = bf ? 2 : 4;
+    const int of32 = bf ? (out_f32 ? 1 : 0) : 1;
+    GemmGroup g;
+    memset(&g, 0, sizeof g);
+    for (int i = 0; i < G; ++i) {
+        g.A[i] = static_cast<const unsigned char*>(d_A) + (size_t)i * strideA * esz;
+        g.W[i] = static_cast<const unsigned char*>(d_W) + (size_t)i * strideW * esz;
+        g.C[i] = static_cast<unsigned char*>(d_C) + (size_t)i * strideC * (of32 ? 4 : 2);
+        g.bias[i] = d_bias ? d_bias + (size_t)i * strideBias : nullptr;
+        g.residual[i] = d_residual ? d_residual + (size_t)i * strideRes : nullptr;
+        g.N[i] = N;
+    }
+    GemmShape s{G, M, N, K, lda, ldc, ldc, act_kind, of32};
+    hipError_t e = bf ? launch_gemm_bf16(g, s, static_cast<hipStream_t>(hip_stream))
+                      : launch_gemm_f32(g, s, 0, static_cast<hipStream_t>(hip_stream));
     if (e == hipErrorInvalidValue) return MT_ERR_SHAPE;
     return e == hipSuccess ? MT_OK : MT_ERR_HIP;
 }
