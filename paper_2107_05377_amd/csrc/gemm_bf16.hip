@@ -411,9 +411,10 @@ hipError_t launch_one(const GemmGroup& g, const GemmShape& s, hipStream_t stream
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int MINW>
 hipError_t launch_cfg(const GemmGroup& g, const GemmShape& s, hipStream_t stream)
 {
-    // Instantiated epilogues: float32 output without activation (residual sums feeding LayerNorm) and
-    // bf16 output with none / GELU(erf) / GELU(tanh).
+    // Instantiated epilogues: float32 output without activation (residual sums feeding LayerNorm) or with
+    // tanh (pooler), and bf16 output with none / GELU(erf) / GELU(tanh).
     if (s.out_f32) {
+        if (s.act == ACT_TANH) return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, true, ACT_TANH>(g, s, stream);
         if (s.act != ACT_NONE) return hipErrorInvalidValue;
         return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, true, ACT_NONE>(g, s, stream);
     }

@@ -60,4 +60,23 @@ hipError_t launch_embed_ln(const int32_t* ids, int B, int S, int H, int vocab, c
                            const void* type, int emb_bf16, const float* gamma, const float* beta, float eps,
                            float* out_f32, bf16_t* out_bf16, hipStream_t stream);
 
+// Pooler input for the matrix-core path: row b of problem g is token 0 of sequence b of x[g] (float32,
+// row stride ldx); it is written as [hi | lo] bfloat16 halves, hi = bf16(v), lo = bf16(v - hi), into
+// out[g] ([B][2H]), so that a bf16 contraction against [W | W] reproduces the float32 input to ~2^-17.
+struct SplitGroup {
+    const float* x[kMaxGroup];
+    bf16_t* out[kMaxGroup];
+};
+hipError_t launch_cls_split(const SplitGroup& g, int G, int B, int H, int64_t ldx, hipStream_t stream);
+
+// logits[g][b][c] = Wc_g[c][:] . pooled_g[b][:] + bc_g[c]; one wavefront per (g, b, c).  Wc bf16 or fp32.
+struct ClsGroup {
+    const float* pooled[kMaxGroup];   // [B][H]
+    const void* Wc[kMaxGroup];        // [C][H]
+    const float* bc[kMaxGroup];
+    float* out[kMaxGroup];            // first logit column of the task, row stride ldo
+    int32_t C[kMaxGroup];
+};
+hipError_t launch_classifier(const ClsGroup& g, int G, int B, int H, int maxC, int w_bf16, int64_t ldo, hipStream_t stream);
+
 }  // namespace mt

@@ -35,7 +35,7 @@ struct LayerW {   // byte offsets into the weight arena
 };
 struct TaskW {
     std::vector<LayerW> layers;
-    size_t Wp, bp, Wc, bc;
+    size_t Wp, bp, Wc, bc;   // Wp is [H][2H] = [W | W] in bf16 mode (see launch_cls_split), [H][H] in fp32 mode
     size_t begin, end;   // the task's private region of the arena
 };
 struct Scratch {   // byte offsets into the workspace; one set for the trunk and one per task
@@ -70,7 +70,7 @@ struct mt_model {
     Scratch trunk_scr{};
     std::vector<Scratch> task_scr;
     std::vector<size_t> task_xf, task_xb;
-    size_t pooled = 0;
+    size_t pooled = 0, cls_split = 0;
     size_t workspace_bytes = 0;
 
     unsigned char* d_w = nullptr;
@@ -420,7 +420,7 @@ int mt_create(const mt_config* cfg, mt_model** out)
         TaskW& tw = m->taskw[t];
         tw.begin = wb.off;
         for (int l = 0; l < m->tasks[t].n_layers; ++l) tw.layers.push_back(layout_layer(wb, H, F, m->esz));
-        tw.Wp = wb.take(H * H * m->esz);
+        tw.Wp = wb.take(H * H * m->esz * (m->bf16 ? 2 : 1));
         tw.bp = wb.take(H * 4);
         tw.Wc = wb.take((size_t)m->tasks[t].n_classes * H * m->esz);
         tw.bc = wb.take((size_t)m->tasks[t].n_classes * 4);
@@ -457,6 +457,7 @@ int mt_create(const mt_config* cfg, mt_model** out)
         }
     }
     m->pooled = sb.take(T * (size_t)cfg->max_batch * H * 4);
+    m->cls_split = m->bf16 ? sb.take(T * (size_t)cfg->max_batch * 2 * H * 2) : 0;
     m->workspace_bytes = sb.off;
     m->task_loaded.assign(T, 0);
     m->last_enabled.assign(T, 0);
@@ -567,7 +568,17 @@ int mt_load_weights(mt_model* m, int32_t scope, const void* h_blob, size_t nbyte
         const TaskW& tw = m->taskw[scope];
         const size_t C = m->tasks[scope].n_classes;
         for (const LayerW& L : tw.layers) p += stage_layer(m, L, p, img, begin);
-        put_matrix(at(tw.Wp), p, H * H, m->bf16); p += H * H;
+        if (m->bf16) {   // rows of [W | W]
+            std::vector<uint16_t> row(H);
+            for (size_t r = 0; r < H; ++r) {
+                put_matrix(reinterpret_cast<unsigned char*>(row.data()), p + r * H, H, true);
+                memcpy(at(tw.Wp) + r * 2 * H * 2, row.data(), H * 2);
+                memcpy(at(tw.Wp) + r * 2 * H * 2 + H * 2, row.data(), H * 2);
+            }
+        } else {
+            put_matrix(at(tw.Wp), p, H * H, false);
+        }
+        p += H * H;
         memcpy(at(tw.bp), p, H * 4); p += H;
         put_matrix(at(tw.Wc), p, C * H, m->bf16); p += C * H;
         memcpy(at(tw.bc), p, C * 4); p += C;
@@ -671,36 +682,48 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
         }
     }
 
-    // ---- poolers and classifiers (float32 inputs in both modes)
+    // ---- poolers and classifiers.  The pooler input stays float32-accurate in both modes: the bf16
+    // path feeds the matrix cores with the [hi | lo] split of the first-token rows against [W | W].
     for (size_t lo = 0; lo < enabled.size(); lo += kMaxGroup) {
         const int n = (int)std::min(enabled.size() - lo, (size_t)kMaxGroup);
         GemmGroup g;
         memset(&g, 0, sizeof g);
+        SplitGroup sg;
+        memset(&sg, 0, sizeof sg);
+        ClsGroup cg;
+        memset(&cg, 0, sizeof cg);
         int maxC = 0;
         for (int i = 0; i < n; ++i) {
             const int t = enabled[lo + i];
             const mt_task_desc& d = m->tasks[t];
             const float* z = d.n_layers > 0 ? (const float*)(ws + m->task_xf[t])
                                             : (const float*)(ws + m->tap_f[m->tap_of_layer[d.fork_layer]]);
-            g.A[i] = z;   // row b of the problem is token 0 of sequence b: lda = S*H
+            float* pooled = (float*)(ws + m->pooled + (size_t)t * m->cfg.max_batch * H * 4);
+            sg.x[i] = z;
+            sg.out[i] = bf ? (bf16_t*)(ws + m->cls_split + (size_t)t * m->cfg.max_batch * 2 * H * 2) : nullptr;
+            g.A[i] = bf ? (const void*)sg.out[i] : (const void*)z;   // fp32 mode: row b = token 0 of sequence b, lda = S*H
             g.W[i] = W + m->taskw[t].Wp;
             g.bias[i] = (const float*)(W + m->taskw[t].bp);
-            g.C[i] = ws + m->pooled + (size_t)t * m->cfg.max_batch * H * 4;
+            g.C[i] = pooled;
             g.N[i] = H;
+            cg.pooled[i] = pooled;
+            cg.Wc[i] = W + m->taskw[t].Wc;
+            cg.bc[i] = (const float*)(W + m->taskw[t].bc);
+            cg.out[i] = d_out_logits + m->logit_off[t];
+            cg.C[i] = d.n_classes;
+            maxC = std::max(maxC, d.n_classes);
         }
-        GemmShape s{n, B, H, H, (int64_t)S * H, H, 0, ACT_TANH, 1};
-        L.gemm(MT_K_POOL, g, s, true);
-        for (int i = 0; i < n; ++i) {
-            const int t = enabled[lo + i];
-            g.A[i] = g.C[i];
-            g.W[i] = W + m->taskw[t].Wc;
-            g.bias[i] = (const float*)(W + m->taskw[t].bc);
-            g.C[i] = d_out_logits + m->logit_off[t];
-            g.N[i] = m->tasks[t].n_classes;
-            maxC = std::max(maxC, m->tasks[t].n_classes);
+        L.begin(MT_K_POOL);
+        if (bf) {
+            L.check(launch_cls_split(sg, n, B, H, (int64_t)S * H, L.st));
+            GemmShape s{n, B, H, 2 * H, 2 * H, H, 0, ACT_TANH, 1};
+            L.check(launch_gemm_bf16(g, s, L.st));
+        } else {
+            GemmShape s{n, B, H, H, (int64_t)S * H, H, 0, ACT_TANH, 1};
+            L.check(launch_gemm_f32(g, s, 0, L.st));
         }
-        GemmShape c{n, B, maxC, H, H, m->C_tot, 0, ACT_NONE, 1};
-        L.gemm(MT_K_POOL, g, c, true);
+        L.check(launch_classifier(cg, n, B, H, maxC, bf ? 1 : 0, m->C_tot, L.st));
+        L.end();
     }
 
     if (L.first_err != hipSuccess) return fail(m, MT_ERR_HIP, "mt_forward: launch failed: %s", hipGetErrorString(L.first_err));

@@ -174,7 +174,50 @@ hipError_t embed_dispatch(const int32_t* ids, int B, int S, int H, int vocab, co
     return hipGetLastError();
 }
 
+__global__ __launch_bounds__(256) void cls_split_kernel(SplitGroup g, int H, int64_t ldx)
+{
+    const int grp = blockIdx.y, b = blockIdx.x;
+    const float* x = g.x[grp] + (size_t)b * ldx;
+    __bf16* out = reinterpret_cast<__bf16*>(g.out[grp]) + (size_t)b * 2 * H;
+    for (int i = threadIdx.x; i < H; i += 256) {
+        const float v = x[i];
+        const __bf16 hi = (__bf16)v;
+        out[i] = hi;
+        out[H + i] = (__bf16)(v - (float)hi);
+    }
+}
+
+template <typename TW>
+__global__ __launch_bounds__(256) void classifier_kernel(ClsGroup g, int B, int H, int64_t ldo)
+{
+    const int grp = blockIdx.y, b = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float* p = g.pooled[grp] + (size_t)b * H;
+    for (int c = wave; c < g.C[grp]; c += 4) {
+        const TW* w = static_cast<const TW*>(g.Wc[grp]) + (size_t)c * H;
+        float acc = 0.f;
+        for (int i = lane; i < H; i += 64) acc = fmaf(p[i], (float)w[i], acc);
+        acc = wave_sum(acc);
+        if (lane == 0) g.out[grp][(size_t)b * ldo + c] = acc + g.bc[grp][c];
+    }
+}
+
 }  // namespace
+
+hipError_t launch_cls_split(const SplitGroup& g, int G, int B, int H, int64_t ldx, hipStream_t stream)
+{
+    if (G <= 0 || B <= 0) return hipSuccess;
+    hipLaunchKernelGGL(cls_split_kernel, dim3(B, G), dim3(256), 0, stream, g, H, ldx);
+    return hipGetLastError();
+}
+
+hipError_t launch_classifier(const ClsGroup& g, int G, int B, int H, int maxC, int w_bf16, int64_t ldo, hipStream_t stream)
+{
+    if (G <= 0 || B <= 0 || maxC <= 0) return hipSuccess;
+    if (w_bf16) hipLaunchKernelGGL((classifier_kernel<__bf16>), dim3(B, G), dim3(256), 0, stream, g, B, H, ldo);
+    else hipLaunchKernelGGL((classifier_kernel<float>), dim3(B, G), dim3(256), 0, stream, g, B, H, ldo);
+    return hipGetLastError();
+}
 
 hipError_t launch_layernorm(const LnGroup& g, int G, int M, int H, float eps, hipStream_t stream)
 {
