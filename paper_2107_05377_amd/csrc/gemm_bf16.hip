@@ -32,9 +32,18 @@ namespace mt {
 
 namespace {
 
-constexpr int kXcds = 8;
-constexpr bool kInterleave = true;
-constexpr int kBand = 8;            // row-tiles per raster band
+#ifndef MT_GEMM_XCDS
+#define MT_GEMM_XCDS 8
+#endif
+#ifndef MT_GEMM_BAND
+#define MT_GEMM_BAND 8
+#endif
+#ifndef MT_GEMM_INTERLEAVE
+#define MT_GEMM_INTERLEAVE 1
+#endif
+constexpr int kXcds = MT_GEMM_XCDS;              // 1 disables the per-XCD regrouping of workgroup ids
+constexpr bool kInterleave = MT_GEMM_INTERLEAVE != 0;
+constexpr int kBand = MT_GEMM_BAND;              // row-tiles per raster band
 
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -441,12 +450,16 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
         return hipErrorInvalidValue;
     int sel = g_gemm_bf16_tile_override;
     if (sel == 0) {
-        // Measured on MI355X (BERT-base/large shapes): many tiles -> 256x256 with 8 wavefronts; few wide
-        // tiles (N >= 2048) still prefer it; narrow outputs with few tiles -> 128x128, two workgroups per CU.
+        // Shape rule from measurements on MI355X (M = 4096, BERT-base widths, 1 and 8 problems):
+        // wide outputs or very many tiles -> 256x256 with 8 wavefronts (least L2 traffic per flop), except
+        // the GELU epilogue, whose vector work hides better behind a second resident workgroup (256x128);
+        // narrow outputs -> 128x128 with two workgroups per CU, K slices of 64 when there are enough tiles
+        // to fill the chip several times, else the deeper 4-stage ring of 32-wide slices.
         const long t256 = (long)s.G * ((s.M + 255) / 256) * ((s.N + 255) / 256);
-        if (t256 >= 1024) sel = 9;
-        else if (t256 >= 128 && s.N >= 2048) sel = 9;
-        else sel = (s.K >= 2048) ? 1 : 6;
+        const bool gelu = s.act == ACT_GELU_ERF || s.act == ACT_GELU_TANH;
+        if (s.N >= 2048 || t256 >= 2048) sel = (gelu && t256 >= 1024) ? 2 : 9;
+        else if (t256 * 4 >= 1024) sel = 6;
+        else sel = 1;
     }
     switch (sel) {
         case 2: return launch_cfg<256, 128, 2, 2, 32, 3, 2>(g, s, stream);   // 72 KB LDS: two workgroups per CU
