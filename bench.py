@@ -21,12 +21,14 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
 PEAK_FP32_VALU_TFLOPS = 157.3
 
 
-def gemm_flops_per_forward(spec, layer_evals_trunk, branch_layer_evals, B, S):
-    """Executed (dense, padded) FLOPs of the four linear layers, per class, for one forward."""
-    M, H, F = B * S, spec.hidden, spec.ffn
-    L = layer_evals_trunk + branch_layer_evals
-    return {"gemm_qkv": L * 2.0 * M * 3 * H * H, "gemm_out": L * 2.0 * M * H * H,
-            "gemm_ffn1": L * 2.0 * M * F * H, "gemm_ffn2": L * 2.0 * M * H * F}
+def gemm_flops_per_forward(spec, n_layers, rows):
+    """EXECUTED FLOPs of the four linear layers, per class, for one forward over `rows` token rows.
+
+    The library drops padded positions before the first layer, so `rows` is the number of real
+    tokens of the batch (sum of sequence lengths), not batch*seq."""
+    H, F = spec.hidden, spec.ffn
+    return {"gemm_qkv": n_layers * 2.0 * rows * 3 * H * H, "gemm_out": n_layers * 2.0 * rows * H * H,
+            "gemm_ffn1": n_layers * 2.0 * rows * F * H, "gemm_ffn2": n_layers * 2.0 * rows * H * F}
 
 
 def main():
@@ -62,10 +64,12 @@ def main():
     model, _ = mt.load_synthetic(spec, max_batch=B, max_seq=S)
     load_s = time.time() - t0
     n_batches = 8
-    batches = []
+    batches, real_tokens, sq_lengths = [], [], []
     for i in range(n_batches):
-        ids, mask, _ = ms.make_inputs(spec, batch=B, batch_index=i)
+        ids, mask, lengths = ms.make_inputs(spec, batch=B, batch_index=i)
         batches.append((torch.from_numpy(ids).cuda(), torch.from_numpy(mask).cuda()))
+        real_tokens.append(int(mask.sum()))
+        sq_lengths.append(float((lengths.astype(np.float64) ** 2).sum()))
     out = torch.zeros((B, model.n_logits), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
 
@@ -91,7 +95,10 @@ def main():
     model.profile_enable(False)
 
     n_layers = model.layer_count()
-    flops = gemm_flops_per_forward(spec, spec.n_trunk_layers, n_layers - spec.n_trunk_layers, B, S)
+    # the timed steps cycle through the batches: average real-token count over the steps actually run
+    rows = float(np.mean([real_tokens[i % n_batches] for i in range(args.steps)]))
+    sumsq = float(np.mean([sq_lengths[i % n_batches] for i in range(args.steps)]))
+    flops = gemm_flops_per_forward(spec, n_layers, rows)
     kernels = {}
     for k, (ms_tot, n) in prof.items():
         if n == 0:
@@ -108,12 +115,15 @@ def main():
     roofline = {"kernel": "gemm_bf16_kernel" if bf16 else "gemm_f32_kernel", "bound": "mfma" if bf16 else "alu",
                 "achieved": gemm_tflops, "peak": peak, "unit": "TFLOP/s", "frac": gemm_tflops / peak, "traffic": None,
                 "flops_per_launch": sum(flops.values()) / gemm_launches, "avg_launch_us": 1e3 * gemm_ms / gemm_launches,
+                "flops_counted": "executed: real (unpadded) token rows only",
                 "launches_per_step": gemm_launches, "gemm_ms_per_step": gemm_ms}
 
     h = spec.hidden
     per_layer = 8.0 * S * h * h + 4.0 * S * h * spec.ffn + 4.0 * S * S * h
-    flops_per_seq = n_layers * per_layer + spec.n_tasks * 2.0 * h * h
-    e2e_tflops = flops_per_seq * seq_per_s / 1e12
+    flops_per_seq_dense = n_layers * per_layer + spec.n_tasks * 2.0 * h * h          # dense, padded convention
+    executed_per_step = sum(flops.values()) + n_layers * 4.0 * h * sumsq + spec.n_tasks * 2.0 * B * 2 * h * h
+    e2e_tflops = executed_per_step / (ms_per_step * 1e-3) / 1e12
+    e2e_tflops_dense = flops_per_seq_dense * seq_per_s / 1e12
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -138,8 +148,10 @@ def main():
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{spec.name}: H={spec.hidden} A={spec.heads} F={spec.ffn} trunk={spec.n_trunk_layers} "
                                f"tasks={spec.n_tasks} layers={n_layers} B={B} S={S} len~U[{spec.len_lo},{spec.len_hi}]",
-                   "batch": B, "seq_len": S, "layer_evals": n_layers},
-        "e2e_tflops_dense_padded": e2e_tflops, "e2e_frac_of_peak": e2e_tflops / peak,
+                   "batch": B, "seq_len": S, "layer_evals": n_layers, "real_tokens_per_batch": rows,
+                   "padding_skipped": True},
+        "e2e_tflops_executed": e2e_tflops, "e2e_frac_of_peak": e2e_tflops / peak,
+        "e2e_tflops_dense_padded_equivalent": e2e_tflops_dense,
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "weights_load_s": load_s,
     }
     print(json.dumps(line))

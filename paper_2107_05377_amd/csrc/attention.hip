@@ -1,4 +1,6 @@
 // Masked-softmax attention, one (problem, sequence, head, 128-query tile) per workgroup.
+// A sequence's rows are either its slice of the padding-free row order (seq_start/seq_len given: every
+// row is a real token, no mask needed) or the dense rows b*S.. with a key mask.
 //
 // bfloat16 path (head width 64): the workgroup stages the head's keys K[S][64] and its values,
 // transposed to Vt[64][S], in LDS once; each of the 4 wavefronts then owns 32 queries.
@@ -30,26 +32,32 @@ constexpr float kMaskedScore = -10000.0f;
 
 __device__ inline int k_chunk_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
 
-__global__ __launch_bounds__(256) void attention_bf16_kernel(AttnGroup g, const int32_t* __restrict__ mask, int B,
-                                                             int S, int H, int Sk, float scale_log2e)
+__global__ __launch_bounds__(256) void attention_bf16_kernel(AttnGroup g, const int32_t* __restrict__ mask,
+                                                             const int32_t* __restrict__ seq_start,
+                                                             const int32_t* __restrict__ seq_len, int B, int S, int H, int Sk_max,
+                                                             float scale_log2e)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int grp = blockIdx.z / B, b = blockIdx.z % B, a = blockIdx.y;
+    const int row0 = seq_start ? seq_start[b] : b * S;             // first row of this sequence
+    const int n_tok = seq_len ? min(seq_len[b], S) : S;            // rows (queries and keys) of this sequence
+    if ((int)blockIdx.x * 128 >= n_tok) return;                    // whole workgroup: nothing to do
+    const int Sk = (n_tok + 31) / 32 * 32;                         // keys rounded up to whole 32-key blocks (<= Sk_max)
     const int vt_stride = Sk + 4;                                  // elements; keeps 8-byte reads aligned, spreads banks
     unsigned char* Ks = lds;                                       // [Sk][128 B], 16-byte chunks XOR-swizzled by row
     __bf16* Vt = reinterpret_cast<__bf16*>(lds + Sk * 128);        // [64][vt_stride]
     float* kvalid = reinterpret_cast<float*>(lds + Sk * 128 + 64 * vt_stride * 2);   // [Sk] 1.0 = real key
     int* blk_any = reinterpret_cast<int*>(kvalid + Sk);            // [Sk/32]
 
-    const int grp = blockIdx.z / B, b = blockIdx.z % B, a = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const size_t ld = (size_t)3 * H;
-    const __bf16* __restrict__ qkv = static_cast<const __bf16*>(g.qkv[grp]) + (size_t)b * S * ld;
-    const int32_t* __restrict__ mrow = mask + (size_t)b * S;
+    const __bf16* __restrict__ qkv = static_cast<const __bf16*>(g.qkv[grp]) + (size_t)row0 * ld;
+    const int32_t* __restrict__ mrow = mask ? mask + (size_t)b * S : nullptr;
     const int nblk = Sk / 32;
 
     // ---- stage key validity
-    for (int k = tid; k < Sk; k += 256) kvalid[k] = (k < S && mrow[k] != 0) ? 1.0f : 0.0f;
+    for (int k = tid; k < Sk; k += 256) kvalid[k] = (k < n_tok && (!mrow || mrow[k] != 0)) ? 1.0f : 0.0f;
     __syncthreads();
     if (tid < nblk) {
         int any = 0;
@@ -60,7 +68,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(AttnGroup g, const 
     for (int c = tid; c < Sk * 8; c += 256) {
         const int key = c >> 3, ch = c & 7;
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (key < S) v = *reinterpret_cast<const uint4*>(qkv + (size_t)key * ld + H + a * 64 + ch * 8);
+        if (key < n_tok) v = *reinterpret_cast<const uint4*>(qkv + (size_t)key * ld + H + a * 64 + ch * 8);
         *reinterpret_cast<uint4*>(Ks + k_chunk_off(key, ch)) = v;
     }
     // ---- stage V transposed: each item is a pair of adjacent keys x one 8-wide chunk of d
@@ -82,11 +90,11 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(AttnGroup g, const 
 
     // ---- this wavefront's 32 queries
     const int q0 = blockIdx.x * 128 + wave * 32;
-    if (q0 >= S) return;
+    if (q0 >= n_tok) return;
     const int q = q0 + l32;
-    const bool q_real = (q < S) && (mrow[q < S ? q : 0] != 0);
+    const bool q_real = (q < n_tok) && (!mrow || mrow[q < n_tok ? q : 0] != 0);
     if (__ballot(q_real) == 0ull) return;
-    const int qc = q < S ? q : S - 1;
+    const int qc = q < n_tok ? q : n_tok - 1;
 
     bf16x8 qf[4];
 #pragma unroll
@@ -181,9 +189,9 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(AttnGroup g, const 
         }
     }
 
-    if (q < S) {
+    if (q < n_tok) {
         const float inv = 1.0f / l_run;
-        __bf16* out = static_cast<__bf16*>(g.ctx[grp]) + ((size_t)b * S + q) * H + a * 64;
+        __bf16* out = static_cast<__bf16*>(g.ctx[grp]) + ((size_t)row0 + q) * H + a * 64;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
@@ -197,17 +205,21 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(AttnGroup g, const 
 
 // float32 validation path.  One workgroup per (problem, sequence, head); each wavefront takes queries
 // wave, wave+4, ...; lanes run over keys for the scores and over head columns for the context.
-__global__ __launch_bounds__(256) void attention_f32_kernel(AttnGroup g, const int32_t* __restrict__ mask, int B,
-                                                            int S, int H, int A, float scale)
+__global__ __launch_bounds__(256) void attention_f32_kernel(AttnGroup g, const int32_t* __restrict__ mask,
+                                                            const int32_t* __restrict__ seq_start,
+                                                            const int32_t* __restrict__ seq_len, int B, int Smax, int H, int A,
+                                                            float scale)
 {
-    extern __shared__ float sprob[];   // [4][S]
+    extern __shared__ float sprob[];   // [4][Smax]
     const int grp = blockIdx.z / B, b = blockIdx.z % B, a = blockIdx.y;
     const int d = H / A;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t ld = (size_t)3 * H;
-    const float* qkv = static_cast<const float*>(g.qkv[grp]) + (size_t)b * S * ld;
-    const int32_t* mrow = mask + (size_t)b * S;
-    float* p = sprob + wave * S;
+    const int row0 = seq_start ? seq_start[b] : b * Smax;
+    const int S = seq_len ? min(seq_len[b], Smax) : Smax;
+    const float* qkv = static_cast<const float*>(g.qkv[grp]) + (size_t)row0 * ld;
+    const int32_t* mrow = mask ? mask + (size_t)b * Smax : nullptr;
+    float* p = sprob + wave * Smax;
     for (int i = wave; i < S; i += 4) {
         const float* qi = qkv + (size_t)i * ld + a * d;
         float mx = -INFINITY;
@@ -216,7 +228,7 @@ __global__ __launch_bounds__(256) void attention_f32_kernel(AttnGroup g, const i
             float acc = 0.f;
             for (int c = 0; c < d; ++c) acc = fmaf(qi[c], kj[c], acc);
             float sc = acc * scale;
-            if (mrow[j] == 0) sc += kMaskedScore;
+            if (mrow && mrow[j] == 0) sc += kMaskedScore;
             p[j] = sc;
             mx = fmaxf(mx, sc);
         }
@@ -232,16 +244,17 @@ __global__ __launch_bounds__(256) void attention_f32_kernel(AttnGroup g, const i
         for (int c = lane; c < d; c += 64) {
             float acc = 0.f;
             for (int j = 0; j < S; ++j) acc = fmaf(p[j], qkv[(size_t)j * ld + 2 * H + a * d + c], acc);
-            static_cast<float*>(g.ctx[grp])[((size_t)b * S + i) * H + a * d + c] = acc * inv;
+            static_cast<float*>(g.ctx[grp])[((size_t)row0 + i) * H + a * d + c] = acc * inv;
         }
     }
 }
 
 }  // namespace
 
-hipError_t launch_attention_bf16(const AttnGroup& g, int G, const int32_t* mask, int B, int S, int H, int A,
-                                 hipStream_t stream)
+hipError_t launch_attention_bf16(const AttnGroup& g, int G, const int32_t* mask, const int32_t* seq_start,
+                                 const int32_t* seq_len, int B, int S, int H, int A, hipStream_t stream)
 {
+    if (!mask && !(seq_start && seq_len)) return hipErrorInvalidValue;
     if (G <= 0 || B <= 0 || S <= 0) return hipSuccess;
     if (H != A * 64 || G > kMaxGroup || S > 1024) return hipErrorInvalidValue;
     const int Sk = (S + 31) / 32 * 32;
@@ -256,18 +269,20 @@ hipError_t launch_attention_bf16(const AttnGroup& g, int G, const int32_t* mask,
     }
     dim3 grid((S + 127) / 128, A, B * G), block(256);
     const float scale_log2e = (1.0f / sqrtf(64.0f)) * kLog2e;
-    hipLaunchKernelGGL(attention_bf16_kernel, grid, block, lds, stream, g, mask, B, S, H, Sk, scale_log2e);
+    hipLaunchKernelGGL(attention_bf16_kernel, grid, block, lds, stream, g, mask, seq_start, seq_len, B, S, H, Sk, scale_log2e);
     return hipGetLastError();
 }
 
-hipError_t launch_attention_f32(const AttnGroup& g, int G, const int32_t* mask, int B, int S, int H, int A,
-                                hipStream_t stream)
+hipError_t launch_attention_f32(const AttnGroup& g, int G, const int32_t* mask, const int32_t* seq_start,
+                                const int32_t* seq_len, int B, int S, int H, int A, hipStream_t stream)
 {
+    if (!mask && !(seq_start && seq_len)) return hipErrorInvalidValue;
     if (G <= 0 || B <= 0 || S <= 0) return hipSuccess;
     if (G > kMaxGroup || (size_t)S * 16 > 64 * 1024) return hipErrorInvalidValue;
     dim3 grid(1, A, B * G), block(256);
     const float scale = 1.0f / sqrtf((float)(H / A));
-    hipLaunchKernelGGL(attention_f32_kernel, grid, block, (size_t)S * 4 * sizeof(float), stream, g, mask, B, S, H, A, scale);
+    hipLaunchKernelGGL(attention_f32_kernel, grid, block, (size_t)S * 4 * sizeof(float), stream, g, mask, seq_start, seq_len, B, S, H, A,
+                       scale);
     return hipGetLastError();
 }
 

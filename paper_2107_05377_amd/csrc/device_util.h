@@ -18,6 +18,12 @@ __device__ inline float wave_sum(float v)
     for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
     return v;
 }
+__device__ inline int wave_sum_int(int v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
 __device__ inline float wave_max(float v)
 {
 #pragma unroll

@@ -136,15 +136,18 @@ __device__ __forceinline__ void interleave_step()
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int MINW, bool OUT_F32, int ACT>
-__global__ __launch_bounds__(WAVES_M* WAVES_N * 64, MINW) void gemm_bf16_kernel(GemmGroup g, GemmShape s, int tiles_m,
-                                                                          int tiles_n)
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64, MINW) void gemm_bf16_kernel(GemmGroup g, GemmShape s, int tiles_n)
 {
     using Cfg = GemmCfg<BM, BN, WAVES_M, WAVES_N, BK, STAGES>;
     constexpr int TMI = Cfg::TMI, TNI = Cfg::TNI, KK = Cfg::KK, ROW_BYTES = Cfg::ROW_BYTES, LPS = Cfg::LPS, LPP = Cfg::LPP;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
-    // ---- workgroup id -> (problem, row-tile, col-tile)
+    // ---- rows actually present (the grid is sized for the bound s.M), then
+    //      workgroup id -> (problem, row-tile, col-tile); workgroups beyond the last tile leave at once
+    const int M = s.d_M ? min(s.M, *s.d_M) : s.M;
+    const int tiles_m = (M + BM - 1) / BM;
     const int total = s.G * tiles_m * tiles_n;
+    if ((int)blockIdx.x >= total) return;
     int tile;
     {
         const int bid = blockIdx.x;
@@ -183,7 +186,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, MINW) void gemm_bf16_kernel(
         const bool isA = i < Cfg::A_LOADS;
         const int row = (wave + (isA ? i : i - Cfg::A_LOADS) * Cfg::NW) * Cfg::RPI + lane / Cfg::CH;
         const int chunk = (lane % Cfg::CH) ^ ((row >> Cfg::KEY_SHIFT) & (Cfg::CH - 1));
-        if (isA) ld_off[i] = (uint32_t)min(m0 + row, s.M - 1) * (uint32_t)(s.lda * 2) + chunk * 16;
+        if (isA) ld_off[i] = (uint32_t)min(m0 + row, M - 1) * (uint32_t)(s.lda * 2) + chunk * 16;
         else ld_off[i] = (uint32_t)min(n0 + row, s.N - 1) * (uint32_t)(s.K * 2) + chunk * 16;
     }
 
@@ -322,8 +325,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, MINW) void gemm_bf16_kernel(
     const float* __restrict__ res = g.residual[grp];
     unsigned char* __restrict__ Cout = static_cast<unsigned char*>(g.C[grp]);     // hoisted: read the argument block once
     const size_t ldc_b = (size_t)s.ldc * (OUT_F32 ? 4 : 2), ldr_b = (size_t)s.ldr * 4;
-    const int M = s.M;
-
     constexpr int NIT = RPP / ROWS_PER_INST;                 // read-back iterations per pass
     constexpr int UNR = NIT >= 4 ? 4 : 1;                      // LDS reads in flight per lane
     // residual rows of a pass are fetched up front so that their HBM latency overlaps the parking:
@@ -413,7 +414,7 @@ hipError_t launch_one(const GemmGroup& g, const GemmShape& s, hipStream_t stream
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kfn, dim3(total), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, g, s, tiles_m, tiles_n);
+    hipLaunchKernelGGL(kfn, dim3(total), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, g, s, tiles_n);
     return hipGetLastError();
 }
 

@@ -19,8 +19,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmGroup g, GemmShape s)
     __shared__ float Ws[TK][TN + 4];
     const int grp = blockIdx.z;
     const int N = g.N[grp];
+    const int M = s.d_M ? min(s.M, *s.d_M) : s.M;      // rows actually present; the grid covers the bound s.M
     const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
-    if (n0 >= N) return;
+    if (n0 >= N || m0 >= M) return;
     const float* A = static_cast<const float*>(g.A[grp]);
     const TW* W = static_cast<const TW*>(g.W[grp]);
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -32,7 +33,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmGroup g, GemmShape s)
         for (int j = 0; j < 4; ++j) {
             const int k = k0 + lk + j;
             const int am = m0 + lr, wn = n0 + lr;
-            As[lk + j][lr] = (am < s.M && k < s.K) ? A[(size_t)am * s.lda + k] : 0.f;
+            As[lk + j][lr] = (am < M && k < s.K) ? A[(size_t)am * s.lda + k] : 0.f;
             Ws[lk + j][lr] = (wn < N && k < s.K) ? (float)W[(size_t)wn * s.K + k] : 0.f;
         }
         __syncthreads();
@@ -54,7 +55,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmGroup g, GemmShape s)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int m = m0 + ty * 4 + i;
-        if (m >= s.M) continue;
+        if (m >= M) continue;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int n = n0 + tx * 4 + j;

@@ -26,10 +26,11 @@ struct GemmGroup {
 };
 
 struct GemmShape {
-    int32_t G, M, N, K;     // N = max over the group
+    int32_t G, M, N, K;     // N = max over the group; M = row bound (grid size), see d_M
     int64_t lda, ldc, ldr;  // row strides in elements (W is dense: ldw = K)
     int32_t act;            // ActKind
     int32_t out_f32;        // 1: C is float32, 0: C has the activation element type
+    const int32_t* d_M;     // optional device scalar: rows actually present (<= M); tiles beyond it exit at once
 };
 
 // bf16 x bf16 -> fp32 accumulate on the matrix cores.  Needs K % 64 == 0, lda % 8 == 0, 16-byte aligned A/W rows.
@@ -37,14 +38,29 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
 // fp32 (A) x {fp32|bf16} (W) on the vector ALUs, any shape.  w_bf16 selects the W element type.
 hipError_t launch_gemm_f32(const GemmGroup& g, const GemmShape& s, int w_bf16, hipStream_t stream);
 
-struct AttnGroup {
-    const void* qkv[kMaxGroup];   // [B*S][3H]: Q | K | V
-    void* ctx[kMaxGroup];         // [B*S][H]
+// Token rows of a batch in padding-free order: only positions with mask == 1 are kept, sequence after
+// sequence, so every row-wise kernel and every contraction runs on sum_b len_b rows instead of B*S.
+struct RowMap {
+    int32_t* n_rows;      // [1]  number of kept rows
+    int32_t* src;         // [B*S] kept row -> b*S+s
+    int32_t* row_of;      // [B*S] b*S+s -> kept row, or -1
+    int32_t* seq_start;   // [B]  first kept row of sequence b
+    int32_t* seq_len;     // [B]  kept rows of sequence b
 };
-hipError_t launch_attention_bf16(const AttnGroup& g, int G, const int32_t* mask, int B, int S, int H, int A,
-                                 hipStream_t stream);
-hipError_t launch_attention_f32(const AttnGroup& g, int G, const int32_t* mask, int B, int S, int H, int A,
-                                hipStream_t stream);
+hipError_t launch_build_row_map(const int32_t* mask, int B, int S, const RowMap& map, hipStream_t stream);
+// out[b*S+s][:] = x[row_of[b*S+s]][:] or 0 (float32, H columns)
+hipError_t launch_unpack_rows(const float* x, const int32_t* row_of, int n_pos, int H, float* out, hipStream_t stream);
+
+struct AttnGroup {
+    const void* qkv[kMaxGroup];   // [rows][3H]: Q | K | V
+    void* ctx[kMaxGroup];         // [rows][H]
+};
+// Sequence b owns rows seq_start[b] .. +seq_len[b]-1 (all real tokens) when the two arrays are given;
+// otherwise rows b*S .. b*S+S-1 with `mask` ([B][S], 1 = real) marking the keys.  S bounds the length.
+hipError_t launch_attention_bf16(const AttnGroup& g, int G, const int32_t* mask, const int32_t* seq_start,
+                                 const int32_t* seq_len, int B, int S, int H, int A, hipStream_t stream);
+hipError_t launch_attention_f32(const AttnGroup& g, int G, const int32_t* mask, const int32_t* seq_start,
+                                const int32_t* seq_len, int B, int S, int H, int A, hipStream_t stream);
 
 struct LnGroup {
     const float* x[kMaxGroup];      // [M][H] fp32, already bias+residual summed
@@ -53,21 +69,27 @@ struct LnGroup {
     float* out_f32[kMaxGroup];      // may be null
     bf16_t* out_bf16[kMaxGroup];    // may be null
 };
-hipError_t launch_layernorm(const LnGroup& g, int G, int M, int H, float eps, hipStream_t stream);
+// d_M (optional device scalar) = rows actually present (<= M)
+hipError_t launch_layernorm(const LnGroup& g, int G, int M, const int32_t* d_M, int H, float eps, hipStream_t stream);
 
-// X0 = LN(word[id] + pos[s] + type[0]); tables are bf16 (emb_bf16 != 0) or fp32.
-hipError_t launch_embed_ln(const int32_t* ids, int B, int S, int H, int vocab, const void* word, const void* pos,
+// X0[r] = LN(word[ids[p]] + pos[p % S] + type[0]) with p = src[r] for the kept rows r < *d_M (p = r and all
+// B*S rows when src is null); tables are bf16 (emb_bf16 != 0) or fp32.
+hipError_t launch_embed_ln(const int32_t* ids, const int32_t* src, const int32_t* d_M, int B, int S, int H, int vocab, const void* word, const void* pos,
                            const void* type, int emb_bf16, const float* gamma, const float* beta, float eps,
                            float* out_f32, bf16_t* out_bf16, hipStream_t stream);
 
-// Pooler input for the matrix-core path: row b of problem g is token 0 of sequence b of x[g] (float32,
-// row stride ldx); it is written as [hi | lo] bfloat16 halves, hi = bf16(v), lo = bf16(v - hi), into
+// Pooler input for the matrix-core path: row b of problem g is the first token of sequence b of x[g]
+// (float32 rows of H; row seq_start[b], or b*rows_per_seq when seq_start is null); it is written as [hi | lo] bfloat16 halves, hi = bf16(v), lo = bf16(v - hi), into
 // out[g] ([B][2H]), so that a bf16 contraction against [W | W] reproduces the float32 input to ~2^-17.
 struct SplitGroup {
     const float* x[kMaxGroup];
     bf16_t* out[kMaxGroup];
 };
-hipError_t launch_cls_split(const SplitGroup& g, int G, int B, int H, int64_t ldx, hipStream_t stream);
+// float32 validation mode: the same first-token rows copied unchanged, out[g] reinterpreted as float [B][H]
+hipError_t launch_gather_rows(const SplitGroup& g, int G, int B, int H, const int32_t* seq_start, int rows_per_seq, int max_rows,
+                              hipStream_t stream);
+hipError_t launch_cls_split(const SplitGroup& g, int G, int B, int H, const int32_t* seq_start, int rows_per_seq, int max_rows,
+                            hipStream_t stream);
 
 // logits[g][b][c] = Wc_g[c][:] . pooled_g[b][:] + bc_g[c]; one wavefront per (g, b, c).  Wc bf16 or fp32.
 struct ClsGroup {

@@ -1,6 +1,10 @@
 // Host side of the library: configuration checks, the merged graph's schedule (paper Section 3.3,
 // Fig. 1(c)), arena layouts, checkpoint loading and the enqueue-only forward pass.
 //
+// Rows.  Every forward first builds the padding-free row order of the batch on the device (only
+// positions with mask == 1 are kept); all row-wise kernels and contractions then run on those rows,
+// their count being read from device memory so that the host never waits for it.
+//
 // Schedule.  The trunk (shared frozen layers) runs once up to the deepest fork among the enabled
 // tasks; the hidden state after every layer some task forks at is kept (a "tap").  Branches then
 // advance in lock step: stage s runs layer s of every enabled task that has at least s own layers,
@@ -71,6 +75,7 @@ struct mt_model {
     std::vector<Scratch> task_scr;
     std::vector<size_t> task_xf, task_xb;
     size_t pooled = 0, cls_split = 0;
+    size_t rm_n = 0, rm_src = 0, rm_rowof = 0, rm_start = 0, rm_len = 0;   // padding-free row map of the current batch
     size_t workspace_bytes = 0;
 
     unsigned char* d_w = nullptr;
@@ -252,7 +257,7 @@ struct LayerIO {
     void* out_b;
 };
 
-void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const int32_t* d_mask, int B, int S)
+void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& rm, int B, int S)
 {
     mt_model* m = L.m;
     const int H = m->cfg.hidden, F = m->cfg.ffn, A = m->cfg.heads, M = B * S;
@@ -275,7 +280,7 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const int32_t*
         g.C[i] = ws + io[i].scr->qkv;
         g.N[i] = 3 * H;
     }
-    s = GemmShape{n, M, 3 * H, H, H, 3 * H, 0, ACT_NONE, bf ? 0 : 1};
+    s = GemmShape{n, M, 3 * H, H, H, 3 * H, 0, ACT_NONE, bf ? 0 : 1, rm.n_rows};
     L.gemm(MT_K_GEMM_QKV, g, s, false);
 
     // attention
@@ -286,7 +291,8 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const int32_t*
         ag.ctx[i] = ws + io[i].scr->ctx;
     }
     L.begin(MT_K_ATTN);
-    L.check(bf ? launch_attention_bf16(ag, n, d_mask, B, S, H, A, L.st) : launch_attention_f32(ag, n, d_mask, B, S, H, A, L.st));
+    L.check(bf ? launch_attention_bf16(ag, n, nullptr, rm.seq_start, rm.seq_len, B, S, H, A, L.st)
+               : launch_attention_f32(ag, n, nullptr, rm.seq_start, rm.seq_len, B, S, H, A, L.st));
     L.end();
 
     // output projection + bias + residual -> y (fp32), then LayerNorm -> x1
@@ -298,7 +304,7 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const int32_t*
         g.C[i] = ws + io[i].scr->y;
         g.N[i] = H;
     }
-    s = GemmShape{n, M, H, H, H, H, H, ACT_NONE, 1};
+    s = GemmShape{n, M, H, H, H, H, H, ACT_NONE, 1, rm.n_rows};
     L.gemm(MT_K_GEMM_OUT, g, s, false);
 
     LnGroup lg;
@@ -311,7 +317,7 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const int32_t*
         lg.out_bf16[i] = bf ? (bf16_t*)(ws + io[i].scr->x1b) : nullptr;
     }
     L.begin(MT_K_LN);
-    L.check(launch_layernorm(lg, n, M, H, m->cfg.ln_eps, L.st));
+    L.check(launch_layernorm(lg, n, M, rm.n_rows, H, m->cfg.ln_eps, L.st));
     L.end();
 
     // FFN1 + bias + GELU -> u
@@ -323,7 +329,7 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const int32_t*
         g.C[i] = ws + io[i].scr->u;
         g.N[i] = F;
     }
-    s = GemmShape{n, M, F, H, H, F, 0, gelu_act, bf ? 0 : 1};
+    s = GemmShape{n, M, F, H, H, F, 0, gelu_act, bf ? 0 : 1, rm.n_rows};
     L.gemm(MT_K_GEMM_FFN1, g, s, false);
 
     // FFN2 + bias + residual -> y, then LayerNorm -> layer output
@@ -335,7 +341,7 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const int32_t*
         g.C[i] = ws + io[i].scr->y;
         g.N[i] = H;
     }
-    s = GemmShape{n, M, H, F, F, H, H, ACT_NONE, 1};
+    s = GemmShape{n, M, H, F, F, H, H, ACT_NONE, 1, rm.n_rows};
     L.gemm(MT_K_GEMM_FFN2, g, s, false);
 
     for (int i = 0; i < n; ++i) {
@@ -346,7 +352,7 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const int32_t*
         lg.out_bf16[i] = bf ? (bf16_t*)io[i].out_b : nullptr;
     }
     L.begin(MT_K_LN);
-    L.check(launch_layernorm(lg, n, M, H, m->cfg.ln_eps, L.st));
+    L.check(launch_layernorm(lg, n, M, rm.n_rows, H, m->cfg.ln_eps, L.st));
     L.end();
 }
 
@@ -456,8 +462,13 @@ int mt_create(const mt_config* cfg, mt_model** out)
             m->task_xb.push_back(0);
         }
     }
+    m->rm_n = sb.take(4);
+    m->rm_src = sb.take(M * 4);
+    m->rm_rowof = sb.take(M * 4);
+    m->rm_start = sb.take((size_t)cfg->max_batch * 4);
+    m->rm_len = sb.take((size_t)cfg->max_batch * 4);
     m->pooled = sb.take(T * (size_t)cfg->max_batch * H * 4);
-    m->cls_split = m->bf16 ? sb.take(T * (size_t)cfg->max_batch * 2 * H * 2) : 0;
+    m->cls_split = sb.take(T * (size_t)cfg->max_batch * H * 4);   // [hi | lo] bf16 halves, or float32 rows in the validation mode
     m->workspace_bytes = sb.off;
     m->task_loaded.assign(T, 0);
     m->last_enabled.assign(T, 0);
@@ -634,11 +645,14 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
             ob = bf ? (void*)(ws + m->pp_b[pp]) : nullptr;
         }
     };
+    RowMap rm{(int32_t*)(ws + m->rm_n), (int32_t*)(ws + m->rm_src), (int32_t*)(ws + m->rm_rowof), (int32_t*)(ws + m->rm_start),
+              (int32_t*)(ws + m->rm_len)};
     float* cur_f;
     void* cur_b;
     trunk_out(0, 0, cur_f, cur_b);
     L.begin(MT_K_EMBED);
-    L.check(launch_embed_ln(d_input_ids, B, S, H, m->cfg.vocab, W + m->w_word, W + m->w_pos, W + m->w_type, bf ? 1 : 0,
+    L.check(launch_build_row_map(d_attn_mask, B, S, rm, L.st));
+    L.check(launch_embed_ln(d_input_ids, rm.src, rm.n_rows, B, S, H, m->cfg.vocab, W + m->w_word, W + m->w_pos, W + m->w_type, bf ? 1 : 0,
                             (const float*)(W + m->w_embg), (const float*)(W + m->w_embb), m->cfg.ln_eps, cur_f,
                             (bf16_t*)cur_b, L.st));
     L.end();
@@ -650,7 +664,7 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
         void* nb;
         trunk_out(l + 1, (l + 1) & 1, nf, nb);
         io[0] = LayerIO{cur_f, cur_b, &m->trunk[l], &m->trunk_scr, nf, nb};
-        run_layer_group(L, io, d_attn_mask, B, S);
+        run_layer_group(L, io, rm, B, S);
         cur_f = nf;
         cur_b = nb;
     }
@@ -678,7 +692,7 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
         }
         for (size_t lo = 0; lo < all.size(); lo += kMaxGroup) {
             std::vector<LayerIO> part(all.begin() + lo, all.begin() + std::min(all.size(), lo + (size_t)kMaxGroup));
-            run_layer_group(L, part, d_attn_mask, B, S);
+            run_layer_group(L, part, rm, B, S);
         }
     }
 
@@ -700,8 +714,9 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
                                             : (const float*)(ws + m->tap_f[m->tap_of_layer[d.fork_layer]]);
             float* pooled = (float*)(ws + m->pooled + (size_t)t * m->cfg.max_batch * H * 4);
             sg.x[i] = z;
-            sg.out[i] = bf ? (bf16_t*)(ws + m->cls_split + (size_t)t * m->cfg.max_batch * 2 * H * 2) : nullptr;
-            g.A[i] = bf ? (const void*)sg.out[i] : (const void*)z;   // fp32 mode: row b = token 0 of sequence b, lda = S*H
+            sg.out[i] = bf ? (bf16_t*)(ws + m->cls_split + (size_t)t * m->cfg.max_batch * 2 * H * 2)
+                           : (bf16_t*)(ws + m->cls_split + (size_t)t * m->cfg.max_batch * H * 4);   // fp32 mode: float32 rows
+            g.A[i] = bf ? (const void*)sg.out[i] : (const void*)(ws + m->cls_split + (size_t)t * m->cfg.max_batch * H * 4);
             g.W[i] = W + m->taskw[t].Wp;
             g.bias[i] = (const float*)(W + m->taskw[t].bp);
             g.C[i] = pooled;
@@ -715,11 +730,12 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
         }
         L.begin(MT_K_POOL);
         if (bf) {
-            L.check(launch_cls_split(sg, n, B, H, (int64_t)S * H, L.st));
-            GemmShape s{n, B, H, 2 * H, 2 * H, H, 0, ACT_TANH, 1};
+            L.check(launch_cls_split(sg, n, B, H, rm.seq_start, S, B * S, L.st));
+            GemmShape s{n, B, H, 2 * H, 2 * H, H, 0, ACT_TANH, 1, nullptr};
             L.check(launch_gemm_bf16(g, s, L.st));
         } else {
-            GemmShape s{n, B, H, H, (int64_t)S * H, H, 0, ACT_TANH, 1};
+            L.check(launch_gather_rows(sg, n, B, H, rm.seq_start, S, B * S, L.st));
+            GemmShape s{n, B, H, H, H, H, 0, ACT_TANH, 1, nullptr};
             L.check(launch_gemm_f32(g, s, 0, L.st));
         }
         L.check(launch_classifier(cg, n, B, H, maxC, bf ? 1 : 0, m->C_tot, L.st));
@@ -749,7 +765,8 @@ int mt_read_hidden(mt_model* m, int32_t task, int32_t layer, float* d_out, size_
         const mt_task_desc& d = m->tasks[task];
         src = d.n_layers > 0 ? m->d_ws + m->task_xf[task] : m->d_ws + m->tap_f[m->tap_of_layer[d.fork_layer]];
     }
-    hipError_t e = hipMemcpyAsync(d_out, src, bytes, hipMemcpyDeviceToDevice, static_cast<hipStream_t>(hip_stream));
+    hipError_t e = launch_unpack_rows((const float*)src, (const int32_t*)(m->d_ws + m->rm_rowof), m->last_B * m->last_S, m->cfg.hidden,
+                                      d_out, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(m, MT_ERR_HIP, "mt_read_hidden: %s", hipGetErrorString(e));
     return MT_OK;
 }
@@ -807,7 +824,7 @@ int mt_op_linear(int32_t precision, const void* d_A, int64_t lda, const void* d_
     g.bias[0] = d_bias;
     g.residual[0] = d_residual;
     g.N[0] = N;
-    GemmShape s{1, M, N, K, lda, ldc, ldc, act_kind, (precision == MT_BF16) ? (out_f32 ? 1 : 0) : 1};
+    GemmShape s{1, M, N, K, lda, ldc, ldc, act_kind, (precision == MT_BF16) ? (out_f32 ? 1 : 0) : 1, nullptr};
     hipError_t e = precision == MT_BF16 ? launch_gemm_bf16(g, s, static_cast<hipStream_t>(hip_stream))
                                         : launch_gemm_f32(g, s, 0, static_cast<hipStream_t>(hip_stream));
     if (e == hipErrorInvalidValue) return MT_ERR_SHAPE;
@@ -834,7 +851,7 @@ int mt_op_linear_batched(int32_t precision, int32_t G, const void* d_A, int64_t 
         g.residual[i] = d_residual ? d_residual + (size_t)i * strideRes : nullptr;
         g.N[i] = N;
     }
-    GemmShape s{G, M, N, K, lda, ldc, ldc, act_kind, of32};
+    GemmShape s{G, M, N, K, lda, ldc, ldc, act_kind, of32, nullptr};
     hipError_t e = bf ? launch_gemm_bf16(g, s, static_cast<hipStream_t>(hip_stream))
                       : launch_gemm_f32(g, s, 0, static_cast<hipStream_t>(hip_stream));
     if (e == hipErrorInvalidValue) return MT_ERR_SHAPE;
@@ -851,8 +868,8 @@ int mt_op_attention(int32_t precision, const void* d_qkv, const int32_t* d_mask,
     g.qkv[0] = d_qkv;
     g.ctx[0] = d_ctx;
     hipError_t e = precision == MT_BF16
-                       ? launch_attention_bf16(g, 1, d_mask, batch, seq, hidden, heads, static_cast<hipStream_t>(hip_stream))
-                       : launch_attention_f32(g, 1, d_mask, batch, seq, hidden, heads, static_cast<hipStream_t>(hip_stream));
+                       ? launch_attention_bf16(g, 1, d_mask, nullptr, nullptr, batch, seq, hidden, heads, static_cast<hipStream_t>(hip_stream))
+                       : launch_attention_f32(g, 1, d_mask, nullptr, nullptr, batch, seq, hidden, heads, static_cast<hipStream_t>(hip_stream));
     if (e == hipErrorInvalidValue) return MT_ERR_SHAPE;
     return e == hipSuccess ? MT_OK : MT_ERR_HIP;
 }
@@ -869,7 +886,7 @@ int mt_op_layernorm(const float* d_x, const float* d_gamma, const float* d_beta,
     g.beta[0] = d_beta;
     g.out_f32[0] = d_out_f32;
     g.out_bf16[0] = static_cast<bf16_t*>(d_out_bf16);
-    hipError_t e = launch_layernorm(g, 1, M, H, eps, static_cast<hipStream_t>(hip_stream));
+    hipError_t e = launch_layernorm(g, 1, M, nullptr, H, eps, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MT_OK : MT_ERR_HIP;
 }
 

@@ -1,4 +1,5 @@
-// Row kernels: embedding sum + LayerNorm, and LayerNorm of a pre-summed row.
+// Row kernels: the padding-free row map, embedding sum + LayerNorm, LayerNorm of a pre-summed row,
+// pooler input split and classifier.
 // One 64-lane wavefront owns one row; statistics are float32 with a two-pass variance taken from
 // registers, reductions are wavefront shuffles.  Both kernels are HBM-bound: each row is read once
 // and written once (float32 and, for the matrix-core path, a bfloat16 copy).
@@ -58,11 +59,12 @@ __device__ inline void ln_finish_store(float4 (&v)[NV], int lane, int H, const f
 
 // H == NV*256: the whole row lives in registers.
 template <int NV>
-__global__ __launch_bounds__(256) void layernorm_fast(LnGroup g, int M, int H, float eps)
+__global__ __launch_bounds__(256) void layernorm_fast(LnGroup g, int M, const int32_t* __restrict__ d_M, int H, float eps)
 {
     const int grp = blockIdx.y;
     const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
+    if (d_M) M = min(M, *d_M);
     if (row >= M) return;
     const float* x = g.x[grp] + (size_t)row * H;
     float4 v[NV];
@@ -74,11 +76,12 @@ __global__ __launch_bounds__(256) void layernorm_fast(LnGroup g, int M, int H, f
 }
 
 // Any H: three strided passes over the row (it stays in cache between passes).
-__global__ __launch_bounds__(256) void layernorm_any(LnGroup g, int M, int H, float eps)
+__global__ __launch_bounds__(256) void layernorm_any(LnGroup g, int M, const int32_t* __restrict__ d_M, int H, float eps)
 {
     const int grp = blockIdx.y;
     const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
+    if (d_M) M = min(M, *d_M);
     if (row >= M) return;
     const float* x = g.x[grp] + (size_t)row * H;
     float s = 0.f;
@@ -99,17 +102,20 @@ __global__ __launch_bounds__(256) void layernorm_any(LnGroup g, int M, int H, fl
 }
 
 template <typename TE, int NV>
-__global__ __launch_bounds__(256) void embed_ln_fast(const int32_t* ids, int M, int S, int H, int vocab,
+__global__ __launch_bounds__(256) void embed_ln_fast(const int32_t* ids, const int32_t* __restrict__ src,
+                                                     const int32_t* __restrict__ d_M, int M, int S, int H, int vocab,
                                                      const TE* word, const TE* pos, const TE* type,
                                                      const float* gamma, const float* beta, float eps,
                                                      float* out_f32, __bf16* out_bf16)
 {
     const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
+    if (d_M) M = min(M, *d_M);
     if (row >= M) return;
-    int id = ids[row];
+    const int p_idx = src ? src[row] : row;
+    int id = ids[p_idx];
     id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
-    const int s = row % S;
+    const int s = p_idx % S;
     const TE* w = word + (size_t)id * H;
     const TE* p = pos + (size_t)s * H;
     float4 v[NV];
@@ -124,17 +130,20 @@ __global__ __launch_bounds__(256) void embed_ln_fast(const int32_t* ids, int M, 
 }
 
 template <typename TE>
-__global__ __launch_bounds__(256) void embed_ln_any(const int32_t* ids, int M, int S, int H, int vocab,
+__global__ __launch_bounds__(256) void embed_ln_any(const int32_t* ids, const int32_t* __restrict__ src,
+                                                    const int32_t* __restrict__ d_M, int M, int S, int H, int vocab,
                                                     const TE* word, const TE* pos, const TE* type,
                                                     const float* gamma, const float* beta, float eps,
                                                     float* out_f32, __bf16* out_bf16)
 {
     const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
+    if (d_M) M = min(M, *d_M);
     if (row >= M) return;
-    int id = ids[row];
+    const int p_idx = src ? src[row] : row;
+    int id = ids[p_idx];
     id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
-    const int sidx = row % S;
+    const int sidx = p_idx % S;
     const TE* w = word + (size_t)id * H;
     const TE* p = pos + (size_t)sidx * H;
     float s = 0.f;
@@ -155,29 +164,95 @@ __global__ __launch_bounds__(256) void embed_ln_any(const int32_t* ids, int M, i
 }
 
 template <typename TE>
-hipError_t embed_dispatch(const int32_t* ids, int B, int S, int H, int vocab, const TE* word, const TE* pos,
+hipError_t embed_dispatch(const int32_t* ids, const int32_t* src, const int32_t* d_M, int B, int S, int H, int vocab, const TE* word, const TE* pos,
                           const TE* type, const float* gamma, const float* beta, float eps, float* of, __bf16* ob,
                           hipStream_t st)
 {
     const int M = B * S;
     dim3 grid((M + kRowsPerBlock - 1) / kRowsPerBlock), block(256);
     if (H == 768)
-        hipLaunchKernelGGL((embed_ln_fast<TE, 3>), grid, block, 0, st, ids, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+        hipLaunchKernelGGL((embed_ln_fast<TE, 3>), grid, block, 0, st, ids, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
     else if (H == 1024)
-        hipLaunchKernelGGL((embed_ln_fast<TE, 4>), grid, block, 0, st, ids, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+        hipLaunchKernelGGL((embed_ln_fast<TE, 4>), grid, block, 0, st, ids, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
     else if (H == 256)
-        hipLaunchKernelGGL((embed_ln_fast<TE, 1>), grid, block, 0, st, ids, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+        hipLaunchKernelGGL((embed_ln_fast<TE, 1>), grid, block, 0, st, ids, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
     else if (H == 512)
-        hipLaunchKernelGGL((embed_ln_fast<TE, 2>), grid, block, 0, st, ids, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+        hipLaunchKernelGGL((embed_ln_fast<TE, 2>), grid, block, 0, st, ids, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
     else
-        hipLaunchKernelGGL((embed_ln_any<TE>), grid, block, 0, st, ids, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+        hipLaunchKernelGGL((embed_ln_any<TE>), grid, block, 0, st, ids, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
     return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void cls_split_kernel(SplitGroup g, int H, int64_t ldx)
+// Pass 1 of the row map, one workgroup per sequence: rank of every real token inside its sequence
+// (written into row_of, -1 for padding) and the sequence's count of real tokens.
+__global__ __launch_bounds__(256) void row_rank_kernel(const int32_t* __restrict__ mask, int S, int32_t* __restrict__ row_of,
+                                                       int32_t* __restrict__ seq_len)
+{
+    __shared__ int wave_cnt[4];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int base = 0;
+    for (int c0 = 0; c0 < S; c0 += 256) {
+        const int s = c0 + tid;
+        const bool flag = s < S && mask[(size_t)b * S + s] != 0;
+        const unsigned long long bal = __ballot(flag);
+        const int lane_rank = __popcll(bal & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_cnt[wave] = __popcll(bal);
+        __syncthreads();
+        int woff = 0, total = 0;
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) woff += wave_cnt[w];
+            total += wave_cnt[w];
+        }
+        if (s < S) row_of[(size_t)b * S + s] = flag ? base + woff + lane_rank : -1;
+        base += total;
+        __syncthreads();
+    }
+    if (tid == 0) seq_len[b] = base;
+}
+
+// Pass 2: sequence b starts at the sum of the counts before it; ranks become global rows.
+__global__ __launch_bounds__(256) void row_place_kernel(int B, int S, int32_t* __restrict__ row_of,
+                                                        const int32_t* __restrict__ seq_len, int32_t* __restrict__ seq_start,
+                                                        int32_t* __restrict__ src, int32_t* __restrict__ n_rows)
+{
+    __shared__ int part[4];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int acc = 0;
+    for (int i = tid; i < b; i += 256) acc += seq_len[i];
+    acc = wave_sum_int(acc);
+    if (lane == 0) part[wave] = acc;
+    __syncthreads();
+    const int start = part[0] + part[1] + part[2] + part[3];
+    if (tid == 0) {
+        seq_start[b] = start;
+        if (b == B - 1) *n_rows = start + seq_len[b];
+    }
+    for (int s = tid; s < S; s += 256) {
+        const size_t p = (size_t)b * S + s;
+        const int r = row_of[p];
+        if (r >= 0) {
+            row_of[p] = start + r;
+            src[start + r] = (int)p;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void unpack_rows_kernel(const float* __restrict__ x, const int32_t* __restrict__ row_of, int n_pos,
+                                                          int H, float* __restrict__ out)
+{
+    const int p = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (p >= n_pos) return;
+    const int r = row_of[p];
+    for (int i = lane; i < H; i += 64) out[(size_t)p * H + i] = r >= 0 ? x[(size_t)r * H + i] : 0.f;
+}
+
+__global__ __launch_bounds__(256) void cls_split_kernel(SplitGroup g, int H, const int32_t* __restrict__ seq_start,
+                                                        int rows_per_seq, int max_rows)
 {
     const int grp = blockIdx.y, b = blockIdx.x;
-    const float* x = g.x[grp] + (size_t)b * ldx;
+    const int row = min(seq_start ? seq_start[b] : b * rows_per_seq, max_rows - 1);
+    const float* x = g.x[grp] + (size_t)row * H;
     __bf16* out = reinterpret_cast<__bf16*>(g.out[grp]) + (size_t)b * 2 * H;
     for (int i = threadIdx.x; i < H; i += 256) {
         const float v = x[i];
@@ -185,6 +260,16 @@ __global__ __launch_bounds__(256) void cls_split_kernel(SplitGroup g, int H, int
         out[i] = hi;
         out[H + i] = (__bf16)(v - (float)hi);
     }
+}
+
+__global__ __launch_bounds__(256) void gather_rows_kernel(SplitGroup g, int H, const int32_t* __restrict__ seq_start,
+                                                          int rows_per_seq, int max_rows)
+{
+    const int grp = blockIdx.y, b = blockIdx.x;
+    const int row = min(seq_start ? seq_start[b] : b * rows_per_seq, max_rows - 1);
+    const float* x = g.x[grp] + (size_t)row * H;
+    float* out = reinterpret_cast<float*>(g.out[grp]) + (size_t)b * H;
+    for (int i = threadIdx.x; i < H; i += 256) out[i] = x[i];
 }
 
 template <typename TW>
@@ -204,10 +289,36 @@ __global__ __launch_bounds__(256) void classifier_kernel(ClsGroup g, int B, int 
 
 }  // namespace
 
-hipError_t launch_cls_split(const SplitGroup& g, int G, int B, int H, int64_t ldx, hipStream_t stream)
+hipError_t launch_cls_split(const SplitGroup& g, int G, int B, int H, const int32_t* seq_start, int rows_per_seq, int max_rows,
+                            hipStream_t stream)
 {
     if (G <= 0 || B <= 0) return hipSuccess;
-    hipLaunchKernelGGL(cls_split_kernel, dim3(B, G), dim3(256), 0, stream, g, H, ldx);
+    hipLaunchKernelGGL(cls_split_kernel, dim3(B, G), dim3(256), 0, stream, g, H, seq_start, rows_per_seq, max_rows);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(const SplitGroup& g, int G, int B, int H, const int32_t* seq_start, int rows_per_seq, int max_rows,
+                              hipStream_t stream)
+{
+    if (G <= 0 || B <= 0) return hipSuccess;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3(B, G), dim3(256), 0, stream, g, H, seq_start, rows_per_seq, max_rows);
+    return hipGetLastError();
+}
+
+hipError_t launch_build_row_map(const int32_t* mask, int B, int S, const RowMap& map, hipStream_t stream)
+{
+    if (B <= 0 || S <= 0) return hipSuccess;
+    hipLaunchKernelGGL(row_rank_kernel, dim3(B), dim3(256), 0, stream, mask, S, map.row_of, map.seq_len);
+    hipLaunchKernelGGL(row_place_kernel, dim3(B), dim3(256), 0, stream, B, S, map.row_of, map.seq_len, map.seq_start, map.src,
+                       map.n_rows);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack_rows(const float* x, const int32_t* row_of, int n_pos, int H, float* out, hipStream_t stream)
+{
+    if (n_pos <= 0) return hipSuccess;
+    hipLaunchKernelGGL(unpack_rows_kernel, dim3((n_pos + kRowsPerBlock - 1) / kRowsPerBlock), dim3(256), 0, stream, x, row_of,
+                       n_pos, H, out);
     return hipGetLastError();
 }
 
@@ -219,28 +330,28 @@ hipError_t launch_classifier(const ClsGroup& g, int G, int B, int H, int maxC, i
     return hipGetLastError();
 }
 
-hipError_t launch_layernorm(const LnGroup& g, int G, int M, int H, float eps, hipStream_t stream)
+hipError_t launch_layernorm(const LnGroup& g, int G, int M, const int32_t* d_M, int H, float eps, hipStream_t stream)
 {
     if (G <= 0 || M <= 0) return hipSuccess;
     dim3 grid((M + kRowsPerBlock - 1) / kRowsPerBlock, G), block(256);
-    if (H == 768) hipLaunchKernelGGL((layernorm_fast<3>), grid, block, 0, stream, g, M, H, eps);
-    else if (H == 1024) hipLaunchKernelGGL((layernorm_fast<4>), grid, block, 0, stream, g, M, H, eps);
-    else if (H == 512) hipLaunchKernelGGL((layernorm_fast<2>), grid, block, 0, stream, g, M, H, eps);
-    else if (H == 256) hipLaunchKernelGGL((layernorm_fast<1>), grid, block, 0, stream, g, M, H, eps);
-    else hipLaunchKernelGGL(layernorm_any, grid, block, 0, stream, g, M, H, eps);
+    if (H == 768) hipLaunchKernelGGL((layernorm_fast<3>), grid, block, 0, stream, g, M, d_M, H, eps);
+    else if (H == 1024) hipLaunchKernelGGL((layernorm_fast<4>), grid, block, 0, stream, g, M, d_M, H, eps);
+    else if (H == 512) hipLaunchKernelGGL((layernorm_fast<2>), grid, block, 0, stream, g, M, d_M, H, eps);
+    else if (H == 256) hipLaunchKernelGGL((layernorm_fast<1>), grid, block, 0, stream, g, M, d_M, H, eps);
+    else hipLaunchKernelGGL(layernorm_any, grid, block, 0, stream, g, M, d_M, H, eps);
     return hipGetLastError();
 }
 
-hipError_t launch_embed_ln(const int32_t* ids, int B, int S, int H, int vocab, const void* word, const void* pos,
+hipError_t launch_embed_ln(const int32_t* ids, const int32_t* src, const int32_t* d_M, int B, int S, int H, int vocab, const void* word, const void* pos,
                            const void* type, int emb_bf16, const float* gamma, const float* beta, float eps,
                            float* out_f32, bf16_t* out_bf16, hipStream_t stream)
 {
     if (B * S <= 0) return hipSuccess;
     __bf16* ob = reinterpret_cast<__bf16*>(out_bf16);
     if (emb_bf16)
-        return embed_dispatch<__bf16>(ids, B, S, H, vocab, (const __bf16*)word, (const __bf16*)pos, (const __bf16*)type,
+        return embed_dispatch<__bf16>(ids, src, d_M, B, S, H, vocab, (const __bf16*)word, (const __bf16*)pos, (const __bf16*)type,
                                       gamma, beta, eps, out_f32, ob, stream);
-    return embed_dispatch<float>(ids, B, S, H, vocab, (const float*)word, (const float*)pos, (const float*)type,
+    return embed_dispatch<float>(ids, src, d_M, B, S, H, vocab, (const float*)word, (const float*)pos, (const float*)type,
                                  gamma, beta, eps, out_f32, ob, stream);
 }
 
