@@ -146,7 +146,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, MINW) void gemm_bf16_kernel(
     //      workgroup id -> (problem, row-tile, col-tile); workgroups beyond the last tile leave at once
     const int M = s.d_M ? min(s.M, *s.d_M) : s.M;
     const int tiles_m = (M + BM - 1) / BM;
-    const int total = s.G * tiles_m * tiles_n;
+    const int total = s.G * s.splits * tiles_m * tiles_n;
     if ((int)blockIdx.x >= total) return;
     int tile;
     {
@@ -156,8 +156,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, MINW) void gemm_bf16_kernel(
         tile = x * q + (x < r ? x : r) + i;
     }
     const int per_problem = tiles_m * tiles_n;
-    const int grp = tile / per_problem;
-    const int t = tile - grp * per_problem;
+    const int gs = tile / per_problem;            // (problem, K range) pair; consecutive K ranges of a problem stay on one XCD
+    const int grp = gs / s.splits, split = gs - grp * s.splits;
+    const int t = tile - gs * per_problem;
     int tm, tn;
     {
         const int band_sz = kBand * tiles_n;
@@ -169,8 +170,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, MINW) void gemm_bf16_kernel(
     }
     const int m0 = tm * BM, n0 = tn * BN;
 
-    const unsigned char* __restrict__ A = static_cast<const unsigned char*>(g.A[grp]);
-    const unsigned char* __restrict__ W = static_cast<const unsigned char*>(g.W[grp]);
+    const int KT = s.K / BK / s.splits;           // slices of this workgroup's K range
+    const unsigned char* __restrict__ A = static_cast<const unsigned char*>(g.A[grp]) + (size_t)split * KT * (BK * 2);
+    const unsigned char* __restrict__ W = static_cast<const unsigned char*>(g.W[grp]) + (size_t)split * KT * (BK * 2);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -207,7 +209,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, MINW) void gemm_bf16_kernel(
         fw_off[kk] = (BM + wn0) * ROW_BYTES + o;
     }
 
-    const int KT = s.K / BK;
 
     // issue load instructions [part*LPP, part*LPP+LPP) of slice kt_ (caller guarantees kt_ < KT)
 #define MT_ISSUE_PART(kt_, part_)                                                                                  \
@@ -323,7 +324,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, MINW) void gemm_bf16_kernel(
     float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
     if (g.bias[grp] && n_ok) bv = *reinterpret_cast<const float4*>(g.bias[grp] + n);
     const float* __restrict__ res = g.residual[grp];
-    unsigned char* __restrict__ Cout = static_cast<unsigned char*>(g.C[grp]);     // hoisted: read the argument block once
+    unsigned char* __restrict__ Cout = static_cast<unsigned char*>(g.C[grp]) + (size_t)split * s.split_stride * 4;   // hoisted
     const size_t ldc_b = (size_t)s.ldc * (OUT_F32 ? 4 : 2), ldr_b = (size_t)s.ldr * 4;
     constexpr int NIT = RPP / ROWS_PER_INST;                 // read-back iterations per pass
     constexpr int UNR = NIT >= 4 ? 4 : 1;                      // LDS reads in flight per lane
@@ -406,7 +407,8 @@ hipError_t launch_one(const GemmGroup& g, const GemmShape& s, hipStream_t stream
 {
     using Cfg = GemmCfg<BM, BN, WAVES_M, WAVES_N, BK, STAGES>;
     const int tiles_m = (s.M + BM - 1) / BM, tiles_n = (s.N + BN - 1) / BN;
-    const int total = s.G * tiles_m * tiles_n;
+    const int total = s.G * s.splits * tiles_m * tiles_n;
+    if (s.K % (BK * s.splits) != 0) return hipErrorInvalidValue;
     auto kfn = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, OUT_F32, ACT>;
     static bool attr_set = false;
     if (Cfg::LDS_BYTES > 64 * 1024 && !attr_set) {
@@ -443,6 +445,7 @@ int g_gemm_bf16_tile_override = 0;   // 0 = choose by shape; set through mt_debu
 hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t stream)
 {
     if (s.G <= 0 || s.M <= 0 || s.N <= 0) return hipSuccess;
+    if (s.splits < 1 || (s.splits > 1 && (!s.out_f32 || s.act != ACT_NONE || g.bias[0] || g.residual[0]))) return hipErrorInvalidValue;
     if (s.K % 64 != 0 || s.K < 64 || s.N % 4 != 0 || s.lda % 8 != 0 || s.ldc % 4 != 0 || s.ldr % 4 != 0 ||
         s.G > kMaxGroup || (!s.out_f32 && g.residual[0] != nullptr))
         return hipErrorInvalidValue;
@@ -451,16 +454,18 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
         return hipErrorInvalidValue;
     int sel = g_gemm_bf16_tile_override;
     if (sel == 0) {
-        // Shape rule from measurements on MI355X (M = 4096, BERT-base widths, 1 and 8 problems):
-        // wide outputs or very many tiles -> 256x256 with 8 wavefronts (least L2 traffic per flop), except
-        // the GELU epilogue, whose vector work hides better behind a second resident workgroup (256x128);
-        // narrow outputs -> 128x128 with two workgroups per CU, K slices of 64 when there are enough tiles
-        // to fill the chip several times, else the deeper 4-stage ring of 32-wide slices.
-        const long t256 = (long)s.G * ((s.M + 255) / 256) * ((s.N + 255) / 256);
+        // Shape rule from measurements on MI355X (BERT-base widths, 1 and 8 problems, 2304 and 4096 rows).
+        // The row bound s.M over-counts when padding is dropped on the device, so the rule keys on the
+        // number of 256x256 tiles the bound implies and errs towards the smaller tile when few.
+        //   many tiles: 256x256 with 8 wavefronts (least L2 traffic per flop); the GELU epilogue's vector
+        //   work instead prefers 8 wavefronts of 64x64 on a 256x128 tile, two workgroups per CU;
+        //   few tiles (single problem): 128x128, two or three workgroups per CU.
+        const long t256 = (long)s.G * s.splits * ((s.M + 255) / 256) * ((s.N + 255) / 256);
         const bool gelu = s.act == ACT_GELU_ERF || s.act == ACT_GELU_TANH;
-        if (s.N >= 2048 || t256 >= 2048) sel = (gelu && t256 >= 1024) ? 2 : 9;
-        else if (t256 * 4 >= 1024) sel = 6;
-        else sel = 1;
+        if (t256 >= 256) sel = gelu ? 11 : 9;
+        else if (s.K / s.splits >= 2048) sel = 1;
+        else if (s.N >= 2048) sel = 6;
+        else sel = 12;
     }
     switch (sel) {
         case 2: return launch_cfg<256, 128, 2, 2, 32, 3, 2>(g, s, stream);   // 72 KB LDS: two workgroups per CU

@@ -31,6 +31,9 @@ struct GemmShape {
     int32_t act;            // ActKind
     int32_t out_f32;        // 1: C is float32, 0: C has the activation element type
     const int32_t* d_M;     // optional device scalar: rows actually present (<= M); tiles beyond it exit at once
+    int32_t splits;         // bf16 path, >= 1: K is cut into `splits` equal ranges, range p of problem g writing its
+                            // partial product (float32, no epilogue) to C_g + p * split_stride elements
+    int64_t split_stride;
 };
 
 // bf16 x bf16 -> fp32 accumulate on the matrix cores.  Needs K % 64 == 0, lda % 8 == 0, 16-byte aligned A/W rows.
@@ -63,14 +66,17 @@ hipError_t launch_attention_f32(const AttnGroup& g, int G, const int32_t* mask, 
                                 const int32_t* seq_len, int B, int S, int H, int A, hipStream_t stream);
 
 struct LnGroup {
-    const float* x[kMaxGroup];      // [M][H] fp32, already bias+residual summed
+    const float* x[kMaxGroup];      // [n_parts][M][H] fp32: the row to normalise is sum_p x[p] (+ bias) (+ residual)
+    const float* bias[kMaxGroup];      // [H], may be null
+    const float* residual[kMaxGroup];  // [M][H] fp32, may be null
     const float* gamma[kMaxGroup];
     const float* beta[kMaxGroup];
     float* out_f32[kMaxGroup];      // may be null
     bf16_t* out_bf16[kMaxGroup];    // may be null
 };
-// d_M (optional device scalar) = rows actually present (<= M)
-hipError_t launch_layernorm(const LnGroup& g, int G, int M, const int32_t* d_M, int H, float eps, hipStream_t stream);
+// d_M (optional device scalar) = rows actually present (<= M); n_parts partial sums part_stride elements apart
+hipError_t launch_layernorm(const LnGroup& g, int G, int M, const int32_t* d_M, int H, float eps, int n_parts, int64_t part_stride,
+                            hipStream_t stream);
 
 // X0[r] = LN(word[ids[p]] + pos[p % S] + type[0]) with p = src[r] for the kept rows r < *d_M (p = r and all
 // B*S rows when src is null); tables are bf16 (emb_bf16 != 0) or fp32.

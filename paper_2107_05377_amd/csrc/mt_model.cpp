@@ -44,6 +44,7 @@ struct TaskW {
 };
 struct Scratch {   // byte offsets into the workspace; one set for the trunk and one per task
     size_t qkv, ctx, y, x1f, x1b, u;
+    int y_parts;   // y holds this many [M][H] float32 partial products (K ranges of a split contraction)
 };
 struct ProfRec {
     int klass;
@@ -136,12 +137,13 @@ LayerW layout_layer(Bump& b, size_t H, size_t F, size_t esz)
     return L;
 }
 
-Scratch layout_scratch(Bump& b, size_t M, size_t H, size_t F, size_t esz, bool bf16)
+Scratch layout_scratch(Bump& b, size_t M, size_t H, size_t F, size_t esz, bool bf16, int y_parts)
 {
     Scratch s;
+    s.y_parts = y_parts;
     s.qkv = b.take(M * 3 * H * esz);
     s.ctx = b.take(M * H * esz);
-    s.y = b.take(M * H * 4);
+    s.y = b.take((size_t)y_parts * M * H * 4);
     s.x1f = b.take(M * H * 4);
     s.x1b = bf16 ? b.take(M * H * 2) : 0;
     s.u = b.take(M * F * esz);
@@ -280,7 +282,7 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& 
         g.C[i] = ws + io[i].scr->qkv;
         g.N[i] = 3 * H;
     }
-    s = GemmShape{n, M, 3 * H, H, H, 3 * H, 0, ACT_NONE, bf ? 0 : 1, rm.n_rows};
+    s = GemmShape{n, M, 3 * H, H, H, 3 * H, 0, ACT_NONE, bf ? 0 : 1, rm.n_rows, 1, 0};
     L.gemm(MT_K_GEMM_QKV, g, s, false);
 
     // attention
@@ -295,29 +297,43 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& 
                : launch_attention_f32(ag, n, nullptr, rm.seq_start, rm.seq_len, B, S, H, A, L.st));
     L.end();
 
-    // output projection + bias + residual -> y (fp32), then LayerNorm -> x1
+    // A contraction with few output tiles (one problem, narrow output) is cut along K into equal
+    // ranges whose float32 partial products the following LayerNorm adds up in a fixed order.
+    auto pick_splits = [&](int K, int N, int max_splits) {
+        if (!bf || n != 1 || io[0].scr->y_parts < 2) return 1;
+        const long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+        if (tiles128 >= 256) return 1;
+        int sp = std::min(max_splits, io[0].scr->y_parts);
+        while (sp > 1 && K % (64 * sp) != 0) sp >>= 1;
+        return sp;
+    };
+
+    // output projection -> y (fp32 partial products), then LayerNorm(y + bias + residual) -> x1
+    const int sp_o = pick_splits(H, H, 2);
     for (int i = 0; i < n; ++i) {
         g.A[i] = ws + io[i].scr->ctx;
         g.W[i] = W + io[i].w->Wo;
-        g.bias[i] = (const float*)(W + io[i].w->bo);
-        g.residual[i] = io[i].in_f;
+        g.bias[i] = nullptr;
+        g.residual[i] = nullptr;
         g.C[i] = ws + io[i].scr->y;
         g.N[i] = H;
     }
-    s = GemmShape{n, M, H, H, H, H, H, ACT_NONE, 1, rm.n_rows};
+    s = GemmShape{n, M, H, H, H, H, 0, ACT_NONE, 1, rm.n_rows, sp_o, (int64_t)m->Mmax * H};
     L.gemm(MT_K_GEMM_OUT, g, s, false);
 
     LnGroup lg;
     memset(&lg, 0, sizeof lg);
     for (int i = 0; i < n; ++i) {
         lg.x[i] = (const float*)(ws + io[i].scr->y);
+        lg.bias[i] = (const float*)(W + io[i].w->bo);
+        lg.residual[i] = io[i].in_f;
         lg.gamma[i] = (const float*)(W + io[i].w->ln1g);
         lg.beta[i] = (const float*)(W + io[i].w->ln1b);
         lg.out_f32[i] = (float*)(ws + io[i].scr->x1f);
         lg.out_bf16[i] = bf ? (bf16_t*)(ws + io[i].scr->x1b) : nullptr;
     }
     L.begin(MT_K_LN);
-    L.check(launch_layernorm(lg, n, M, rm.n_rows, H, m->cfg.ln_eps, L.st));
+    L.check(launch_layernorm(lg, n, M, rm.n_rows, H, m->cfg.ln_eps, sp_o, (int64_t)m->Mmax * H, L.st));
     L.end();
 
     // FFN1 + bias + GELU -> u
@@ -329,30 +345,33 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& 
         g.C[i] = ws + io[i].scr->u;
         g.N[i] = F;
     }
-    s = GemmShape{n, M, F, H, H, F, 0, gelu_act, bf ? 0 : 1, rm.n_rows};
+    s = GemmShape{n, M, F, H, H, F, 0, gelu_act, bf ? 0 : 1, rm.n_rows, 1, 0};
     L.gemm(MT_K_GEMM_FFN1, g, s, false);
 
-    // FFN2 + bias + residual -> y, then LayerNorm -> layer output
+    // FFN2 -> y (fp32 partial products), then LayerNorm(y + bias + residual) -> layer output
+    const int sp_f = pick_splits(F, H, 4);
     for (int i = 0; i < n; ++i) {
         g.A[i] = ws + io[i].scr->u;
         g.W[i] = W + io[i].w->W2;
-        g.bias[i] = (const float*)(W + io[i].w->b2);
-        g.residual[i] = (const float*)(ws + io[i].scr->x1f);
+        g.bias[i] = nullptr;
+        g.residual[i] = nullptr;
         g.C[i] = ws + io[i].scr->y;
         g.N[i] = H;
     }
-    s = GemmShape{n, M, H, F, F, H, H, ACT_NONE, 1, rm.n_rows};
+    s = GemmShape{n, M, H, F, F, H, 0, ACT_NONE, 1, rm.n_rows, sp_f, (int64_t)m->Mmax * H};
     L.gemm(MT_K_GEMM_FFN2, g, s, false);
 
     for (int i = 0; i < n; ++i) {
         lg.x[i] = (const float*)(ws + io[i].scr->y);
+        lg.bias[i] = (const float*)(W + io[i].w->b2);
+        lg.residual[i] = (const float*)(ws + io[i].scr->x1f);
         lg.gamma[i] = (const float*)(W + io[i].w->ln2g);
         lg.beta[i] = (const float*)(W + io[i].w->ln2b);
         lg.out_f32[i] = io[i].out_f;
         lg.out_bf16[i] = bf ? (bf16_t*)io[i].out_b : nullptr;
     }
     L.begin(MT_K_LN);
-    L.check(launch_layernorm(lg, n, M, rm.n_rows, H, m->cfg.ln_eps, L.st));
+    L.check(launch_layernorm(lg, n, M, rm.n_rows, H, m->cfg.ln_eps, sp_f, (int64_t)m->Mmax * H, L.st));
     L.end();
 }
 
@@ -450,10 +469,10 @@ int mt_create(const mt_config* cfg, mt_model** out)
         m->pp_f[i] = sb.take(M * H * 4);
         m->pp_b[i] = m->bf16 ? sb.take(M * H * 2) : 0;
     }
-    m->trunk_scr = layout_scratch(sb, M, H, F, m->esz, m->bf16);
+    m->trunk_scr = layout_scratch(sb, M, H, F, m->esz, m->bf16, m->bf16 ? 4 : 1);
     for (size_t t = 0; t < T; ++t) {
         if (m->tasks[t].n_layers > 0) {
-            m->task_scr.push_back(layout_scratch(sb, M, H, F, m->esz, m->bf16));
+            m->task_scr.push_back(layout_scratch(sb, M, H, F, m->esz, m->bf16, 1));
             m->task_xf.push_back(sb.take(M * H * 4));
             m->task_xb.push_back(m->bf16 ? sb.take(M * H * 2) : 0);
         } else {
@@ -731,11 +750,11 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
         L.begin(MT_K_POOL);
         if (bf) {
             L.check(launch_cls_split(sg, n, B, H, rm.seq_start, S, B * S, L.st));
-            GemmShape s{n, B, H, 2 * H, 2 * H, H, 0, ACT_TANH, 1, nullptr};
+            GemmShape s{n, B, H, 2 * H, 2 * H, H, 0, ACT_TANH, 1, nullptr, 1, 0};
             L.check(launch_gemm_bf16(g, s, L.st));
         } else {
             L.check(launch_gather_rows(sg, n, B, H, rm.seq_start, S, B * S, L.st));
-            GemmShape s{n, B, H, H, H, H, 0, ACT_TANH, 1, nullptr};
+            GemmShape s{n, B, H, H, H, H, 0, ACT_TANH, 1, nullptr, 1, 0};
             L.check(launch_gemm_f32(g, s, 0, L.st));
         }
         L.check(launch_classifier(cg, n, B, H, maxC, bf ? 1 : 0, m->C_tot, L.st));
@@ -824,7 +843,7 @@ int mt_op_linear(int32_t precision, const void* d_A, int64_t lda, const void* d_
     g.bias[0] = d_bias;
     g.residual[0] = d_residual;
     g.N[0] = N;
-    GemmShape s{1, M, N, K, lda, ldc, ldc, act_kind, (precision == MT_BF16) ? (out_f32 ? 1 : 0) : 1, nullptr};
+    GemmShape s{1, M, N, K, lda, ldc, ldc, act_kind, (precision == MT_BF16) ? (out_f32 ? 1 : 0) : 1, nullptr, 1, 0};
     hipError_t e = precision == MT_BF16 ? launch_gemm_bf16(g, s, static_cast<hipStream_t>(hip_stream))
                                         : launch_gemm_f32(g, s, 0, static_cast<hipStream_t>(hip_stream));
     if (e == hipErrorInvalidValue) return MT_ERR_SHAPE;
@@ -851,7 +870,7 @@ int mt_op_linear_batched(int32_t precision, int32_t G, const void* d_A, int64_t 
         g.residual[i] = d_residual ? d_residual + (size_t)i * strideRes : nullptr;
         g.N[i] = N;
     }
-    GemmShape s{G, M, N, K, lda, ldc, ldc, act_kind, of32, nullptr};
+    GemmShape s{G, M, N, K, lda, ldc, ldc, act_kind, of32, nullptr, 1, 0};
     hipError_t e = bf ? launch_gemm_bf16(g, s, static_cast<hipStream_t>(hip_stream))
                       : launch_gemm_f32(g, s, 0, static_cast<hipStream_t>(hip_stream));
     if (e == hipErrorInvalidValue) return MT_ERR_SHAPE;
@@ -886,7 +905,7 @@ int mt_op_layernorm(const float* d_x, const float* d_gamma, const float* d_beta,
     g.beta[0] = d_beta;
     g.out_f32[0] = d_out_f32;
     g.out_bf16[0] = static_cast<bf16_t*>(d_out_bf16);
-    hipError_t e = launch_layernorm(g, 1, M, nullptr, H, eps, static_cast<hipStream_t>(hip_stream));
+    hipError_t e = launch_layernorm(g, 1, M, nullptr, H, eps, 1, 0, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MT_OK : MT_ERR_HIP;
 }
 

@@ -59,7 +59,8 @@ __device__ inline void ln_finish_store(float4 (&v)[NV], int lane, int H, const f
 
 // H == NV*256: the whole row lives in registers.
 template <int NV>
-__global__ __launch_bounds__(256) void layernorm_fast(LnGroup g, int M, const int32_t* __restrict__ d_M, int H, float eps)
+__global__ __launch_bounds__(256) void layernorm_fast(LnGroup g, int M, const int32_t* __restrict__ d_M, int H, float eps,
+                                                      int n_parts, int64_t part_stride)
 {
     const int grp = blockIdx.y;
     const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
@@ -67,35 +68,62 @@ __global__ __launch_bounds__(256) void layernorm_fast(LnGroup g, int M, const in
     if (d_M) M = min(M, *d_M);
     if (row >= M) return;
     const float* x = g.x[grp] + (size_t)row * H;
+    const float* res = g.residual[grp] ? g.residual[grp] + (size_t)row * H : nullptr;
+    const float* bias = g.bias[grp];
     float4 v[NV];
 #pragma unroll
-    for (int i = 0; i < NV; ++i) v[i] = *reinterpret_cast<const float4*>(x + (i * 64 + lane) * 4);
+    for (int i = 0; i < NV; ++i) {
+        const int col = (i * 64 + lane) * 4;
+        v[i] = *reinterpret_cast<const float4*>(x + col);
+        for (int p = 1; p < n_parts; ++p) {                       // fixed order: deterministic
+            const float4 t = *reinterpret_cast<const float4*>(x + (size_t)p * part_stride + col);
+            v[i].x += t.x; v[i].y += t.y; v[i].z += t.z; v[i].w += t.w;
+        }
+        if (bias) {
+            const float4 t = *reinterpret_cast<const float4*>(bias + col);
+            v[i].x += t.x; v[i].y += t.y; v[i].z += t.z; v[i].w += t.w;
+        }
+        if (res) {
+            const float4 t = *reinterpret_cast<const float4*>(res + col);
+            v[i].x += t.x; v[i].y += t.y; v[i].z += t.z; v[i].w += t.w;
+        }
+    }
     float* of = g.out_f32[grp] ? g.out_f32[grp] + (size_t)row * H : nullptr;
     __bf16* ob = g.out_bf16[grp] ? reinterpret_cast<__bf16*>(g.out_bf16[grp]) + (size_t)row * H : nullptr;
     ln_finish_store<NV>(v, lane, H, g.gamma[grp], g.beta[grp], eps, of, ob);
 }
 
 // Any H: three strided passes over the row (it stays in cache between passes).
-__global__ __launch_bounds__(256) void layernorm_any(LnGroup g, int M, const int32_t* __restrict__ d_M, int H, float eps)
+__global__ __launch_bounds__(256) void layernorm_any(LnGroup g, int M, const int32_t* __restrict__ d_M, int H, float eps,
+                                                     int n_parts, int64_t part_stride)
 {
     const int grp = blockIdx.y;
     const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     if (d_M) M = min(M, *d_M);
     if (row >= M) return;
-    const float* x = g.x[grp] + (size_t)row * H;
+    const float* xp = g.x[grp] + (size_t)row * H;
+    const float* res = g.residual[grp] ? g.residual[grp] + (size_t)row * H : nullptr;
+    const float* bias = g.bias[grp];
+    auto value = [&](int i) {
+        float t = xp[i];
+        for (int p = 1; p < n_parts; ++p) t += xp[(size_t)p * part_stride + i];
+        if (bias) t += bias[i];
+        if (res) t += res[i];
+        return t;
+    };
     float s = 0.f;
-    for (int i = lane; i < H; i += 64) s += x[i];
+    for (int i = lane; i < H; i += 64) s += value(i);
     const float mean = wave_sum(s) / (float)H;
     float q = 0.f;
-    for (int i = lane; i < H; i += 64) { float d = x[i] - mean; q += d * d; }
+    for (int i = lane; i < H; i += 64) { float d = value(i) - mean; q += d * d; }
     const float inv = 1.0f / sqrtf(wave_sum(q) / (float)H + eps);
     const float* gamma = g.gamma[grp];
     const float* beta = g.beta[grp];
     float* of = g.out_f32[grp] ? g.out_f32[grp] + (size_t)row * H : nullptr;
     __bf16* ob = g.out_bf16[grp] ? reinterpret_cast<__bf16*>(g.out_bf16[grp]) + (size_t)row * H : nullptr;
     for (int i = lane; i < H; i += 64) {
-        float o = gamma[i] * ((x[i] - mean) * inv) + beta[i];
+        float o = gamma[i] * ((value(i) - mean) * inv) + beta[i];
         if (of) of[i] = o;
         if (ob) ob[i] = (__bf16)o;
     }
@@ -330,15 +358,16 @@ hipError_t launch_classifier(const ClsGroup& g, int G, int B, int H, int maxC, i
     return hipGetLastError();
 }
 
-hipError_t launch_layernorm(const LnGroup& g, int G, int M, const int32_t* d_M, int H, float eps, hipStream_t stream)
+hipError_t launch_layernorm(const LnGroup& g, int G, int M, const int32_t* d_M, int H, float eps, int n_parts, int64_t part_stride,
+                            hipStream_t stream)
 {
     if (G <= 0 || M <= 0) return hipSuccess;
     dim3 grid((M + kRowsPerBlock - 1) / kRowsPerBlock, G), block(256);
-    if (H == 768) hipLaunchKernelGGL((layernorm_fast<3>), grid, block, 0, stream, g, M, d_M, H, eps);
-    else if (H == 1024) hipLaunchKernelGGL((layernorm_fast<4>), grid, block, 0, stream, g, M, d_M, H, eps);
-    else if (H == 512) hipLaunchKernelGGL((layernorm_fast<2>), grid, block, 0, stream, g, M, d_M, H, eps);
-    else if (H == 256) hipLaunchKernelGGL((layernorm_fast<1>), grid, block, 0, stream, g, M, d_M, H, eps);
-    else hipLaunchKernelGGL(layernorm_any, grid, block, 0, stream, g, M, d_M, H, eps);
+    if (H == 768) hipLaunchKernelGGL((layernorm_fast<3>), grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride);
+    else if (H == 1024) hipLaunchKernelGGL((layernorm_fast<4>), grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride);
+    else if (H == 512) hipLaunchKernelGGL((layernorm_fast<2>), grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride);
+    else if (H == 256) hipLaunchKernelGGL((layernorm_fast<1>), grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride);
+    else hipLaunchKernelGGL(layernorm_any, grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride);
     return hipGetLastError();
 }
 
