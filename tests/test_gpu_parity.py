@@ -96,6 +96,30 @@ def test_gemm_bf16_bert_shapes_sampled():
         assert np.abs(out[rows] - ref).max() <= 2e-4 * np.abs(ref).max()
 
 
+def test_gemm_bf16_grouped_and_split_vs_oracle():
+    """The grouped launch (one problem per task): own and shared activations, per-problem weights and bias."""
+    rng = np.random.default_rng(21)
+    G, M, N, K = 3, 200, 264, 128
+    A = bf16_grid(rng.standard_normal((G, M, K)))
+    W = bf16_grid(rng.standard_normal((G, N, K)) * 0.1)
+    bias = rng.standard_normal((G, N)).astype(np.float32)
+    res = rng.standard_normal((G, M, N)).astype(np.float32)
+    for tile in (0, 1, 9, 11):
+        prev = mt.set_gemm_tile(tile)
+        try:
+            out = mt.op_linear_batched(mt.MT_BF16, dev(A, torch.bfloat16), dev(W, torch.bfloat16), dev(bias), dev(res),
+                                       out_f32=True).cpu().numpy()
+            shared = mt.op_linear_batched(mt.MT_BF16, dev(A[1], torch.bfloat16), dev(W, torch.bfloat16), dev(bias),
+                                          act=1).float().cpu().numpy()
+        finally:
+            mt.set_gemm_tile(prev)
+        for g in range(G):
+            ref = oracle.linear(A[g], W[g], bias[g]).astype(np.float64) + res[g]
+            assert np.abs(out[g] - ref).max() <= 2e-4 * np.abs(ref).max()
+            refs = oracle.gelu(oracle.linear(A[1], W[g], bias[g]))
+            assert np.abs(shared[g] - refs).max() <= 2 ** -8 * np.abs(refs).max() + 1e-3
+
+
 def test_gemm_f32_vs_oracle():
     rng = np.random.default_rng(4)
     for (M, N, K) in ((70, 67, 33), (5, 3, 64), (130, 129, 100)):
@@ -257,6 +281,55 @@ def test_bf16_mode_small_model_matches_oracle(stress):
     # smaller batch and sequence than the maximum, on the same model
     ids, mask, _ = ms.make_inputs(spec, batch=2, seq=33, batch_index=5)
     assert np.abs(model.forward(dev(ids), dev(mask)).cpu().numpy() - orc.mt_forward(ids, mask)).max() <= 2e-2
+    model.close()
+
+
+def test_bf16_mode_masks_with_holes_and_extreme_lengths():
+    """Padding-free row order: masks that are not prefixes, a sequence of one token, full sequences."""
+    spec = SMALL
+    tr, tri, tps = _params(spec, True, 0.05)
+    orc = oracle.Oracle(spec, tr, [p for p, _ in tps])
+    model = _load(spec, tr, tri, tps)
+    ids, mask, _ = ms.make_inputs(spec, batch_index=3)
+    mask = mask.copy()
+    mask[0, :] = 1                       # a full sequence
+    mask[1, 1:] = 0                      # a single token
+    mask[2, :] = 1
+    mask[2, [3, 4, 17, 40]] = 0          # holes inside a sequence
+    mask[3, :] = 0
+    mask[3, [0, 5, 43]] = 1              # scattered real tokens, the last position among them
+    ref = orc.mt_forward(ids, mask)
+    got = model.forward(dev(ids), dev(mask)).cpu().numpy()
+    err = np.abs(got - ref).max()
+    say(f"  holes: max |dlogit| {err:.4g}")
+    assert err <= 2e-2
+    # the kept trunk state, put back in [batch, seq] order, matches on every real token and is zero elsewhere
+    _, hidden = orc.mt_forward(ids, mask, want_hidden=True)
+    h = model.read_hidden(-1, 3, *ids.shape).cpu().numpy()
+    real = mask.astype(bool)
+    assert np.abs(h[real] - hidden[3][real]).max() <= 5e-2
+    assert (h[~real] == 0).all()
+    model.close()
+
+
+@pytest.mark.parametrize("name,batch,rows", [("hetero", 64, [0, 33]), ("latency", 8, list(range(8))), ("latency", 1, [0])])
+def test_bf16_other_workloads_sampled(name, batch, rows):
+    """Forks at different trunk layers (a trunk tap per fork, branch stages of shrinking groups) and the
+    small-batch serving shape, in the launch configuration the benchmark uses."""
+    spec = ms.get_config(name)
+    say(f"workload {name}: building weights")
+    tr, tri, tps = _params(spec, False)
+    model = _load(spec, tr, tri, tps, max_batch=batch)
+    assert model.layer_count() == spec.n_trunk_layers + sum(t.n_layers for t in spec.tasks)
+    ids, mask, lengths = ms.make_inputs(spec, batch=batch)
+    got = model.forward(dev(ids), dev(mask)).cpu().numpy()
+    assert np.isfinite(got).all()
+    say("  oracle on rows", rows)
+    ref = oracle.Oracle(spec, tr, [p for p, _ in tps]).mt_forward(ids[rows], mask[rows])
+    err = np.abs(got[rows] - ref).max()
+    n, agree, n_safe, agree_safe = argmax_stats(spec, got[rows], ref)
+    say(f"  max |dlogit| {err:.4g}; argmax agree {agree}/{n}; margin>4e-2: {agree_safe}/{n_safe}")
+    assert err <= 2e-2 and agree_safe == n_safe
     model.close()
 
 
