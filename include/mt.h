@@ -138,7 +138,9 @@ const char* mt_error_name(int code);
 /*
  * Copy the float32 hidden state [batch][seq][hidden] the last mt_forward left for
  *   task < 0 : the trunk after `layer` shared layers (only layers some task forks at are kept);
- *   task >= 0: task's branch output (after its last own layer; `layer` ignored)
+ *   task >= 0: task's branch output after its last own layer, of which only the first token of every
+ *              sequence is computed (the pooler reads nothing else): position 0 holds it, the rest is 0;
+ *              for a task without own layers this is its trunk tap (`layer` ignored)
  * into d_out on `hip_stream`.  For validation.  Errors: NULL, STATE, SHAPE.
  */
 int mt_read_hidden(mt_model* m, int32_t task, int32_t layer, float* d_out, size_t out_bytes, void* hip_stream);
@@ -183,7 +185,7 @@ int mt_op_layernorm(const float* d_x, const float* d_gamma, const float* d_beta,
                     void* d_out_bf16, int32_t M, int32_t H, void* hip_stream);
 
 /* Tuning aid for benchmarks: force one bf16 GEMM tile configuration for all later launches in this
- * process (0 = choose by shape, the default; 1..12 = a fixed configuration).  Returns the previous value. */
+ * process (0 = choose by shape, the default; 1..12 = a fixed tile configuration, 13 = the few-row kernel).  Returns the previous value. */
 int mt_debug_set_gemm_tile(int32_t sel);
 
 #ifdef __cplusplus

@@ -32,7 +32,10 @@ constexpr float kMaskedScore = -10000.0f;
 
 __device__ inline int k_chunk_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
 
-__global__ __launch_bounds__(256) void attention_bf16_kernel(AttnGroup g, const int32_t* __restrict__ mask,
+#ifndef MT_ATTN_MINW
+#define MT_ATTN_MINW 2
+#endif
+__global__ __launch_bounds__(256, MT_ATTN_MINW) void attention_bf16_kernel(AttnGroup g, const int32_t* __restrict__ mask,
                                                              const int32_t* __restrict__ seq_start,
                                                              const int32_t* __restrict__ seq_len, int B, int S, int H, int Sk_max,
                                                              float scale_log2e)
@@ -249,7 +252,81 @@ __global__ __launch_bounds__(256) void attention_f32_kernel(AttnGroup g, const i
     }
 }
 
+// First-token query only.  One wavefront per (problem, sequence, head): lanes run over keys for the scores
+// (float32 dot product over the head width), the softmax is a wavefront reduction, then lanes run over the
+// head's columns for the context.  All of a sequence's rows are real tokens (padding-free row order).
+template <typename T>
+__global__ __launch_bounds__(64) void attention_cls_kernel(AttnClsGroup g, const int32_t* __restrict__ seq_start,
+                                                           const int32_t* __restrict__ seq_len, int B, int Smax, int H, int A,
+                                                           float scale)
+{
+    extern __shared__ float sp[];    // [Smax] scores, then probabilities; then [d] the query
+    constexpr int VEC = 16 / (int)sizeof(T);
+    const int grp = blockIdx.z / B, b = blockIdx.z % B, a = blockIdx.y;
+    const int d = H / A, lane = threadIdx.x;
+    const int row0 = seq_start[b];
+    const int n = min(seq_len[b], Smax);
+    const size_t ld = (size_t)3 * H;
+    float* qs = sp + Smax;
+    const T* q = static_cast<const T*>(g.q[grp]) + (size_t)b * H + a * d;
+    const T* kv = static_cast<const T*>(g.kv[grp]) + (size_t)row0 * ld;
+    for (int c = lane; c < d; c += 64) qs[c] = (float)q[c];
+    __syncthreads();
+    float mx = -INFINITY;
+    for (int j = lane; j < n; j += 64) {
+        const T* kj = kv + (size_t)j * ld + H + a * d;
+        float acc = 0.f;
+        if (d % VEC == 0) {                                   // 16-byte loads along the key row
+            for (int c = 0; c < d; c += VEC) {
+                const uint4 raw = *reinterpret_cast<const uint4*>(kj + c);
+                const T* e = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+                for (int u = 0; u < VEC; ++u) acc = fmaf(qs[c + u], (float)e[u], acc);
+            }
+        } else {
+            for (int c = 0; c < d; ++c) acc = fmaf(qs[c], (float)kj[c], acc);
+        }
+        const float sc = acc * scale;
+        sp[j] = sc;
+        mx = fmaxf(mx, sc);
+    }
+    mx = wave_max(mx);
+    float sum = 0.f;
+    for (int j = lane; j < n; j += 64) {
+        const float e = expf(sp[j] - mx);
+        sp[j] = e;
+        sum += e;
+    }
+    sum = wave_sum(sum);
+    __syncthreads();
+    if (n <= 0) return;
+    const float inv = 1.0f / sum;
+    for (int c = lane; c < d; c += 64) {                      // lanes over the head's columns: coalesced value rows
+        float acc = 0.f;
+        const T* vc = kv + 2 * H + a * d + c;
+#pragma unroll 4
+        for (int j = 0; j < n; ++j) acc = fmaf(sp[j], (float)vc[(size_t)j * ld], acc);
+        static_cast<T*>(g.ctx[grp])[(size_t)b * H + a * d + c] = (T)(acc * inv);
+    }
+}
+
 }  // namespace
+
+hipError_t launch_attention_cls(const AttnClsGroup& g, int G, int is_bf16, const int32_t* seq_start, const int32_t* seq_len,
+                                int B, int S, int H, int A, hipStream_t stream)
+{
+    if (G <= 0 || B <= 0 || S <= 0) return hipSuccess;
+    if (!seq_start || !seq_len || G > kMaxGroup || H % A != 0 || ((size_t)S + H / A) * 4 > 64 * 1024) return hipErrorInvalidValue;
+    dim3 grid(1, A, B * G), block(64);
+    const float scale = 1.0f / sqrtf((float)(H / A));
+    if (is_bf16)
+        hipLaunchKernelGGL((attention_cls_kernel<__bf16>), grid, block, ((size_t)S + H / A) * sizeof(float), stream, g, seq_start, seq_len, B, S, H,
+                           A, scale);
+    else
+        hipLaunchKernelGGL((attention_cls_kernel<float>), grid, block, ((size_t)S + H / A) * sizeof(float), stream, g, seq_start, seq_len, B, S, H,
+                           A, scale);
+    return hipGetLastError();
+}
 
 hipError_t launch_attention_bf16(const AttnGroup& g, int G, const int32_t* mask, const int32_t* seq_start,
                                  const int32_t* seq_len, int B, int S, int H, int A, hipStream_t stream)

@@ -38,6 +38,8 @@ struct GemmShape {
 
 // bf16 x bf16 -> fp32 accumulate on the matrix cores.  Needs K % 64 == 0, lda % 8 == 0, 16-byte aligned A/W rows.
 hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t stream);
+// Few-row variant (M <= 256), memory-parallel instead of tiled; launch_gemm_bf16 routes to it by itself.
+hipError_t launch_gemm_skinny_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t stream);
 // fp32 (A) x {fp32|bf16} (W) on the vector ALUs, any shape.  w_bf16 selects the W element type.
 hipError_t launch_gemm_f32(const GemmGroup& g, const GemmShape& s, int w_bf16, hipStream_t stream);
 
@@ -90,12 +92,36 @@ hipError_t launch_embed_ln(const int32_t* ids, const int32_t* src, const int32_t
 struct SplitGroup {
     const float* x[kMaxGroup];
     bf16_t* out[kMaxGroup];
+    int32_t compact[kMaxGroup];   // 1: x[g] already holds one row per sequence (row b), ignore seq_start
 };
 // float32 validation mode: the same first-token rows copied unchanged, out[g] reinterpreted as float [B][H]
 hipError_t launch_gather_rows(const SplitGroup& g, int G, int B, int H, const int32_t* seq_start, int rows_per_seq, int max_rows,
                               hipStream_t stream);
 hipError_t launch_cls_split(const SplitGroup& g, int G, int B, int H, const int32_t* seq_start, int rows_per_seq, int max_rows,
                             hipStream_t stream);
+
+// First-token rows of every sequence, gathered into compact [B][H] arrays: float32 and/or element-type copies.
+struct FirstRowsGroup {
+    const float* xf[kMaxGroup];     // [rows][H] fp32 source, may be null
+    const void* xa[kMaxGroup];      // [rows][H] activation-type source (bf16 or fp32), may be null
+    float* out_f[kMaxGroup];        // [B][H]
+    void* out_a[kMaxGroup];         // [B][H]
+};
+hipError_t launch_gather_first_rows(const FirstRowsGroup& g, int G, int B, int H, int act_bytes, const int32_t* seq_start,
+                                    int max_rows, hipStream_t stream);
+// out[b][s][:] = (s == 0) ? x[b][:] : 0 for a [B][S][H] float32 output
+hipError_t launch_place_first_rows(const float* x, int B, int S, int H, float* out, hipStream_t stream);
+
+// Attention for the first-token query of every sequence only (the last layer of a branch needs nothing else):
+// q[g] is [B][H] (one query row per sequence), keys and values come from kv[g] = [rows][3H] (columns H.. and 2H..),
+// sequence b owning rows seq_start[b] .. +seq_len[b]-1; ctx[g] is [B][H].  Any head width <= 256.
+struct AttnClsGroup {
+    const void* q[kMaxGroup];
+    const void* kv[kMaxGroup];
+    void* ctx[kMaxGroup];
+};
+hipError_t launch_attention_cls(const AttnClsGroup& g, int G, int is_bf16, const int32_t* seq_start, const int32_t* seq_len,
+                                int B, int S, int H, int A, hipStream_t stream);
 
 // logits[g][b][c] = Wc_g[c][:] . pooled_g[b][:] + bc_g[c]; one wavefront per (g, b, c).  Wc bf16 or fp32.
 struct ClsGroup {

@@ -279,7 +279,7 @@ __global__ __launch_bounds__(256) void cls_split_kernel(SplitGroup g, int H, con
                                                         int rows_per_seq, int max_rows)
 {
     const int grp = blockIdx.y, b = blockIdx.x;
-    const int row = min(seq_start ? seq_start[b] : b * rows_per_seq, max_rows - 1);
+    const int row = g.compact[grp] ? b : min(seq_start ? seq_start[b] : b * rows_per_seq, max_rows - 1);
     const float* x = g.x[grp] + (size_t)row * H;
     __bf16* out = reinterpret_cast<__bf16*>(g.out[grp]) + (size_t)b * 2 * H;
     for (int i = threadIdx.x; i < H; i += 256) {
@@ -294,10 +294,39 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(SplitGroup g, int H, c
                                                           int rows_per_seq, int max_rows)
 {
     const int grp = blockIdx.y, b = blockIdx.x;
-    const int row = min(seq_start ? seq_start[b] : b * rows_per_seq, max_rows - 1);
+    const int row = g.compact[grp] ? b : min(seq_start ? seq_start[b] : b * rows_per_seq, max_rows - 1);
     const float* x = g.x[grp] + (size_t)row * H;
     float* out = reinterpret_cast<float*>(g.out[grp]) + (size_t)b * H;
     for (int i = threadIdx.x; i < H; i += 256) out[i] = x[i];
+}
+
+__global__ __launch_bounds__(256) void gather_first_rows_kernel(FirstRowsGroup g, int H, int act_bytes,
+                                                                const int32_t* __restrict__ seq_start, int max_rows)
+{
+    const int grp = blockIdx.y, b = blockIdx.x;
+    const int row = min(seq_start[b], max_rows - 1);
+    if (g.xf[grp]) {
+        const float* x = g.xf[grp] + (size_t)row * H;
+        float* o = g.out_f[grp] + (size_t)b * H;
+        for (int i = threadIdx.x; i < H; i += 256) o[i] = x[i];
+    }
+    if (g.xa[grp]) {
+        const size_t nbytes = (size_t)H * act_bytes;            // H * 2 or H * 4, a multiple of 4 (H is even in bf16 mode)
+        const uint32_t* x = reinterpret_cast<const uint32_t*>(static_cast<const unsigned char*>(g.xa[grp]) + (size_t)row * nbytes);
+        uint32_t* o = reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(g.out_a[grp]) + (size_t)b * nbytes);
+        for (int i = threadIdx.x; i < (int)(nbytes / 4); i += 256) o[i] = x[i];
+    }
+}
+
+__global__ __launch_bounds__(256) void place_first_rows_kernel(const float* __restrict__ x, int n_pos, int S, int H,
+                                                               float* __restrict__ out)
+{
+    const int p = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (p >= n_pos) return;
+    const bool first = (p % S) == 0;
+    const float* src = x + (size_t)(p / S) * H;
+    for (int i = lane; i < H; i += 64) out[(size_t)p * H + i] = first ? src[i] : 0.f;
 }
 
 template <typename TW>
@@ -330,6 +359,24 @@ hipError_t launch_gather_rows(const SplitGroup& g, int G, int B, int H, const in
 {
     if (G <= 0 || B <= 0) return hipSuccess;
     hipLaunchKernelGGL(gather_rows_kernel, dim3(B, G), dim3(256), 0, stream, g, H, seq_start, rows_per_seq, max_rows);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_first_rows(const FirstRowsGroup& g, int G, int B, int H, int act_bytes, const int32_t* seq_start,
+                                    int max_rows, hipStream_t stream)
+{
+    if (G <= 0 || B <= 0) return hipSuccess;
+    if (!seq_start || (act_bytes != 2 && act_bytes != 4) || (H * act_bytes) % 4 != 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(gather_first_rows_kernel, dim3(B, G), dim3(256), 0, stream, g, H, act_bytes, seq_start, max_rows);
+    return hipGetLastError();
+}
+
+hipError_t launch_place_first_rows(const float* x, int B, int S, int H, float* out, hipStream_t stream)
+{
+    if (B <= 0 || S <= 0) return hipSuccess;
+    const int n_pos = B * S;
+    hipLaunchKernelGGL(place_first_rows_kernel, dim3((n_pos + kRowsPerBlock - 1) / kRowsPerBlock), dim3(256), 0, stream, x, n_pos, S, H,
+                       out);
     return hipGetLastError();
 }
 

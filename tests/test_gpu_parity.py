@@ -55,7 +55,7 @@ SMALL = ms.MTSpec("small", vocab=500, hidden=128, heads=2, ffn=256, max_pos=64, 
 
 # ------------------------------------------------------------------ single operations
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13])
 def test_gemm_bf16_vs_oracle(tile):
     say(f"gemm_bf16 tile={tile}")
     rng = np.random.default_rng(10 + tile)
@@ -104,7 +104,7 @@ def test_gemm_bf16_grouped_and_split_vs_oracle():
     W = bf16_grid(rng.standard_normal((G, N, K)) * 0.1)
     bias = rng.standard_normal((G, N)).astype(np.float32)
     res = rng.standard_normal((G, M, N)).astype(np.float32)
-    for tile in (0, 1, 9, 11):
+    for tile in (0, 1, 9, 11, 13):
         prev = mt.set_gemm_tile(tile)
         try:
             out = mt.op_linear_batched(mt.MT_BF16, dev(A, torch.bfloat16), dev(W, torch.bfloat16), dev(bias), dev(res),
@@ -372,15 +372,17 @@ def test_bf16_base_invariants_at_full_size(base_model):
     ids2 = ids.copy()
     ids2[mask == 0] = (ids2[mask == 0] * 7 + 3) % spec.vocab
     assert np.array_equal(model.forward(dev(ids2), d_mask).cpu().numpy(), base)
-    # each sequence alone gives its row of the batched run
+    # each sequence alone gives its row of the batched run.  Not bit for bit: a problem of few rows runs in the
+    # few-row contraction kernel, which adds the K range up in four quarters, so some bf16 roundings of the
+    # activations fall the other way; the bound is a quarter of the logit tolerance.
     for b in (0, 5):
         one = model.forward(dev(ids[b:b + 1]), dev(mask[b:b + 1])).cpu().numpy()
-        assert np.abs(one[0] - base[b]).max() <= 1e-5
+        assert np.abs(one[0] - base[b]).max() <= 5e-3
     # truncating the padding away changes nothing
     L = int(lengths[:4].max())
     L = (L + 7) // 8 * 8
     cut = model.forward(dev(ids[:4, :L]), dev(mask[:4, :L])).cpu().numpy()
-    assert np.abs(cut - base[:4]).max() <= 1e-5
+    assert np.abs(cut - base[:4]).max() <= 5e-3        # four sequences can also fall under the few-row limit
     # task mask: disabled tasks' columns stay untouched, enabled ones are unchanged
     out = torch.full((ids.shape[0], model.n_logits), 7.0, device="cuda")
     tm = [1, 0, 1, 1, 0, 0, 1, 0]
