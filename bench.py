@@ -21,14 +21,29 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
 PEAK_FP32_VALU_TFLOPS = 157.3
 
 
-def gemm_flops_per_forward(spec, n_layers, rows):
-    """EXECUTED FLOPs of the four linear layers, per class, for one forward over `rows` token rows.
+def layer_kinds(spec):
+    """(#layers evaluated on every token row, #layers evaluated on the first token only).
+
+    Only position 0 of a branch's output feeds its pooler, so the library computes the last own layer
+    of every branch for that position alone (its keys and values still come from every row)."""
+    n_full = spec.n_trunk_layers + sum(max(t.n_layers - 1, 0) for t in spec.tasks)
+    n_first = sum(1 for t in spec.tasks if t.n_layers >= 1)
+    return n_full, n_first
+
+
+def gemm_flops_per_forward(spec, rows, batch):
+    """EXECUTED FLOPs of the linear layers, per profile class, for one forward over `rows` token rows.
 
     The library drops padded positions before the first layer, so `rows` is the number of real
-    tokens of the batch (sum of sequence lengths), not batch*seq."""
+    tokens of the batch (sum of sequence lengths), not batch*seq; a first-token-only layer projects
+    keys and values for every row and everything else for one row per sequence."""
     H, F = spec.hidden, spec.ffn
-    return {"gemm_qkv": n_layers * 2.0 * rows * 3 * H * H, "gemm_out": n_layers * 2.0 * rows * H * H,
-            "gemm_ffn1": n_layers * 2.0 * rows * F * H, "gemm_ffn2": n_layers * 2.0 * rows * H * F}
+    n_full, n_first = layer_kinds(spec)
+    return {"gemm_qkv": n_full * 2.0 * rows * 3 * H * H + n_first * 2.0 * rows * 2 * H * H,
+            "gemm_out": n_full * 2.0 * rows * H * H,
+            "gemm_ffn1": n_full * 2.0 * rows * F * H,
+            "gemm_ffn2": n_full * 2.0 * rows * H * F,
+            "gemm_first": n_first * 2.0 * batch * (2 * H * H + 2 * H * F)}
 
 
 def main():
@@ -38,8 +53,14 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="base", help="tiny | base | hetero | latency | large")
     ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--in-flight", type=int, default=3,
+                    help="batches in flight: forwards are issued round-robin to this many model replicas (shared "
+                         "weights, own workspace) on as many streams; 1 = strictly one forward after another")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=8, help="sequences the CPU oracle is timed on")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="before the warm-up, run one plain 256 MiB device copy (a kernel of known traffic to scale "
+                         "hardware byte counters by); untimed")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (sequences are independent, so N GPUs would run N "
@@ -72,19 +93,45 @@ def main():
         sq_lengths.append(float((lengths.astype(np.float64) ** 2).sum()))
     out = torch.zeros((B, model.n_logits), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
+    n_fly = max(1, args.in_flight)
+    models = [model] + [model.replica() for _ in range(n_fly - 1)]
+    streams = [torch.cuda.Stream() for _ in range(n_fly)]          # default priority
+    outs = [torch.zeros_like(out) for _ in range(n_fly)]
 
-    for i in range(args.warmup):
-        model.forward(*batches[i % n_batches], out=out)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(stream)
-    for i in range(args.steps):
-        model.forward(*batches[i % n_batches], out=out)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    ms_per_step = e0.elapsed_time(e1) / args.steps
+    def run_steps(k, fly):
+        """k forwards, round-robin over the replicas' streams; returns elapsed milliseconds."""
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for st in streams[:fly]:
+            st.wait_event(e0)
+        for i in range(k):
+            j = i % fly
+            with torch.cuda.stream(streams[j]):
+                models[j].forward(*batches[i % n_batches], out=outs[j])
+        for st in streams[:fly]:
+            stream.wait_stream(st)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    if args.copy_calibration:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")       # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    run_steps(args.warmup, n_fly)
+    ms_per_step = run_steps(args.steps, n_fly) / args.steps
     seq_per_s = B / (ms_per_step * 1e-3)
-    assert torch.isfinite(out).all()
+    for o in outs[:min(n_fly, args.steps)]:
+        assert torch.isfinite(o).all()
+    # the same K steps strictly one after another on one stream (latency of one batch; also what the
+    # per-kernel figures below are measured on, so that no other batch's kernels share the chip with them)
+    run_steps(min(args.warmup, 3), 1)
+    ms_serial = run_steps(args.steps, 1) / args.steps
 
     # ---- per-kernel durations from HIP events around every launch, same stream, same steps
     model.profile_enable(True)
@@ -98,7 +145,9 @@ def main():
     # the timed steps cycle through the batches: average real-token count over the steps actually run
     rows = float(np.mean([real_tokens[i % n_batches] for i in range(args.steps)]))
     sumsq = float(np.mean([sq_lengths[i % n_batches] for i in range(args.steps)]))
-    flops = gemm_flops_per_forward(spec, n_layers, rows)
+    flops = gemm_flops_per_forward(spec, rows, B)
+    n_full, n_first = layer_kinds(spec)
+    assert n_full + n_first == n_layers
     kernels = {}
     for k, (ms_tot, n) in prof.items():
         if n == 0:
@@ -107,21 +156,27 @@ def main():
         if k in flops:
             ent["tflops"] = flops[k] * args.steps / (ms_tot * 1e-3) / 1e12
         kernels[k] = ent
-    gemm_ms = sum(prof[k][0] for k in flops) / args.steps
-    gemm_launches = sum(prof[k][1] for k in flops) / args.steps
-    gemm_tflops = sum(flops.values()) / (gemm_ms * 1e-3) / 1e12
+    # the dominant kernel: the tiled matrix-core contraction over all token rows (the one-row-per-sequence
+    # contractions of the branches' last layers run in the few-row kernel and are listed on their own)
+    main = [k for k in flops if k != "gemm_first"]
+    main_flops = sum(flops[k] for k in main)
+    gemm_ms = sum(prof[k][0] for k in main) / args.steps
+    gemm_launches = sum(prof[k][1] for k in main) / args.steps
+    gemm_tflops = main_flops / (gemm_ms * 1e-3) / 1e12
     bf16 = spec.precision == "bf16"
     peak = PEAK_BF16_MFMA_TFLOPS if bf16 else PEAK_FP32_VALU_TFLOPS
-    roofline = {"kernel": "gemm_bf16_kernel" if bf16 else "gemm_f32_kernel", "bound": "mfma" if bf16 else "alu",
+    kname = ("gemm_bf16_kernel" if rows > 256 else "gemm_skinny_bf16_kernel") if bf16 else "gemm_f32_kernel"
+    roofline = {"kernel": kname, "bound": "mfma" if bf16 else "alu",
                 "achieved": gemm_tflops, "peak": peak, "unit": "TFLOP/s", "frac": gemm_tflops / peak, "traffic": None,
-                "flops_per_launch": sum(flops.values()) / gemm_launches, "avg_launch_us": 1e3 * gemm_ms / gemm_launches,
+                "flops_per_launch": main_flops / gemm_launches, "avg_launch_us": 1e3 * gemm_ms / gemm_launches,
                 "flops_counted": "executed: real (unpadded) token rows only",
                 "launches_per_step": gemm_launches, "gemm_ms_per_step": gemm_ms}
 
     h = spec.hidden
     per_layer = 8.0 * S * h * h + 4.0 * S * h * spec.ffn + 4.0 * S * S * h
     flops_per_seq_dense = n_layers * per_layer + spec.n_tasks * 2.0 * h * h          # dense, padded convention
-    executed_per_step = sum(flops.values()) + n_layers * 4.0 * h * sumsq + spec.n_tasks * 2.0 * B * 2 * h * h
+    executed_per_step = (sum(flops.values()) + n_full * 4.0 * h * sumsq + n_first * 4.0 * h * rows
+                         + spec.n_tasks * 2.0 * B * 2 * h * h)
     e2e_tflops = executed_per_step / (ms_per_step * 1e-3) / 1e12
     e2e_tflops_dense = flops_per_seq_dense * seq_per_s / 1e12
 
@@ -148,8 +203,10 @@ def main():
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{spec.name}: H={spec.hidden} A={spec.heads} F={spec.ffn} trunk={spec.n_trunk_layers} "
                                f"tasks={spec.n_tasks} layers={n_layers} B={B} S={S} len~U[{spec.len_lo},{spec.len_hi}]",
-                   "batch": B, "seq_len": S, "layer_evals": n_layers, "real_tokens_per_batch": rows,
-                   "padding_skipped": True},
+                   "batch": B, "seq_len": S, "layer_evals": n_layers, "layers_on_all_rows": n_full,
+                   "layers_on_first_token_only": n_first, "real_tokens_per_batch": rows, "padding_skipped": True,
+                   "batches_in_flight": n_fly},
+        "ms_per_step_one_in_flight": ms_serial, "sequences_per_s_one_in_flight": B / (ms_serial * 1e-3),
         "e2e_tflops_executed": e2e_tflops, "e2e_frac_of_peak": e2e_tflops / peak,
         "e2e_tflops_dense_padded_equivalent": e2e_tflops_dense,
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "weights_load_s": load_s,

@@ -93,6 +93,19 @@ size_t mt_workspace_bytes(const mt_model* m);
 int mt_bind(mt_model* m, void* d_weights, size_t weight_bytes, void* d_workspace, size_t workspace_bytes);
 
 /*
+ * Serving replicas (the merged model of Section 3.3 is stateless across batches: weights are only read).
+ * `m` must have been created from a configuration equal to `owner`'s and bound to the SAME weight arena
+ * with a workspace of its own; it then takes over `owner`'s loaded state without copying anything.
+ * mt_forward calls on `m` and on `owner` may then be in flight at the same time on different streams
+ * (each writes only its own workspace and its caller's logits), which lets one batch's kernels fill the
+ * compute units another batch's kernels leave idle.  Loading weights into either handle afterwards is
+ * visible to both arenas-wise, but only the loading handle's state is updated: call mt_share_weights
+ * again.  Host only.  Errors: NULL, CONFIG (configurations differ), STATE (not bound to the same
+ * weight arena, or owner has nothing loaded).
+ */
+int mt_share_weights(mt_model* m, const mt_model* owner);
+
+/*
  * Load one checkpoint into the graph ("load weights from multiple model checkpoints into one
  * computation graph", Section 3.3).  scope -1 = embeddings + trunk layers, scope t >= 0 = task t's
  * layers, pooler and classifier; loading one task never touches another's memory (the per-task
@@ -149,10 +162,13 @@ int mt_read_hidden(mt_model* m, int32_t task, int32_t layer, float* d_out, size_
  * Per-kernel timing.  While enabled, mt_forward brackets every launch with HIP events on the
  * forward's stream.  mt_profile_read waits for them, then reports, per kernel class, the number of
  * launches and their summed duration since the last read, and clears the record.
+ * MT_K_GEMM_FIRST collects the four one-row-per-sequence contractions (query, output projection and
+ * both feed-forward layers) of every branch's last layer; that layer's K|V projection over all rows
+ * counts under MT_K_GEMM_QKV.
  */
 enum {
     MT_K_EMBED = 0, MT_K_GEMM_QKV, MT_K_ATTN, MT_K_GEMM_OUT, MT_K_LN, MT_K_GEMM_FFN1, MT_K_GEMM_FFN2,
-    MT_K_POOL, MT_K_COUNT
+    MT_K_POOL, MT_K_GEMM_FIRST, MT_K_COUNT
 };
 int mt_profile_enable(mt_model* m, int32_t on);
 int mt_profile_read(mt_model* m, float* h_ms /*[MT_K_COUNT]*/, int32_t* h_launches /*[MT_K_COUNT]*/);

@@ -20,12 +20,12 @@ MT_OK, MT_ERR_NULL, MT_ERR_CONFIG, MT_ERR_SHAPE, MT_ERR_STATE, MT_ERR_BLOB, MT_E
 MT_BF16, MT_FP32_CHECK = 0, 1
 MT_GELU_ERF, MT_GELU_TANH = 0, 1
 MT_ABI_VERSION = 1
-KERNEL_CLASSES = ["embed", "gemm_qkv", "attn", "gemm_out", "ln", "gemm_ffn1", "gemm_ffn2", "pool"]
+KERNEL_CLASSES = ["embed", "gemm_qkv", "attn", "gemm_out", "ln", "gemm_ffn1", "gemm_ffn2", "pool", "gemm_first"]
 
 EXPORTS = ["mt_create", "mt_destroy", "mt_weight_bytes", "mt_workspace_bytes", "mt_bind", "mt_load_weights",
            "mt_forward", "mt_logit_offset", "mt_n_logits", "mt_layer_count", "mt_last_error", "mt_error_name",
            "mt_read_hidden", "mt_profile_enable", "mt_profile_read", "mt_op_linear", "mt_op_attention",
-           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile"]
+           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights"]
 
 
 class mt_task_desc(C.Structure):
@@ -72,6 +72,7 @@ def lib():
         L.mt_read_hidden.argtypes = [vp, i32, i32, vp, sz, vp]
         L.mt_profile_enable.argtypes = [vp, i32]
         L.mt_profile_read.argtypes = [vp, vp, vp]
+        L.mt_share_weights.argtypes = [vp, vp]
         L.mt_op_linear.argtypes = [i32, vp, i64, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, vp]
         L.mt_op_linear_batched.argtypes = [i32, i32, vp, i64, i64, vp, i64, vp, i64, vp, i64, vp, i64, i64, i32, i32, i32, i32, i32, vp]
         L.mt_op_attention.argtypes = [i32, vp, vp, vp, i32, i32, i32, i32, vp]
@@ -164,6 +165,17 @@ class Model:
         self.workspace = torch.empty(self.workspace_bytes(), dtype=torch.uint8, device=self.device)
         self._check(lib().mt_bind(self.h, _ptr(self.weights), self.weights.numel(), _ptr(self.workspace),
                                   self.workspace.numel()))
+
+    def replica(self):
+        """A second handle on the same weights with a workspace of its own (mt_share_weights): its forwards
+        may overlap this model's on another stream."""
+        import torch
+        r = Model(self.cfg, device=self.device, bind=False)
+        r.weights = self.weights
+        r.workspace = torch.empty(r.workspace_bytes(), dtype=torch.uint8, device=self.device)
+        r._check(lib().mt_bind(r.h, _ptr(r.weights), r.weights.numel(), _ptr(r.workspace), r.workspace.numel()))
+        r._check(lib().mt_share_weights(r.h, self.h))
+        return r
 
     def load_weights(self, scope: int, blob: bytes):
         buf = C.create_string_buffer(blob, len(blob)) if not isinstance(blob, C.Array) else blob

@@ -67,8 +67,9 @@ struct GemmCfg {
     static_assert(BK == 32 || BK == 64, "BK");
     static_assert(BM % (WAVES_M * 32) == 0 && BN % (WAVES_N * 32) == 0, "wave tile must be a multiple of 32x32");
     static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "rows must split evenly over wavefront loads");
-    static_assert(STAGES >= 2 && STAGES <= 4, "STAGES");
+    static_assert(STAGES >= 2 && STAGES <= 8, "STAGES");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds 160 KB");
+    static_assert(LPS * (STAGES - 2) <= 63, "steady-state loads in flight exceed the 6-bit vmcnt");
 };
 
 template <int N>
@@ -82,9 +83,15 @@ __device__ __forceinline__ void wait_lgkmcnt0() { asm volatile("s_waitcnt lgkmcn
 template <int LPS>
 __device__ __forceinline__ void wait_slices(int y)
 {
-    if (y >= 2) wait_vmcnt<2 * LPS>();
-    else if (y == 1) wait_vmcnt<LPS>();
-    else wait_vmcnt<0>();
+    constexpr int YMAX = (63 / LPS) < 6 ? (63 / LPS) : 6;     // vmcnt is a 6-bit counter
+    if (y > YMAX) y = YMAX;
+    if constexpr (YMAX >= 6) if (y == 6) { wait_vmcnt<6 * LPS>(); return; }
+    if constexpr (YMAX >= 5) if (y == 5) { wait_vmcnt<5 * LPS>(); return; }
+    if constexpr (YMAX >= 4) if (y == 4) { wait_vmcnt<4 * LPS>(); return; }
+    if constexpr (YMAX >= 3) if (y == 3) { wait_vmcnt<3 * LPS>(); return; }
+    if constexpr (YMAX >= 2) if (y == 2) { wait_vmcnt<2 * LPS>(); return; }
+    if (y == 1) { wait_vmcnt<LPS>(); return; }
+    wait_vmcnt<0>();
 }
 
 // Fast GELU(x) = x * Phi(x) for the bf16 epilogue: erf through the Abramowitz-Stegun 7.1.26 rational
@@ -189,7 +196,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, MINW) void gemm_bf16_kernel(
         const int row = (wave + (isA ? i : i - Cfg::A_LOADS) * Cfg::NW) * Cfg::RPI + lane / Cfg::CH;
         const int chunk = (lane % Cfg::CH) ^ ((row >> Cfg::KEY_SHIFT) & (Cfg::CH - 1));
         if (isA) ld_off[i] = (uint32_t)min(m0 + row, M - 1) * (uint32_t)(s.lda * 2) + chunk * 16;
-        else ld_off[i] = (uint32_t)min(n0 + row, s.N - 1) * (uint32_t)(s.K * 2) + chunk * 16;
+        else ld_off[i] = (uint32_t)min(n0 + row, s.N - 1) * (uint32_t)((s.ldw ? s.ldw : s.K) * 2) + chunk * 16;
     }
 
     f32x16 acc[TMI][TNI];
@@ -446,11 +453,11 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
 {
     if (s.G <= 0 || s.M <= 0 || s.N <= 0) return hipSuccess;
     if (s.splits < 1 || (s.splits > 1 && (!s.out_f32 || s.act != ACT_NONE || g.bias[0] || g.residual[0]))) return hipErrorInvalidValue;
-    if (s.K % 64 != 0 || s.K < 64 || s.N % 4 != 0 || s.lda % 8 != 0 || s.ldc % 4 != 0 || s.ldr % 4 != 0 ||
+    if (s.K % 64 != 0 || s.K < 64 || s.N % 4 != 0 || s.lda % 8 != 0 || s.ldw % 8 != 0 || (s.ldw && s.ldw < s.K) || s.ldc % 4 != 0 || s.ldr % 4 != 0 ||
         s.G > kMaxGroup || (!s.out_f32 && g.residual[0] != nullptr))
         return hipErrorInvalidValue;
     // per-lane chunk offsets are 32-bit
-    if ((uint64_t)s.M * (uint64_t)s.lda * 2 >= (1ull << 32) || (uint64_t)s.N * (uint64_t)s.K * 2 >= (1ull << 32))
+    if ((uint64_t)s.M * (uint64_t)s.lda * 2 >= (1ull << 32) || (uint64_t)s.N * (uint64_t)(s.ldw ? s.ldw : s.K) * 2 >= (1ull << 32))
         return hipErrorInvalidValue;
     int sel = g_gemm_bf16_tile_override;
     if ((sel == 0 && s.M <= 256) || sel == 13) return launch_gemm_skinny_bf16(g, s, stream);   // few rows: weight-streaming kernel
@@ -480,6 +487,10 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
         case 10: return launch_cfg<256, 128, 2, 2, 64, 2, 1>(g, s, stream);
         case 11: return launch_cfg<256, 128, 4, 2, 32, 3, 2>(g, s, stream);  // 8 wavefronts of 64x64, 72 KB
         case 12: return launch_cfg<128, 128, 2, 2, 32, 3, 2>(g, s, stream);  // 48 KB: three workgroups per CU
+        case 14: return launch_cfg<128, 128, 2, 2, 64, 4, 1>(g, s, stream);  // 128 KB: 3 slices of 64 ahead
+        case 15: return launch_cfg<128, 128, 2, 2, 32, 8, 1>(g, s, stream);  // 128 KB: 7 slices of 32 ahead
+        case 16: return launch_cfg<256, 128, 4, 2, 32, 6, 1>(g, s, stream);  // 144 KB, 8 wavefronts
+        case 17: return launch_cfg<128, 128, 2, 2, 32, 6, 1>(g, s, stream);  // 96 KB
         default: return launch_cfg<128, 128, 2, 2, 32, 4, 2>(g, s, stream);  // 64 KB LDS
     }
 }

@@ -24,6 +24,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmGroup g, GemmShape s)
     if (n0 >= N || m0 >= M) return;
     const float* A = static_cast<const float*>(g.A[grp]);
     const TW* W = static_cast<const TW*>(g.W[grp]);
+    const size_t ldw = s.ldw ? s.ldw : s.K;
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     const int lr = threadIdx.x >> 2;          // 0..63: tile row loaded by this thread
     const int lk = (threadIdx.x & 3) * 4;     // 0,4,8,12: first of 4 k's
@@ -34,7 +35,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmGroup g, GemmShape s)
             const int k = k0 + lk + j;
             const int am = m0 + lr, wn = n0 + lr;
             As[lk + j][lr] = (am < M && k < s.K) ? A[(size_t)am * s.lda + k] : 0.f;
-            Ws[lk + j][lr] = (wn < N && k < s.K) ? (float)W[(size_t)wn * s.K + k] : 0.f;
+            Ws[lk + j][lr] = (wn < N && k < s.K) ? (float)W[(size_t)wn * ldw + k] : 0.f;
         }
         __syncthreads();
 #pragma unroll

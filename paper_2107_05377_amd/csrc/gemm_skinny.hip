@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmGroup g, Gemm
     const __bf16* __restrict__ a_row =
         static_cast<const __bf16*>(g.A[grp]) + (size_t)min(m0 + l32, M - 1) * s.lda + k_begin + half * 8;
     const __bf16* __restrict__ w_row =
-        static_cast<const __bf16*>(g.W[grp]) + (size_t)min(n0 + l32, s.N - 1) * s.K + k_begin + half * 8;
+        static_cast<const __bf16*>(g.W[grp]) + (size_t)min(n0 + l32, s.N - 1) * (s.ldw ? s.ldw : s.K) + k_begin + half * 8;
 
     f32x16 acc;
 #pragma unroll
@@ -130,7 +130,7 @@ hipError_t launch_gemm_skinny_bf16(const GemmGroup& g, const GemmShape& s, hipSt
 {
     if (s.G <= 0 || s.M <= 0 || s.N <= 0) return hipSuccess;
     if (s.splits < 1 || (s.splits > 1 && (!s.out_f32 || s.act != ACT_NONE || g.bias[0] || g.residual[0]))) return hipErrorInvalidValue;
-    if (s.K % (64 * s.splits) != 0 || s.N % 4 != 0 || s.lda % 8 != 0 || s.ldc % 4 != 0 || s.ldr % 4 != 0 || s.G > kMaxGroup ||
+    if (s.K % (64 * s.splits) != 0 || s.N % 4 != 0 || s.lda % 8 != 0 || s.ldw % 8 != 0 || (s.ldw && s.ldw < s.K) || s.ldc % 4 != 0 || s.ldr % 4 != 0 || s.G > kMaxGroup ||
         (!s.out_f32 && g.residual[0] != nullptr) || (long)s.G * s.splits > 65535)
         return hipErrorInvalidValue;
     dim3 grid((s.N + SK_BN - 1) / SK_BN, (s.M + SK_BM - 1) / SK_BM, s.G * s.splits), block(256);

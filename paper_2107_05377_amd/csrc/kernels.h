@@ -27,13 +27,14 @@ struct GemmGroup {
 
 struct GemmShape {
     int32_t G, M, N, K;     // N = max over the group; M = row bound (grid size), see d_M
-    int64_t lda, ldc, ldr;  // row strides in elements (W is dense: ldw = K)
+    int64_t lda, ldc, ldr;  // row strides in elements
     int32_t act;            // ActKind
     int32_t out_f32;        // 1: C is float32, 0: C has the activation element type
     const int32_t* d_M;     // optional device scalar: rows actually present (<= M); tiles beyond it exit at once
     int32_t splits;         // bf16 path, >= 1: K is cut into `splits` equal ranges, range p of problem g writing its
                             // partial product (float32, no epilogue) to C_g + p * split_stride elements
     int64_t split_stride;
+    int64_t ldw;            // row stride of W in elements; 0 = dense (K)
 };
 
 // bf16 x bf16 -> fp32 accumulate on the matrix cores.  Needs K % 64 == 0, lda % 8 == 0, 16-byte aligned A/W rows.

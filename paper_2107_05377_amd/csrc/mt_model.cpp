@@ -439,7 +439,7 @@ void run_last_layer_group(Launcher& L, const std::vector<LastIO>& io, const RowM
         g.N[i] = H;
     }
     s = GemmShape{n, B, H, H, H, H, 0, ACT_NONE, bf ? 0 : 1, nullptr, 1, 0};
-    L.gemm(MT_K_GEMM_QKV, g, s, false);
+    L.gemm(MT_K_GEMM_FIRST, g, s, false);
 
     AttnClsGroup ag;
     memset(&ag, 0, sizeof ag);
@@ -468,7 +468,7 @@ void run_last_layer_group(Launcher& L, const std::vector<LastIO>& io, const RowM
         g.N[i] = H;
     }
     s = GemmShape{n, B, H, H, H, H, 0, ACT_NONE, 1, nullptr, sp_o, MBH};
-    L.gemm(MT_K_GEMM_OUT, g, s, false);
+    L.gemm(MT_K_GEMM_FIRST, g, s, false);
 
     LnGroup lg;
     memset(&lg, 0, sizeof lg);
@@ -493,7 +493,7 @@ void run_last_layer_group(Launcher& L, const std::vector<LastIO>& io, const RowM
         g.N[i] = F;
     }
     s = GemmShape{n, B, F, H, H, F, 0, gelu_act, bf ? 0 : 1, nullptr, 1, 0};
-    L.gemm(MT_K_GEMM_FFN1, g, s, false);
+    L.gemm(MT_K_GEMM_FIRST, g, s, false);
 
     const int sp_f = splits_for(F, 4);
     for (int i = 0; i < n; ++i) {
@@ -504,7 +504,7 @@ void run_last_layer_group(Launcher& L, const std::vector<LastIO>& io, const RowM
         g.N[i] = H;
     }
     s = GemmShape{n, B, H, F, F, H, 0, ACT_NONE, 1, nullptr, sp_f, MBH};
-    L.gemm(MT_K_GEMM_FFN2, g, s, false);
+    L.gemm(MT_K_GEMM_FIRST, g, s, false);
 
     for (int i = 0; i < n; ++i) {
         lg.x[i] = (const float*)(ws + io[i].cls->y);
@@ -695,6 +695,28 @@ int mt_bind(mt_model* m, void* d_weights, size_t weight_bytes, void* d_workspace
     m->d_ws = static_cast<unsigned char*>(d_workspace);
     m->trunk_loaded = false;
     std::fill(m->task_loaded.begin(), m->task_loaded.end(), 0);
+    return MT_OK;
+}
+
+int mt_share_weights(mt_model* m, const mt_model* owner)
+{
+    if (!m || !owner) return MT_ERR_NULL;
+    const mt_config &a = m->cfg, &b = owner->cfg;
+    bool same = a.vocab == b.vocab && a.hidden == b.hidden && a.heads == b.heads && a.ffn == b.ffn && a.max_pos == b.max_pos &&
+                a.type_vocab == b.type_vocab && a.n_trunk_layers == b.n_trunk_layers && a.n_tasks == b.n_tasks &&
+                a.precision == b.precision && a.gelu == b.gelu && a.ln_eps == b.ln_eps && m->weight_bytes == owner->weight_bytes &&
+                m->tasks.size() == owner->tasks.size();
+    for (size_t t = 0; same && t < m->tasks.size(); ++t)
+        same = m->tasks[t].fork_layer == owner->tasks[t].fork_layer && m->tasks[t].n_layers == owner->tasks[t].n_layers &&
+               m->tasks[t].n_classes == owner->tasks[t].n_classes;
+    if (!same) return fail(m, MT_ERR_CONFIG, "mt_share_weights: the two models were created from different configurations");
+    if (!m->d_w || m->d_w != owner->d_w) return fail(m, MT_ERR_STATE, "mt_share_weights: not bound to the owner's weight arena");
+    if (m->d_ws == owner->d_ws) return fail(m, MT_ERR_STATE, "mt_share_weights: the replica needs a workspace of its own");
+    bool any = owner->trunk_loaded;
+    for (char c : owner->task_loaded) any = any || c;
+    if (!any) return fail(m, MT_ERR_STATE, "mt_share_weights: owner has no weights loaded");
+    m->trunk_loaded = owner->trunk_loaded;
+    m->task_loaded = owner->task_loaded;
     return MT_OK;
 }
 
@@ -998,7 +1020,7 @@ int mt_profile_read(mt_model* m, float* h_ms, int32_t* h_launches)
 int mt_debug_set_gemm_tile(int32_t sel)
 {
     const int prev = mt::g_gemm_bf16_tile_override;
-    mt::g_gemm_bf16_tile_override = (sel >= 0 && sel <= 13) ? sel : 0;
+    mt::g_gemm_bf16_tile_override = (sel >= 0 && sel <= 17) ? sel : 0;
     return prev;
 }
 

@@ -136,6 +136,30 @@ def test_call_order_and_blob_errors():
     L.mt_destroy(h)
 
 
+def test_share_weights_checks():
+    """A replica must match the owner's configuration, share its weight arena, bring a workspace of its own,
+    and the owner must have something loaded."""
+    L = mt.lib()
+    spec = ms.get_config("tiny")
+    _, a, _ = _create(spec)
+    _, b, _ = _create(spec)
+    _, c, _ = _create(ms.get_config("hetero"))
+    w, ws1, ws2 = C.c_void_p(0x10000), C.c_void_p(0x20000), C.c_void_p(0x30000)
+    assert L.mt_share_weights(None, a) == mt.MT_ERR_NULL
+    assert L.mt_bind(a, w, 1 << 40, ws1, 1 << 40) == mt.MT_OK
+    assert L.mt_share_weights(c, a) == mt.MT_ERR_CONFIG
+    assert L.mt_share_weights(b, a) == mt.MT_ERR_STATE                  # b not bound
+    assert L.mt_bind(b, ws2, 1 << 40, ws2, 1 << 40) == mt.MT_OK
+    assert L.mt_share_weights(b, a) == mt.MT_ERR_STATE                  # other weight arena
+    assert L.mt_bind(b, w, 1 << 40, ws1, 1 << 40) == mt.MT_OK
+    assert L.mt_share_weights(b, a) == mt.MT_ERR_STATE                  # same workspace
+    assert L.mt_bind(b, w, 1 << 40, ws2, 1 << 40) == mt.MT_OK
+    assert L.mt_share_weights(b, a) == mt.MT_ERR_STATE                  # owner has nothing loaded
+    assert b"nothing loaded" in L.mt_last_error(b) or b"no weights" in L.mt_last_error(b)
+    for h in (a, b, c):
+        L.mt_destroy(h)
+
+
 def test_op_entry_points_reject_bad_arguments():
     L = mt.lib()
     fake = C.c_void_p(0x10000)

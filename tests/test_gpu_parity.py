@@ -55,7 +55,7 @@ SMALL = ms.MTSpec("small", vocab=500, hidden=128, heads=2, ffn=256, max_pos=64, 
 
 # ------------------------------------------------------------------ single operations
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17])
 def test_gemm_bf16_vs_oracle(tile):
     say(f"gemm_bf16 tile={tile}")
     rng = np.random.default_rng(10 + tile)
@@ -439,3 +439,27 @@ def test_bf16_vs_fp32_mode_argmax_over_many_sequences(base_model):
     assert worst <= 2e-2
     assert agree_safe == n_safe
     assert agree / n >= 0.999
+
+
+def test_replicas_in_flight_match_serial(base_model):
+    """Forwards of two replicas (shared weights, own workspaces) overlapping on two streams give, batch by batch,
+    exactly what one model gives running them one after another."""
+    spec, model, _, _ = base_model
+    batches = []
+    for i in range(4):
+        ids, mask, _ = ms.make_inputs(spec, batch_index=10 + i)
+        batches.append((dev(ids), dev(mask)))
+    serial = [model.forward(*b).clone() for b in batches]
+    torch.cuda.synchronize()
+    reps = [model, model.replica()]
+    streams = [torch.cuda.Stream() for _ in reps]
+    outs = [torch.zeros_like(serial[0]) for _ in batches]
+    for rounds in range(3):
+        for i, b in enumerate(batches):
+            j = i % 2
+            with torch.cuda.stream(streams[j]):
+                reps[j].forward(*b, out=outs[i])
+        torch.cuda.synchronize()
+        for i in range(len(batches)):
+            assert torch.equal(outs[i], serial[i]), f"round {rounds}, batch {i}"
+    reps[1].close()
