@@ -46,18 +46,65 @@ def gemm_flops_per_forward(spec, rows, batch):
             "gemm_first": n_first * 2.0 * batch * (2 * H * H + 2 * H * F)}
 
 
+def stored_traffic(workload_name):
+    """HBM-side bytes per launch of the tiled contraction kernel from the committed counter summary, or None
+    when there is none for this workload or the kernel's source has changed since the counters were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", f"bench_{workload_name}_hbm_traffic.txt")
+    src = os.path.join(ROOT, "paper_2107_05377_amd", "csrc", "gemm_bf16.hip")
+    if not (os.path.exists(path) and os.path.exists(src)):
+        return None
+    vals = {}
+    for line in open(path):
+        if " = " in line:
+            k, v = line.split(" = ", 1)
+            vals[k.strip()] = v.split()[0]
+    if vals.get("kernel_source_sha256") != hashlib.sha256(open(src, "rb").read()).hexdigest():
+        return None
+    return float(vals["traffic_bytes_per_launch"]) if "traffic_bytes_per_launch" in vals else None
+
+
+def latency_sweep(mt, ms, spec, model, calls):
+    """One forward at a time, host clock around launch + stream sync, per batch size: p50 / p99 / sequences/s."""
+    import numpy as np
+    import torch
+    res = []
+    for b in (1, 2, 4, 8):
+        if b > spec.batch:
+            continue
+        sets = []
+        for i in range(8):
+            ids, mask, _ = ms.make_inputs(spec, batch=b, batch_index=i)
+            sets.append((torch.from_numpy(ids).cuda(), torch.from_numpy(mask).cuda()))
+        out = torch.zeros((b, model.n_logits), dtype=torch.float32, device="cuda")
+        for i in range(50):
+            model.forward(*sets[i % 8], out=out)
+        torch.cuda.synchronize()
+        t = np.empty(calls)
+        for i in range(calls):
+            t0 = time.perf_counter()
+            model.forward(*sets[i % 8], out=out)
+            torch.cuda.synchronize()
+            t[i] = time.perf_counter() - t0
+        res.append({"batch": b, "calls": calls, "p50_ms": float(np.percentile(t, 50) * 1e3), "p99_ms": float(np.percentile(t, 99) * 1e3),
+                    "mean_ms": float(t.mean() * 1e3), "sequences_per_s": float(b / t.mean())})
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="base", help="tiny | base | hetero | latency | large")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--in-flight", type=int, default=3,
                     help="batches in flight: forwards are issued round-robin to this many model replicas (shared "
                          "weights, own workspace) on as many streams; 1 = strictly one forward after another")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=8, help="sequences the CPU oracle is timed on")
+    ap.add_argument("--cpu-sample", type=int, default=64, help="sequences the CPU oracle is timed on")
+    ap.add_argument("--latency-calls", type=int, default=2000,
+                    help="config 'latency' only: forwards timed one by one (host clock, stream sync per call) per batch size")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="before the warm-up, run one plain 256 MiB device copy (a kernel of known traffic to scale "
                          "hardware byte counters by); untimed")
@@ -166,8 +213,12 @@ def main():
     bf16 = spec.precision == "bf16"
     peak = PEAK_BF16_MFMA_TFLOPS if bf16 else PEAK_FP32_VALU_TFLOPS
     kname = ("gemm_bf16_kernel" if rows > 256 else "gemm_skinny_bf16_kernel") if bf16 else "gemm_f32_kernel"
+    traffic = stored_traffic(spec.name) if (bf16 and B == spec.batch and kname == "gemm_bf16_kernel") else None
+    measured_peak = mt.mfma_peak() if bf16 else None
     roofline = {"kernel": kname, "bound": "mfma" if bf16 else "alu",
-                "achieved": gemm_tflops, "peak": peak, "unit": "TFLOP/s", "frac": gemm_tflops / peak, "traffic": None,
+                "achieved": gemm_tflops, "peak": peak, "unit": "TFLOP/s", "frac": gemm_tflops / peak, "traffic": traffic,
+                "peak_measured_mfma_only": measured_peak,
+                "frac_of_measured_peak": (gemm_tflops / measured_peak) if measured_peak else None,
                 "flops_per_launch": main_flops / gemm_launches, "avg_launch_us": 1e3 * gemm_ms / gemm_launches,
                 "flops_counted": "executed: real (unpadded) token rows only",
                 "launches_per_step": gemm_launches, "gemm_ms_per_step": gemm_ms}
@@ -183,18 +234,35 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        n = max(1, min(args.cpu_sample, B))
         trunk, _ = ms.make_trunk_params(spec)
         tasks = [ms.make_task_params(spec, t)[0] for t in range(spec.n_tasks)]
         orc = oracle.Oracle(spec, trunk, tasks)
+        left, dt, n_done, err = max(1, args.cpu_sample), 0.0, 0, 0.0
+        for bi in range(n_batches):
+            if left <= 0:
+                break
+            n = min(left, B)
+            ids, mask, _ = ms.make_inputs(spec, batch=B, batch_index=bi)
+            t0 = time.time()
+            ref = orc.mt_forward(ids[:n], mask[:n])
+            dt += time.time() - t0
+            got = model.forward(*batches[bi]).cpu().numpy()[:n]
+            err = max(err, float(np.abs(got - ref).max()))
+            left -= n
+            n_done += n
+        cpu = {"value": n_done / dt, "unit": "sequences/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"the first {n_done} sequences of the same workload's batches, one pass, {dt:.1f} s",
+               "max_abs_dlogit_vs_gpu": err}
+        # the same oracle on one thread, on a smaller sample
+        n1 = max(1, min(4, n_done))
+        all_threads = oracle.num_threads()
+        oracle.set_num_threads(1)
         ids, mask, _ = ms.make_inputs(spec, batch=B, batch_index=0)
         t0 = time.time()
-        ref = orc.mt_forward(ids[:n], mask[:n])
-        dt = time.time() - t0
-        got = model.forward(*batches[0]).cpu().numpy()[:n]
-        cpu = {"value": n / dt, "unit": "sequences/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"first {n} sequences of batch 0 of the same workload, one pass, {dt:.1f} s",
-               "max_abs_dlogit_vs_gpu": float(np.abs(got - ref).max())}
+        orc.mt_forward(ids[:n1], mask[:n1])
+        dt1 = time.time() - t0
+        oracle.set_num_threads(all_threads)
+        cpu["one_thread"] = {"value": n1 / dt1, "unit": "sequences/s", "sample": f"first {n1} sequences of batch 0, {dt1:.1f} s"}
 
     line = {
         "metric": "sequences/sec (8-task MT forward, BERT-base, seq128) + % bf16 MFMA peak",
@@ -211,6 +279,8 @@ def main():
         "e2e_tflops_dense_padded_equivalent": e2e_tflops_dense,
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "weights_load_s": load_s,
     }
+    if spec.name == "latency":
+        line["latency"] = latency_sweep(mt, ms, spec, model, args.latency_calls)
     print(json.dumps(line))
 
 

@@ -204,6 +204,15 @@ int mt_op_layernorm(const float* d_x, const float* d_gamma, const float* d_beta,
  * process (0 = choose by shape, the default; 1..12 = a fixed tile configuration, 13 = the few-row kernel).  Returns the previous value. */
 int mt_debug_set_gemm_tile(int32_t sel);
 
+/*
+ * Measured matrix-core rate (the roofline of the bf16 contractions, Section 3.3's serving cost being all
+ * transformer layers): runs back-to-back register-only v_mfma_f32_32x32x16_bf16 on every compute unit of the
+ * current device for `iters` x 8 instructions per wavefront and writes the achieved dense bf16 TFLOP/s to
+ * *h_tflops (host).  d_scratch: device memory of at least `scratch_bytes` >= 1 MiB, overwritten.  Blocks until
+ * the measurement is done.  Errors: NULL, SHAPE (iters < 1 or scratch too small), HIP.
+ */
+int mt_debug_mfma_peak(int32_t iters, void* d_scratch, size_t scratch_bytes, float* h_tflops, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

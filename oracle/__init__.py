@@ -5,7 +5,7 @@ library never does.  The arithmetic lives in mt_oracle.c (C, float32 storage, fl
 and, independently, in brute_tiny.py (scalar float64 loops for tiny shapes).
 """
 from .binding import (Oracle, overhead, linear, layernorm, gelu, softmax_row, attention,
-                      encoder_layer, layer_param_count, num_threads)
+                      encoder_layer, layer_param_count, num_threads, set_num_threads)
 
 __all__ = ["Oracle", "overhead", "linear", "layernorm", "gelu", "softmax_row", "attention",
-           "encoder_layer", "layer_param_count", "num_threads"]
+           "encoder_layer", "layer_param_count", "num_threads", "set_num_threads"]

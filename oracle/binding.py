@@ -53,6 +53,11 @@ def _i32(a):
     return np.ascontiguousarray(a, dtype=np.int32)
 
 
+def set_num_threads(n: int) -> None:
+    """Limit the OpenMP threads the oracle uses from now on (timing baselines only; results do not depend on it)."""
+    lib().orc_set_num_threads(int(n))
+
+
 def num_threads() -> int:
     """Threads the oracle's OpenMP loops will use."""
     return int(lib().orc_num_threads())

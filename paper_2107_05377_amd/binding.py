@@ -25,7 +25,7 @@ KERNEL_CLASSES = ["embed", "gemm_qkv", "attn", "gemm_out", "ln", "gemm_ffn1", "g
 EXPORTS = ["mt_create", "mt_destroy", "mt_weight_bytes", "mt_workspace_bytes", "mt_bind", "mt_load_weights",
            "mt_forward", "mt_logit_offset", "mt_n_logits", "mt_layer_count", "mt_last_error", "mt_error_name",
            "mt_read_hidden", "mt_profile_enable", "mt_profile_read", "mt_op_linear", "mt_op_attention",
-           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights"]
+           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak"]
 
 
 class mt_task_desc(C.Structure):
@@ -73,6 +73,7 @@ def lib():
         L.mt_profile_enable.argtypes = [vp, i32]
         L.mt_profile_read.argtypes = [vp, vp, vp]
         L.mt_share_weights.argtypes = [vp, vp]
+        L.mt_debug_mfma_peak.argtypes = [i32, vp, C.c_size_t, vp, vp]
         L.mt_op_linear.argtypes = [i32, vp, i64, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, vp]
         L.mt_op_linear_batched.argtypes = [i32, i32, vp, i64, i64, vp, i64, vp, i64, vp, i64, vp, i64, i64, i32, i32, i32, i32, i32, vp]
         L.mt_op_attention.argtypes = [i32, vp, vp, vp, i32, i32, i32, i32, vp]
@@ -210,6 +211,17 @@ class Model:
         n = (C.c_int32 * len(KERNEL_CLASSES))()
         self._check(lib().mt_profile_read(self.h, ms, n))
         return {k: (float(ms[i]), int(n[i])) for i, k in enumerate(KERNEL_CLASSES)}
+
+
+def mfma_peak(iters=4000):
+    """Measured register-only bf16 matrix-core rate of the current device in TFLOP/s (mt_debug_mfma_peak)."""
+    import torch
+    scratch = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    out = C.c_float(0.0)
+    rc = lib().mt_debug_mfma_peak(iters, _ptr(scratch), scratch.numel(), C.byref(out), _stream())
+    if rc != MT_OK:
+        raise MTError(rc, "mt_debug_mfma_peak")
+    return float(out.value)
 
 
 def op_linear(precision, A, W, bias=None, residual=None, act=0, out_f32=False, lda=None):

@@ -41,6 +41,12 @@ namespace {
 #ifndef MT_GEMM_INTERLEAVE
 #define MT_GEMM_INTERLEAVE 1
 #endif
+#ifndef MT_GEMM_BIG_TILE
+#define MT_GEMM_BIG_TILE 9
+#endif
+#ifndef MT_GEMM_DSPER
+#define MT_GEMM_DSPER 1
+#endif
 constexpr int kXcds = MT_GEMM_XCDS;              // 1 disables the per-XCD regrouping of workgroup ids
 constexpr bool kInterleave = MT_GEMM_INTERLEAVE != 0;
 constexpr int kBand = MT_GEMM_BAND;              // row-tiles per raster band
@@ -122,17 +128,24 @@ __device__ __forceinline__ float epi_act(float v)
 
 // Interleave hint for one K step: NF fragment reads and NL global->LDS loads are slotted between the
 // step's NM MFMAs so that no long run of non-MFMA instructions stalls the matrix pipe.
+template <int LEFT, int P>
+__device__ __forceinline__ void interleave_reads()
+{
+    if constexpr (LEFT > 0) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // one MFMA ...
+        __builtin_amdgcn_sched_group_barrier(0x100, LEFT < P ? LEFT : P, 0);     // ... then up to P fragment reads
+        interleave_reads<(LEFT > P ? LEFT - P : 0), P>();
+    }
+}
+
 template <int NM, int NF, int NL>
 __device__ __forceinline__ void interleave_step()
 {
-    constexpr int a = NF < NM ? NF : NM;
+    constexpr int P = MT_GEMM_DSPER;                       // fragment reads slotted behind each of the first MFMAs
+    constexpr int a0 = (NF + P - 1) / P;
+    constexpr int a = a0 < NM ? a0 : NM;
     constexpr int b = (NL < NM - a) ? NL : (NM - a);
-#pragma unroll
-    for (int i = 0; i < a; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    if constexpr (NF > a) __builtin_amdgcn_sched_group_barrier(0x100, NF - a, 0);
+    interleave_reads<NF, P>();
 #pragma unroll
     for (int i = 0; i < b; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -470,7 +483,7 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
         //   few tiles (single problem): 128x128, two or three workgroups per CU.
         const long t256 = (long)s.G * s.splits * ((s.M + 255) / 256) * ((s.N + 255) / 256);
         const bool gelu = s.act == ACT_GELU_ERF || s.act == ACT_GELU_TANH;
-        if (t256 >= 256) sel = gelu ? 11 : 9;
+        if (t256 >= 256) sel = gelu ? 11 : MT_GEMM_BIG_TILE;
         else if (s.K / s.splits >= 2048) sel = 1;
         else if (s.N >= 2048) sel = 6;
         else sel = 12;

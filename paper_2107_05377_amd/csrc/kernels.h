@@ -41,6 +41,10 @@ struct GemmShape {
 hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t stream);
 // Few-row variant (M <= 256), memory-parallel instead of tiled; launch_gemm_bf16 routes to it by itself.
 hipError_t launch_gemm_skinny_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t stream);
+// Register-only matrix-core rate measurement: n_cu workgroups of 8 wavefronts, `iters` x 8 MFMAs each; d_out needs
+// mfma_rate_out_floats(n_cu) floats.  Synchronises on the stream.
+hipError_t run_mfma_rate(int iters, int n_cu, float* d_out, hipStream_t stream, float* tflops);
+int mfma_rate_out_floats(int n_cu);
 // fp32 (A) x {fp32|bf16} (W) on the vector ALUs, any shape.  w_bf16 selects the W element type.
 hipError_t launch_gemm_f32(const GemmGroup& g, const GemmShape& s, int w_bf16, hipStream_t stream);
 

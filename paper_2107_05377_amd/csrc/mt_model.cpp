@@ -32,6 +32,14 @@ namespace mt {
 extern int g_gemm_bf16_tile_override;
 }
 
+// Upper bounds on the K split of the two narrow contractions of a layer (tuning knobs).
+#ifndef MT_MAX_SPLITS_OUT
+#define MT_MAX_SPLITS_OUT 2
+#endif
+#ifndef MT_MAX_SPLITS_FFN2
+#define MT_MAX_SPLITS_FFN2 4
+#endif
+
 namespace {
 
 constexpr size_t kAlign = 256;
@@ -316,7 +324,7 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& 
     };
 
     // output projection -> y (fp32 partial products), then LayerNorm(y + bias + residual) -> x1
-    const int sp_o = pick_splits(H, H, 2);
+    const int sp_o = pick_splits(H, H, MT_MAX_SPLITS_OUT);
     for (int i = 0; i < n; ++i) {
         g.A[i] = ws + io[i].scr->ctx;
         g.W[i] = W + io[i].w->Wo;
@@ -356,7 +364,7 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& 
     L.gemm(MT_K_GEMM_FFN1, g, s, false);
 
     // FFN2 -> y (fp32 partial products), then LayerNorm(y + bias + residual) -> layer output
-    const int sp_f = pick_splits(F, H, 4);
+    const int sp_f = pick_splits(F, H, MT_MAX_SPLITS_FFN2);
     for (int i = 0; i < n; ++i) {
         g.A[i] = ws + io[i].scr->u;
         g.W[i] = W + io[i].w->W2;
@@ -1015,6 +1023,17 @@ int mt_profile_read(mt_model* m, float* h_ms, int32_t* h_launches)
     }
     m->prof.clear();
     return rc;
+}
+
+int mt_debug_mfma_peak(int32_t iters, void* d_scratch, size_t scratch_bytes, float* h_tflops, void* hip_stream)
+{
+    if (!d_scratch || !h_tflops) return MT_ERR_NULL;
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+        return MT_ERR_HIP;
+    if (iters < 1 || scratch_bytes < (size_t)mfma_rate_out_floats(n_cu) * 4) return MT_ERR_SHAPE;
+    return run_mfma_rate(iters, n_cu, static_cast<float*>(d_scratch), static_cast<hipStream_t>(hip_stream), h_tflops) == hipSuccess ? MT_OK
+                                                                                                                       : MT_ERR_HIP;
 }
 
 int mt_debug_set_gemm_tile(int32_t sel)
