@@ -96,7 +96,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="base", help="tiny | base | hetero | latency | large")
+    ap.add_argument("--config", default="base", help="tiny | base | hetero | latency | large | industrial")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--in-flight", type=int, default=3,
                     help="batches in flight: forwards are issued round-robin to this many model replicas (shared "
@@ -279,7 +279,7 @@ def main():
         "e2e_tflops_dense_padded_equivalent": e2e_tflops_dense,
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "weights_load_s": load_s,
     }
-    if spec.name == "latency":
+    if spec.name in ("latency", "industrial"):
         line["latency"] = latency_sweep(mt, ms, spec, model, args.latency_calls)
     print(json.dumps(line))
 

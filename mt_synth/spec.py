@@ -90,6 +90,13 @@ def _hetero_tasks() -> Tuple[TaskSpec, ...]:
     return tuple(TaskSpec(12 - k, (k + 1) // 2, c) for k, c in zip(ks, _GLUE_CLASSES))
 
 
+def _industrial_tasks() -> Tuple[TaskSpec, ...]:
+    # Appendix E: 21 tasks on 8 shared layers, 32 task layers in all (1.5 per task on average): 11 tasks keep two
+    # distilled layers, 10 keep one.  Class counts are stand-ins for intent / domain / emotion style label sets.
+    classes = (2, 3, 5, 8, 12, 2, 4, 30, 2, 6, 3, 2, 16, 4, 2, 9, 3, 2, 50, 7, 2)
+    return tuple(TaskSpec(8, 2 if t % 2 == 0 else 1, c) for t, c in enumerate(classes))
+
+
 CONFIGS = {
     "tiny": MTSpec("tiny", vocab=1000, hidden=64, heads=2, ffn=256, max_pos=32, n_trunk_layers=2,
                    tasks=(TaskSpec(2, 1, 2), TaskSpec(2, 1, 3)), precision="fp32",
@@ -106,12 +113,16 @@ CONFIGS = {
     "large": MTSpec("large", vocab=30522, hidden=1024, heads=16, ffn=4096, max_pos=512, n_trunk_layers=18,
                     tasks=_uniform_tasks(18, 2), precision="bf16",
                     batch=128, seq=256, len_lo=64, len_hi=256, input_seed=1004),
+    # second workload (Appendix E): many small tasks over short utterances
+    "industrial": MTSpec("industrial", vocab=21128, hidden=768, heads=12, ffn=3072, max_pos=512, n_trunk_layers=8,
+                         tasks=_industrial_tasks(), precision="bf16",
+                         batch=16, seq=32, len_lo=4, len_hi=32, input_seed=1005),
 }
-_ORDER = ["tiny", "base", "hetero", "latency", "large"]
+_ORDER = ["tiny", "base", "hetero", "latency", "large", "industrial"]
 
 
 def get_config(key) -> MTSpec:
-    """Look a workload up by name or by index 0..4 (tiny, base, hetero, latency, large)."""
+    """Look a workload up by name or by index 0..5 (tiny, base, hetero, latency, large, industrial)."""
     if isinstance(key, int):
         key = _ORDER[key]
     return CONFIGS[key]

@@ -136,6 +136,17 @@ def test_call_order_and_blob_errors():
     L.mt_destroy(h)
 
 
+def test_industrial_workload_layer_count():
+    """Appendix E: 21 tasks served by 40 transformer layers, 8 of them shared."""
+    spec = ms.get_config("industrial")
+    assert spec.n_tasks == 21 and spec.n_trunk_layers == 8 and sum(t.n_layers for t in spec.tasks) == 32
+    rc, h, _ = _create(spec)
+    assert rc == mt.MT_OK
+    assert mt.lib().mt_layer_count(h) == 40
+    assert mt.lib().mt_n_logits(h) == sum(t.n_classes for t in spec.tasks)
+    mt.lib().mt_destroy(h)
+
+
 def test_share_weights_checks():
     """A replica must match the owner's configuration, share its weight arena, bring a workspace of its own,
     and the owner must have something loaded."""
