@@ -864,26 +864,27 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
                             (bf16_t*)cur_b, L.st));
     L.end();
 
-    // ---- trunk, once, up to the deepest enabled fork
-    std::vector<LayerIO> io(1);
-    for (int l = 0; l < depth; ++l) {
-        float* nf;
-        void* nb;
-        trunk_out(l + 1, (l + 1) & 1, nf, nb);
-        io[0] = LayerIO{cur_f, cur_b, &m->trunk[l], &m->trunk_scr, nf, nb};
-        run_layer_group(L, io, rm, B, S);
-        cur_f = nf;
-        cur_b = nb;
-    }
-
-    // ---- branches in lock step, one grouped launch sequence per stage; a task's last own layer takes
-    //      the first-token-only path
-    for (int stage = 0; stage < max_y; ++stage) {
+    // ---- trunk and branches as one wavefront (Fig. 1(c)): step k evaluates trunk layer k+1 together with, for
+    //      every task that forked at or before k, its own layer k - fork (if it has one), as ONE grouped launch
+    //      sequence: a branch starts as soon as its tap exists instead of waiting for the whole trunk, so the
+    //      number of sequential layer steps is max(D, max_t(fork_t + layers_t)) instead of D + max_t layers_t.
+    //      A task's last own layer takes the first-token-only path.
+    int n_steps = depth;
+    for (int t : enabled) n_steps = std::max(n_steps, m->tasks[t].fork_layer + m->tasks[t].n_layers);
+    (void)max_y;
+    for (int step = 0; step < n_steps; ++step) {
         std::vector<LayerIO> full;
         std::vector<LastIO> last;
+        float* nf = nullptr;
+        void* nb = nullptr;
+        if (step < depth) {
+            trunk_out(step + 1, (step + 1) & 1, nf, nb);
+            full.push_back(LayerIO{cur_f, cur_b, &m->trunk[step], &m->trunk_scr, nf, nb});
+        }
         for (int t : enabled) {
             const mt_task_desc& d = m->tasks[t];
-            if (d.n_layers <= stage) continue;
+            const int stage = step - d.fork_layer;
+            if (stage < 0 || stage >= d.n_layers) continue;
             const float* in_f;
             const void* in_b;
             if (stage == 0) {
@@ -908,6 +909,10 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
         for (size_t lo = 0; lo < last.size(); lo += kMaxGroup) {
             std::vector<LastIO> part(last.begin() + lo, last.begin() + std::min(last.size(), lo + (size_t)kMaxGroup));
             run_last_layer_group(L, part, rm, B, S);
+        }
+        if (step < depth) {
+            cur_f = nf;
+            cur_b = nb;
         }
     }
 
