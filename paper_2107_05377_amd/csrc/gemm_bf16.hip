@@ -155,7 +155,7 @@ __device__ __forceinline__ void interleave_step()
     if constexpr (NM - a - b > 0) __builtin_amdgcn_sched_group_barrier(0x008, NM - a - b, 0);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int MINW, bool OUT_F32, int ACT>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int MINW, bool OUT_F32, int ACT, int FS>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, MINW) void gemm_bf16_kernel(GemmGroup g, GemmShape s, int tiles_n)
 {
     using Cfg = GemmCfg<BM, BN, WAVES_M, WAVES_N, BK, STAGES>;
@@ -262,62 +262,140 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, MINW) void gemm_bf16_kernel(
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf_][j], af[buf_][i], acc[i][j], 0, 0, 0); \
     } while (0)
 
-    bf16x8 af[2][TMI], wf[2][TNI];
+    if constexpr (FS) {
+        // ---- slice-scope fragment buffers: ALL fragments of slice kt+1 are read while the MFMAs of slice kt
+        // run, so the LDS read latency hides behind a whole slice of MFMAs (tiles with few MFMAs per K step
+        // cannot hide it behind one step).  Per slice: wait own reads of slice kt and own loads of slice
+        // kt+1, barrier (stage kt is free, slice kt+1 is complete), refill stage kt, read slice kt+1,
+        // multiply slice kt.
+        bf16x8 afs[2][KK][TMI], wfs[2][KK][TNI];
+#define MT_LOAD_SLICE(buf_, kt_)                                                                                   \
+    do {                                                                                                           \
+        const unsigned char* sb = lds + ((kt_) % STAGES) * Cfg::STAGE_BYTES;                                       \
+        _Pragma("unroll") for (int kk = 0; kk < KK; ++kk) {                                                        \
+            _Pragma("unroll") for (int i = 0; i < TMI; ++i)                                                        \
+                afs[buf_][kk][i] = *reinterpret_cast<const bf16x8*>(sb + fa_off[kk] + i * 32 * ROW_BYTES);         \
+            _Pragma("unroll") for (int j = 0; j < TNI; ++j)                                                        \
+                wfs[buf_][kk][j] = *reinterpret_cast<const bf16x8*>(sb + fw_off[kk] + j * 32 * ROW_BYTES);         \
+        }                                                                                                          \
+    } while (0)
+#define MT_MFMA_SLICE(buf_)                                                                                        \
+    do {                                                                                                           \
+        _Pragma("unroll") for (int kk = 0; kk < KK; ++kk)                                                          \
+            _Pragma("unroll") for (int i = 0; i < TMI; ++i)                                                        \
+                _Pragma("unroll") for (int j = 0; j < TNI; ++j)                                                    \
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfs[buf_][kk][j], afs[buf_][kk][i], acc[i][j], 0, 0, 0); \
+    } while (0)
+#define MT_ISSUE_SLICE(kt_)                                                                                        \
+    do {                                                                                                           \
+        _Pragma("unroll") for (int part = 0; part < KK; ++part) MT_ISSUE_PART(kt_, part);                          \
+    } while (0)
+        // one slice in the steady state (its refill exists): buffer index is a compile-time constant
+#define MT_STEADY(kt_, buf_)                                                                                       \
+    do {                                                                                                           \
+        wait_lgkmcnt0();                                                                                           \
+        wait_vmcnt<LPS*(STAGES - 2)>();                                                                            \
+        __builtin_amdgcn_s_barrier();                                                                              \
+        MT_ISSUE_SLICE((kt_) + STAGES);                                                                            \
+        MT_LOAD_SLICE((buf_) ^ 1, (kt_) + 1);                                                                      \
+        MT_MFMA_SLICE(buf_);                                                                                       \
+        if constexpr (kInterleave) interleave_step<TMI * TNI * KK, (TMI + TNI) * KK, LPS>();                       \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+    } while (0)
+        // one slice of the tail: the refill and even the next slice may not exist
+#define MT_TAIL(kt_, buf_)                                                                                         \
+    do {                                                                                                           \
+        wait_lgkmcnt0();                                                                                           \
+        if ((kt_) + 1 < KT) {                                                                                      \
+            wait_slices<LPS>(min(KT - 2 - (kt_), STAGES - 2));                                                     \
+            __builtin_amdgcn_s_barrier();                                                                          \
+            if ((kt_) + STAGES < KT) MT_ISSUE_SLICE((kt_) + STAGES);                                               \
+            MT_LOAD_SLICE((buf_) ^ 1, (kt_) + 1);                                                                  \
+        }                                                                                                          \
+        MT_MFMA_SLICE(buf_);                                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+    } while (0)
 
-    // prologue: slices 0..STAGES-2 in flight, wait for slice 0, then start refilling like a sync point would
 #pragma unroll
-    for (int p = 0; p < STAGES - 1; ++p)
-        if (p < KT) {
-#pragma unroll
-            for (int part = 0; part < KK; ++part) MT_ISSUE_PART(p, part);
+        for (int p = 0; p < STAGES - 1; ++p)
+            if (p < KT) MT_ISSUE_SLICE(p);
+        wait_slices<LPS>(min(STAGES - 2, KT - 1));
+        __builtin_amdgcn_s_barrier();
+        if (STAGES - 1 < KT) MT_ISSUE_SLICE(STAGES - 1);
+        MT_LOAD_SLICE(0, 0);
+        const int KT_pairs = (max(0, KT - STAGES) & ~1);      // slices handled two at a time, every refill exists
+        int kt = 0;
+        for (; kt < KT_pairs; kt += 2) {
+            MT_STEADY(kt, 0);
+            MT_STEADY(kt + 1, 1);
         }
-    wait_slices<LPS>(min(STAGES - 2, KT - 1));
-    __builtin_amdgcn_s_barrier();
-    if (STAGES - 1 < KT) MT_ISSUE_PART(STAGES - 1, 0);
-    MT_LOAD_FRAGS(0, 0, 0);
-
-    // steady state: every refill exists, no conditionals inside
-    const int KT_main = max(0, KT - STAGES);
-    int kt = 0;
-    for (; kt < KT_main; ++kt) {
-#pragma unroll
-        for (int kk = 0; kk < KK - 1; ++kk) {
-            MT_LOAD_FRAGS((kk + 1) & 1, kt, kk + 1);
-            MT_ISSUE_PART(kt + STAGES - 1, kk + 1);
-            MT_MFMAS(kk & 1);
+        for (; kt < KT; kt += 2) {
+            MT_TAIL(kt, 0);
+            if (kt + 1 < KT) MT_TAIL(kt + 1, 1);
+        }
+#undef MT_LOAD_SLICE
+#undef MT_MFMA_SLICE
+#undef MT_ISSUE_SLICE
+#undef MT_STEADY
+#undef MT_TAIL
+    } else {
+    bf16x8 af[2][TMI], wf[2][TNI];
+    
+        // prologue: slices 0..STAGES-2 in flight, wait for slice 0, then start refilling like a sync point would
+    #pragma unroll
+        for (int p = 0; p < STAGES - 1; ++p)
+            if (p < KT) {
+    #pragma unroll
+                for (int part = 0; part < KK; ++part) MT_ISSUE_PART(p, part);
+            }
+        wait_slices<LPS>(min(STAGES - 2, KT - 1));
+        __builtin_amdgcn_s_barrier();
+        if (STAGES - 1 < KT) MT_ISSUE_PART(STAGES - 1, 0);
+        MT_LOAD_FRAGS(0, 0, 0);
+    
+        // steady state: every refill exists, no conditionals inside
+        const int KT_main = max(0, KT - STAGES);
+        int kt = 0;
+        for (; kt < KT_main; ++kt) {
+    #pragma unroll
+            for (int kk = 0; kk < KK - 1; ++kk) {
+                MT_LOAD_FRAGS((kk + 1) & 1, kt, kk + 1);
+                MT_ISSUE_PART(kt + STAGES - 1, kk + 1);
+                MT_MFMAS(kk & 1);
+                if constexpr (kInterleave) interleave_step<TMI * TNI, TMI + TNI, LPP>();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // sync point: this wavefront's reads of slice kt are in registers; slice kt+1 must have landed
+            wait_lgkmcnt0();
+            wait_vmcnt<LPS*(STAGES - 2)>();
+            __builtin_amdgcn_s_barrier();
+            MT_ISSUE_PART(kt + STAGES, 0);          // stage kt % STAGES was just vacated by everyone
+            MT_LOAD_FRAGS(0, kt + 1, 0);
+            MT_MFMAS((KK - 1) & 1);
             if constexpr (kInterleave) interleave_step<TMI * TNI, TMI + TNI, LPP>();
             __builtin_amdgcn_sched_barrier(0);
         }
-        // sync point: this wavefront's reads of slice kt are in registers; slice kt+1 must have landed
-        wait_lgkmcnt0();
-        wait_vmcnt<LPS*(STAGES - 2)>();
-        __builtin_amdgcn_s_barrier();
-        MT_ISSUE_PART(kt + STAGES, 0);          // stage kt % STAGES was just vacated by everyone
-        MT_LOAD_FRAGS(0, kt + 1, 0);
-        MT_MFMAS((KK - 1) & 1);
-        if constexpr (kInterleave) interleave_step<TMI * TNI, TMI + TNI, LPP>();
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    // drain: the last min(KT, STAGES) slices; only slice KT-1 may still lack its parts 1..KK-1
-    if (kt + STAGES - 1 < KT) {
-#pragma unroll
-        for (int part = 1; part < KK; ++part) MT_ISSUE_PART(kt + STAGES - 1, part);
-    }
-    for (; kt < KT; ++kt) {
-#pragma unroll
-        for (int kk = 0; kk < KK - 1; ++kk) {
-            MT_LOAD_FRAGS((kk + 1) & 1, kt, kk + 1);
-            MT_MFMAS(kk & 1);
+        // drain: the last min(KT, STAGES) slices; only slice KT-1 may still lack its parts 1..KK-1
+        if (kt + STAGES - 1 < KT) {
+    #pragma unroll
+            for (int part = 1; part < KK; ++part) MT_ISSUE_PART(kt + STAGES - 1, part);
+        }
+        for (; kt < KT; ++kt) {
+    #pragma unroll
+            for (int kk = 0; kk < KK - 1; ++kk) {
+                MT_LOAD_FRAGS((kk + 1) & 1, kt, kk + 1);
+                MT_MFMAS(kk & 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (kt + 1 < KT) {
+                wait_lgkmcnt0();
+                wait_slices<LPS>(KT - 1 - (kt + 1));
+                __builtin_amdgcn_s_barrier();
+                MT_LOAD_FRAGS(0, kt + 1, 0);
+            }
+            MT_MFMAS((KK - 1) & 1);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (kt + 1 < KT) {
-            wait_lgkmcnt0();
-            wait_slices<LPS>(KT - 1 - (kt + 1));
-            __builtin_amdgcn_s_barrier();
-            MT_LOAD_FRAGS(0, kt + 1, 0);
-        }
-        MT_MFMAS((KK - 1) & 1);
-        __builtin_amdgcn_sched_barrier(0);
     }
 #undef MT_ISSUE_PART
 #undef MT_LOAD_FRAGS
@@ -422,14 +500,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, MINW) void gemm_bf16_kernel(
     }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int MINW, bool OUT_F32, int ACT>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int MINW, bool OUT_F32, int ACT, int FS>
 hipError_t launch_one(const GemmGroup& g, const GemmShape& s, hipStream_t stream)
 {
     using Cfg = GemmCfg<BM, BN, WAVES_M, WAVES_N, BK, STAGES>;
     const int tiles_m = (s.M + BM - 1) / BM, tiles_n = (s.N + BN - 1) / BN;
     const int total = s.G * s.splits * tiles_m * tiles_n;
     if (s.K % (BK * s.splits) != 0) return hipErrorInvalidValue;
-    auto kfn = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, OUT_F32, ACT>;
+    auto kfn = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, OUT_F32, ACT, FS>;
     static bool attr_set = false;
     if (Cfg::LDS_BYTES > 64 * 1024 && !attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
@@ -440,20 +518,20 @@ hipError_t launch_one(const GemmGroup& g, const GemmShape& s, hipStream_t stream
     return hipGetLastError();
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int MINW>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int MINW, int FS = 0>
 hipError_t launch_cfg(const GemmGroup& g, const GemmShape& s, hipStream_t stream)
 {
     // Instantiated epilogues: float32 output without activation (residual sums feeding LayerNorm) or with
     // tanh (pooler), and bf16 output with none / GELU(erf) / GELU(tanh).
     if (s.out_f32) {
-        if (s.act == ACT_TANH) return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, true, ACT_TANH>(g, s, stream);
+        if (s.act == ACT_TANH) return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, true, ACT_TANH, FS>(g, s, stream);
         if (s.act != ACT_NONE) return hipErrorInvalidValue;
-        return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, true, ACT_NONE>(g, s, stream);
+        return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, true, ACT_NONE, FS>(g, s, stream);
     }
     switch (s.act) {
-        case ACT_NONE: return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, false, ACT_NONE>(g, s, stream);
-        case ACT_GELU_ERF: return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, false, ACT_GELU_ERF>(g, s, stream);
-        case ACT_GELU_TANH: return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, false, ACT_GELU_TANH>(g, s, stream);
+        case ACT_NONE: return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, false, ACT_NONE, FS>(g, s, stream);
+        case ACT_GELU_ERF: return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, false, ACT_GELU_ERF, FS>(g, s, stream);
+        case ACT_GELU_TANH: return launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, false, ACT_GELU_TANH, FS>(g, s, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -480,13 +558,14 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
         // number of 256x256 tiles the bound implies and errs towards the smaller tile when few.
         //   many tiles: 256x256 with 8 wavefronts (least L2 traffic per flop); the GELU epilogue's vector
         //   work instead prefers 8 wavefronts of 64x64 on a 256x128 tile, two workgroups per CU;
-        //   few tiles (single problem): 128x128, two or three workgroups per CU.
+        //   few tiles (single problem): 128x128, two or three workgroups per CU, slice-scope fragment buffers
+        //   (4 MFMAs per K step cannot hide an LDS read behind one step).
         const long t256 = (long)s.G * s.splits * ((s.M + 255) / 256) * ((s.N + 255) / 256);
         const bool gelu = s.act == ACT_GELU_ERF || s.act == ACT_GELU_TANH;
         if (t256 >= 256) sel = gelu ? 11 : MT_GEMM_BIG_TILE;
         else if (s.K / s.splits >= 2048) sel = 1;
-        else if (s.N >= 2048) sel = 6;
-        else sel = 12;
+        else if (s.N >= 2048) sel = 19;
+        else sel = 18;
     }
     switch (sel) {
         case 2: return launch_cfg<256, 128, 2, 2, 32, 3, 2>(g, s, stream);   // 72 KB LDS: two workgroups per CU
@@ -504,6 +583,13 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
         case 15: return launch_cfg<128, 128, 2, 2, 32, 8, 1>(g, s, stream);  // 128 KB: 7 slices of 32 ahead
         case 16: return launch_cfg<256, 128, 4, 2, 32, 6, 1>(g, s, stream);  // 144 KB, 8 wavefronts
         case 17: return launch_cfg<128, 128, 2, 2, 32, 6, 1>(g, s, stream);  // 96 KB
+        // slice-scope fragment buffers
+        case 18: return launch_cfg<128, 128, 2, 2, 32, 3, 2, 1>(g, s, stream);
+        case 19: return launch_cfg<128, 128, 2, 2, 64, 2, 2, 1>(g, s, stream);
+        case 20: return launch_cfg<128, 128, 2, 2, 32, 4, 2, 1>(g, s, stream);
+        case 21: return launch_cfg<256, 128, 4, 2, 32, 3, 2, 1>(g, s, stream);
+        case 22: return launch_cfg<256, 256, 2, 4, 32, 4, 2, 1>(g, s, stream);
+        case 23: return launch_cfg<128, 128, 2, 2, 32, 5, 2, 1>(g, s, stream);  // 80 KB: two workgroups per CU, 4 slices ahead
         default: return launch_cfg<128, 128, 2, 2, 32, 4, 2>(g, s, stream);  // 64 KB LDS
     }
 }
