@@ -41,6 +41,8 @@ def lib():
         L.orc_overhead.restype = C.c_int
         L.orc_mt_forward.restype = C.c_int
         L.orc_st_forward.restype = C.c_int
+        L.orc_mt_forward_typed.restype = C.c_int
+        L.orc_st_forward_typed.restype = C.c_int
         _lib = L
     return _lib
 
@@ -148,25 +150,30 @@ class Oracle:
         for t, p in enumerate(self.task_params):
             assert p.size == L.orc_task_param_count(C.byref(self.cfg), C.byref(self.tasks[t])), f"task {t} parameter count"
 
-    def mt_forward(self, ids, mask, want_hidden=False):
+    def mt_forward(self, ids, mask, want_hidden=False, type_ids=None):
+        """type_ids: optional [B,S] segment ids in [0, type_vocab); None = segment 0 everywhere."""
         ids, mask = _i32(ids), _i32(mask)
+        tt = _i32(type_ids) if type_ids is not None else None
         b, s = ids.shape
         sp = self.spec
         logits = np.empty((b, sp.n_logits), dtype=np.float32)
         hidden = np.empty((sp.n_trunk_layers + 1, b, s, sp.hidden), dtype=np.float32) if want_hidden else None
         ptrs = (C.POINTER(C.c_float) * len(self.task_params))(*[_fp(p) for p in self.task_params])
-        rc = lib().orc_mt_forward(C.byref(self.cfg), self.tasks, _fp(self.trunk), ptrs, _ip(ids), _ip(mask),
-                                  C.c_int64(b), C.c_int64(s), _fp(logits), _fp(hidden))
+        rc = lib().orc_mt_forward_typed(C.byref(self.cfg), self.tasks, _fp(self.trunk), ptrs, _ip(ids),
+                                        _ip(tt) if tt is not None else None, _ip(mask),
+                                        C.c_int64(b), C.c_int64(s), _fp(logits), _fp(hidden))
         if rc != 0:
             raise ValueError("invalid task table")
         return (logits, hidden) if want_hidden else logits
 
-    def st_forward(self, t, ids, mask):
+    def st_forward(self, t, ids, mask, type_ids=None):
         ids, mask = _i32(ids), _i32(mask)
+        tt = _i32(type_ids) if type_ids is not None else None
         b, s = ids.shape
         logits = np.empty((b, self.spec.tasks[t].n_classes), dtype=np.float32)
-        rc = lib().orc_st_forward(C.byref(self.cfg), C.byref(self.tasks[t]), _fp(self.trunk), _fp(self.task_params[t]),
-                                  _ip(ids), _ip(mask), C.c_int64(b), C.c_int64(s), _fp(logits))
+        rc = lib().orc_st_forward_typed(C.byref(self.cfg), C.byref(self.tasks[t]), _fp(self.trunk), _fp(self.task_params[t]),
+                                        _ip(ids), _ip(tt) if tt is not None else None, _ip(mask), C.c_int64(b), C.c_int64(s),
+                                        _fp(logits))
         if rc != 0:
             raise ValueError("invalid task")
         return logits

@@ -73,14 +73,15 @@ def _layer(P, pre, X, mask, heads, eps, tanh_form):
     return out
 
 
-def student_logits(trunk, task, ids, mask, *, fork_layer, n_layers, heads, eps=1e-12, tanh_form=False):
+def student_logits(trunk, task, ids, mask, *, fork_layer, n_layers, heads, eps=1e-12, tanh_form=False, type_ids=None):
     """Logits of one student for ONE sequence.  trunk/task: dicts from unpack(); ids, mask: length-S lists."""
     S = len(ids)
     word, pos, typ = trunk["word_emb"], trunk["pos_emb"], trunk["type_emb"]
     H = word.shape[1]
     X = []
     for s in range(S):
-        e = [float(word[ids[s]][c] + pos[s][c] + typ[0][c]) for c in range(H)]
+        seg = type_ids[s] if type_ids is not None else 0
+        e = [float(word[ids[s]][c] + pos[s][c] + typ[seg][c]) for c in range(H)]
         X.append(_layernorm(e, trunk["emb_ln_g"].tolist(), trunk["emb_ln_b"].tolist(), eps))
     for l in range(fork_layer):
         X = _layer(trunk, f"L{l}.", X, mask, heads, eps, tanh_form)

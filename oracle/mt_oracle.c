@@ -214,7 +214,18 @@ static layer_params slice_layer(const float *p, int64_t H, int64_t F)
 /* ---------------------------------------------------------------- model pieces */
 
 /* X0[b][s][:] = LN(word_emb[ids[b][s]] + pos_emb[s] + type_emb[0]) */
+/* Embeddings with per-token segment ids: word[id] + pos[s] + type[type_ids[b][s]], then LayerNorm.
+ * type_ids == NULL means segment 0 everywhere (single-sentence inputs). */
+void orc_embed_typed(const orc_config *c, const float *trunk, const int32_t *ids, const int32_t *type_ids, int64_t B, int64_t S,
+                     float *X0);
+
 void orc_embed(const orc_config *c, const float *trunk, const int32_t *ids, int64_t B, int64_t S, float *X0)
+{
+    orc_embed_typed(c, trunk, ids, NULL, B, S, X0);
+}
+
+void orc_embed_typed(const orc_config *c, const float *trunk, const int32_t *ids, const int32_t *type_ids, int64_t B, int64_t S,
+                     float *X0)
 {
     const int64_t H = c->hidden;
     const float *word = trunk;
@@ -227,7 +238,8 @@ void orc_embed(const orc_config *c, const float *trunk, const int32_t *ids, int6
         for (int64_t s = 0; s < S; ++s)
             for (int64_t i = 0; i < H; ++i)
                 e[(b * S + s) * H + i] = (float)((double)word[(int64_t)ids[b * S + s] * H + i]
-                                                 + (double)pos[s * H + i] + (double)type[i]);
+                                                 + (double)pos[s * H + i]
+                                                 + (double)type[(int64_t)(type_ids ? type_ids[b * S + s] : 0) * H + i]);
     orc_layernorm(e, NULL, B * S, H, g, bt, c->ln_eps, X0);
     free(e);
 }
@@ -295,8 +307,20 @@ int orc_overhead(const orc_task *tasks, int n_tasks)
  * hidden_out (optional): [n_trunk_layers+1][B][S][H], the embeddings followed by every trunk layer output.
  * Returns 0, or -1 on an invalid task table.
  */
+int orc_mt_forward_typed(const orc_config *c, const orc_task *tasks, const float *trunk, const float *const *task_params,
+                         const int32_t *ids, const int32_t *type_ids, const int32_t *mask, int64_t B, int64_t S, float *logits,
+                         float *hidden_out);
+
 int orc_mt_forward(const orc_config *c, const orc_task *tasks, const float *trunk, const float *const *task_params,
                    const int32_t *ids, const int32_t *mask, int64_t B, int64_t S, float *logits, float *hidden_out)
+{
+    return orc_mt_forward_typed(c, tasks, trunk, task_params, ids, NULL, mask, B, S, logits, hidden_out);
+}
+
+/* The same with segment ids (NULL = all 0); values must lie in [0, type_vocab). */
+int orc_mt_forward_typed(const orc_config *c, const orc_task *tasks, const float *trunk, const float *const *task_params,
+                         const int32_t *ids, const int32_t *type_ids, const int32_t *mask, int64_t B, int64_t S, float *logits,
+                         float *hidden_out)
 {
     const int64_t H = c->hidden, F = c->ffn, MH = B * S * H;
     const int D = c->n_trunk_layers;
@@ -309,7 +333,7 @@ int orc_mt_forward(const orc_config *c, const orc_task *tasks, const float *trun
     const int64_t lsz = orc_layer_param_count(H, F);
 
     float *taps = (float *)malloc(sizeof(float) * (size_t)(MH * (D + 1)));   /* X^(0..D) */
-    orc_embed(c, trunk, ids, B, S, taps);
+    orc_embed_typed(c, trunk, ids, type_ids, B, S, taps);
     for (int l = 0; l < D; ++l)
         orc_encoder_layer(c, layers + l * lsz, taps + (int64_t)l * MH, mask, B, S, taps + (int64_t)(l + 1) * MH);
     if (hidden_out) memcpy(hidden_out, taps, sizeof(float) * (size_t)(MH * (D + 1)));
@@ -332,8 +356,17 @@ int orc_mt_forward(const orc_config *c, const orc_task *tasks, const float *trun
 }
 
 /* Student model of one task on its own.  logits: [B][C_t]. */
+int orc_st_forward_typed(const orc_config *c, const orc_task *task, const float *trunk, const float *task_param,
+                         const int32_t *ids, const int32_t *type_ids, const int32_t *mask, int64_t B, int64_t S, float *logits);
+
 int orc_st_forward(const orc_config *c, const orc_task *task, const float *trunk, const float *task_param,
                    const int32_t *ids, const int32_t *mask, int64_t B, int64_t S, float *logits)
+{
+    return orc_st_forward_typed(c, task, trunk, task_param, ids, NULL, mask, B, S, logits);
+}
+
+int orc_st_forward_typed(const orc_config *c, const orc_task *task, const float *trunk, const float *task_param,
+                         const int32_t *ids, const int32_t *type_ids, const int32_t *mask, int64_t B, int64_t S, float *logits)
 {
     const int64_t H = c->hidden, F = c->ffn, MH = B * S * H;
     if (task->fork_layer < 0 || task->fork_layer > c->n_trunk_layers || task->n_layers < 0 || task->n_classes < 1) return -1;
@@ -341,7 +374,7 @@ int orc_st_forward(const orc_config *c, const orc_task *task, const float *trunk
     const int64_t lsz = orc_layer_param_count(H, F);
     float *xa = (float *)malloc(sizeof(float) * (size_t)MH);
     float *xb = (float *)malloc(sizeof(float) * (size_t)MH);
-    orc_embed(c, trunk, ids, B, S, xa);
+    orc_embed_typed(c, trunk, ids, type_ids, B, S, xa);
     float *cur = xa, *nxt = xb;
     for (int l = 0; l < task->fork_layer; ++l) {
         orc_encoder_layer(c, layers + l * lsz, cur, mask, B, S, nxt);

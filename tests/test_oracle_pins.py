@@ -217,6 +217,54 @@ def test_tanh_gelu_switch_reaches_the_model():
     assert np.abs(lg_t[0, :2] - np.array(ref)).max() <= 5e-6
 
 
+# ------------------------------------------------------------------ segment (token type) ids for sentence-pair inputs
+
+def _segments(mask, rng):
+    """Sentence-pair style ids: 0 up to a split point inside the sequence, 1 after it."""
+    tt = np.zeros_like(mask)
+    for b in range(mask.shape[0]):
+        n = int(mask[b].sum())
+        cut = int(rng.integers(1, max(2, n)))
+        tt[b, cut:] = 1
+    return tt
+
+
+def test_segment_ids_zero_is_the_default_and_brute_force_agrees():
+    spec = MINI
+    tr, tri, tp, tpi = build(spec, stress=True, std=0.1)
+    ids, mask, _ = ms.make_inputs(spec)
+    orc = oracle.Oracle(spec, tr, tp)
+    base = orc.mt_forward(ids, mask)
+    np.testing.assert_array_equal(orc.mt_forward(ids, mask, type_ids=np.zeros_like(ids)), base)
+    tt = _segments(mask, np.random.default_rng(5))
+    lg = orc.mt_forward(ids, mask, type_ids=tt)
+    assert np.abs(lg - base).max() > 1e-6                         # the second table row is really used
+    T = brute_tiny.unpack(tr, tri)
+    col = 0
+    for t, task in enumerate(spec.tasks):
+        K = brute_tiny.unpack(tp[t], tpi[t])
+        np.testing.assert_array_equal(orc.st_forward(t, ids, mask, type_ids=tt), lg[:, col:col + task.n_classes])
+        for b in range(ids.shape[0]):
+            ref = brute_tiny.student_logits(T, K, ids[b].tolist(), mask[b].tolist(), fork_layer=task.fork_layer, n_layers=task.n_layers,
+                                            heads=spec.heads, eps=spec.ln_eps, type_ids=tt[b].tolist())
+            assert np.abs(lg[b, col:col + task.n_classes] - np.array(ref)).max() <= 5e-6
+        col += task.n_classes
+
+
+def test_segment_ids_relabelling_invariance():
+    """Swapping the two rows of the type table and flipping every id is the same model: identical logits."""
+    spec = MINI
+    tr, tri, tp, _ = build(spec, stress=True, std=0.1)
+    ids, mask, _ = ms.make_inputs(spec)
+    tt = _segments(mask, np.random.default_rng(6))
+    lg = oracle.Oracle(spec, tr, tp).mt_forward(ids, mask, type_ids=tt)
+    off = {n: o for n, _, o in tri}["type_emb"]
+    H = spec.hidden
+    tr2 = tr.copy()
+    tr2[off:off + H], tr2[off + H:off + 2 * H] = tr[off + H:off + 2 * H], tr[off:off + H]
+    np.testing.assert_array_equal(oracle.Oracle(spec, tr2, tp).mt_forward(ids, mask, type_ids=1 - tt), lg)
+
+
 # ------------------------------------------------------------------ P2 / P3: merging is exact, tasks are isolated
 
 @pytest.mark.parametrize("spec", [ms.get_config("tiny"), MINI])
