@@ -136,6 +136,15 @@ int mt_load_weights(mt_model* m, int32_t scope, const void* h_blob, size_t nbyte
 int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_mask, int32_t batch, int32_t seq,
                const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream);
 
+/*
+ * mt_forward with segment (token type) ids for sentence-pair inputs, as in the BERT input representation
+ * the student models are built on (Section 3): the embedding of a token adds row d_token_type_ids[b][s]
+ * of the type table instead of row 0.  d_token_type_ids: [batch][seq] int32 device array, values clamped
+ * into [0, type_vocab) by the kernel, or NULL (then identical to mt_forward).  Everything else as above.
+ */
+int mt_forward_typed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask, int32_t batch, int32_t seq,
+               const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream);
+
 /* Column of task t's first logit, or MT_ERR_SHAPE.  mt_n_logits = C_tot. */
 int mt_logit_offset(const mt_model* m, int32_t task);
 int mt_n_logits(const mt_model* m);

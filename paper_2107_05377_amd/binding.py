@@ -25,7 +25,7 @@ KERNEL_CLASSES = ["embed", "gemm_qkv", "attn", "gemm_out", "ln", "gemm_ffn1", "g
 EXPORTS = ["mt_create", "mt_destroy", "mt_weight_bytes", "mt_workspace_bytes", "mt_bind", "mt_load_weights",
            "mt_forward", "mt_logit_offset", "mt_n_logits", "mt_layer_count", "mt_last_error", "mt_error_name",
            "mt_read_hidden", "mt_profile_enable", "mt_profile_read", "mt_op_linear", "mt_op_attention",
-           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak"]
+           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed"]
 
 
 class mt_task_desc(C.Structure):
@@ -62,6 +62,7 @@ def lib():
         L.mt_bind.argtypes = [vp, vp, sz, vp, sz]
         L.mt_load_weights.argtypes = [vp, i32, vp, sz, vp]
         L.mt_forward.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
+        L.mt_forward_typed.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_logit_offset.argtypes = [vp, i32]
         L.mt_n_logits.argtypes = [vp]
         L.mt_layer_count.argtypes = [vp]
@@ -185,8 +186,9 @@ class Model:
     def load_params(self, scope: int, flat: np.ndarray, n_tensors: int):
         self.load_weights(scope, pack_blob(scope, n_tensors, flat))
 
-    def forward(self, ids, mask, out=None, task_mask=None):
-        """ids, mask: int32 CUDA tensors [B,S]; returns the float32 CUDA tensor [B, C_tot] (enqueued, not synced)."""
+    def forward(self, ids, mask, out=None, task_mask=None, type_ids=None):
+        """ids, mask (and optional segment ids type_ids): int32 CUDA tensors [B,S]; returns the float32 CUDA
+        tensor [B, C_tot] (enqueued, not synced)."""
         import torch
         b, s = ids.shape
         if out is None:
@@ -194,7 +196,11 @@ class Model:
         tm = None
         if task_mask is not None:
             tm = (C.c_uint8 * len(task_mask))(*[1 if v else 0 for v in task_mask])
-        self._check(lib().mt_forward(self.h, _ptr(ids), _ptr(mask), b, s, tm, _ptr(out), _stream()))
+        if type_ids is None:
+            self._check(lib().mt_forward(self.h, _ptr(ids), _ptr(mask), b, s, tm, _ptr(out), _stream()))
+        else:
+            assert type_ids.shape == ids.shape
+            self._check(lib().mt_forward_typed(self.h, _ptr(ids), _ptr(type_ids), _ptr(mask), b, s, tm, _ptr(out), _stream()))
         return out
 
     def read_hidden(self, task: int, layer: int, batch: int, seq: int):

@@ -87,7 +87,7 @@ hipError_t launch_layernorm(const LnGroup& g, int G, int M, const int32_t* d_M, 
 
 // X0[r] = LN(word[ids[p]] + pos[p % S] + type[0]) with p = src[r] for the kept rows r < *d_M (p = r and all
 // B*S rows when src is null); tables are bf16 (emb_bf16 != 0) or fp32.
-hipError_t launch_embed_ln(const int32_t* ids, const int32_t* src, const int32_t* d_M, int B, int S, int H, int vocab, const void* word, const void* pos,
+hipError_t launch_embed_ln(const int32_t* ids, const int32_t* type_ids /* [B*S] segment ids or NULL */, int type_vocab, const int32_t* src, const int32_t* d_M, int B, int S, int H, int vocab, const void* word, const void* pos,
                            const void* type, int emb_bf16, const float* gamma, const float* beta, float eps,
                            float* out_f32, bf16_t* out_bf16, hipStream_t stream);
 

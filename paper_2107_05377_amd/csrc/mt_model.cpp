@@ -811,7 +811,7 @@ int mt_load_weights(mt_model* m, int32_t scope, const void* h_blob, size_t nbyte
     return MT_OK;
 }
 
-int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_mask, int32_t batch, int32_t seq,
+int mt_forward_typed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask, int32_t batch, int32_t seq,
                const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream)
 {
     if (!m) return MT_ERR_NULL;
@@ -859,7 +859,7 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
     trunk_out(0, 0, cur_f, cur_b);
     L.begin(MT_K_EMBED);
     L.check(launch_build_row_map(d_attn_mask, B, S, rm, L.st));
-    L.check(launch_embed_ln(d_input_ids, rm.src, rm.n_rows, B, S, H, m->cfg.vocab, W + m->w_word, W + m->w_pos, W + m->w_type, bf ? 1 : 0,
+    L.check(launch_embed_ln(d_input_ids, d_token_type_ids, m->cfg.type_vocab, rm.src, rm.n_rows, B, S, H, m->cfg.vocab, W + m->w_word, W + m->w_pos, W + m->w_type, bf ? 1 : 0,
                             (const float*)(W + m->w_embg), (const float*)(W + m->w_embb), m->cfg.ln_eps, cur_f,
                             (bf16_t*)cur_b, L.st));
     L.end();
@@ -966,6 +966,12 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
     if (L.first_err != hipSuccess) return fail(m, MT_ERR_HIP, "mt_forward: launch failed: %s", hipGetErrorString(L.first_err));
     for (int t : enabled) m->last_enabled[t] = 1;
     return MT_OK;
+}
+
+int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_mask, int32_t batch, int32_t seq,
+               const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream)
+{
+    return mt_forward_typed(m, d_input_ids, nullptr, d_attn_mask, batch, seq, h_task_mask, d_out_logits, hip_stream);
 }
 
 int mt_read_hidden(mt_model* m, int32_t task, int32_t layer, float* d_out, size_t out_bytes, void* hip_stream)

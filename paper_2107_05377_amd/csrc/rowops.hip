@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256) void layernorm_any(LnGroup g, int M, const int
 }
 
 template <typename TE, int NV>
-__global__ __launch_bounds__(256) void embed_ln_fast(const int32_t* ids, const int32_t* __restrict__ src,
+__global__ __launch_bounds__(256) void embed_ln_fast(const int32_t* ids, const int32_t* __restrict__ type_ids, int type_vocab, const int32_t* __restrict__ src,
                                                      const int32_t* __restrict__ d_M, int M, int S, int H, int vocab,
                                                      const TE* word, const TE* pos, const TE* type,
                                                      const float* gamma, const float* beta, float eps,
@@ -144,6 +144,9 @@ __global__ __launch_bounds__(256) void embed_ln_fast(const int32_t* ids, const i
     int id = ids[p_idx];
     id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
     const int s = p_idx % S;
+    int seg = type_ids ? type_ids[p_idx] : 0;
+    seg = seg < 0 ? 0 : (seg >= type_vocab ? type_vocab - 1 : seg);
+    type += (size_t)seg * H;
     const TE* w = word + (size_t)id * H;
     const TE* p = pos + (size_t)s * H;
     float4 v[NV];
@@ -158,7 +161,7 @@ __global__ __launch_bounds__(256) void embed_ln_fast(const int32_t* ids, const i
 }
 
 template <typename TE>
-__global__ __launch_bounds__(256) void embed_ln_any(const int32_t* ids, const int32_t* __restrict__ src,
+__global__ __launch_bounds__(256) void embed_ln_any(const int32_t* ids, const int32_t* __restrict__ type_ids, int type_vocab, const int32_t* __restrict__ src,
                                                     const int32_t* __restrict__ d_M, int M, int S, int H, int vocab,
                                                     const TE* word, const TE* pos, const TE* type,
                                                     const float* gamma, const float* beta, float eps,
@@ -172,6 +175,9 @@ __global__ __launch_bounds__(256) void embed_ln_any(const int32_t* ids, const in
     int id = ids[p_idx];
     id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
     const int sidx = p_idx % S;
+    int seg = type_ids ? type_ids[p_idx] : 0;
+    seg = seg < 0 ? 0 : (seg >= type_vocab ? type_vocab - 1 : seg);
+    type += (size_t)seg * H;
     const TE* w = word + (size_t)id * H;
     const TE* p = pos + (size_t)sidx * H;
     float s = 0.f;
@@ -192,22 +198,22 @@ __global__ __launch_bounds__(256) void embed_ln_any(const int32_t* ids, const in
 }
 
 template <typename TE>
-hipError_t embed_dispatch(const int32_t* ids, const int32_t* src, const int32_t* d_M, int B, int S, int H, int vocab, const TE* word, const TE* pos,
+hipError_t embed_dispatch(const int32_t* ids, const int32_t* type_ids, int type_vocab, const int32_t* src, const int32_t* d_M, int B, int S, int H, int vocab, const TE* word, const TE* pos,
                           const TE* type, const float* gamma, const float* beta, float eps, float* of, __bf16* ob,
                           hipStream_t st)
 {
     const int M = B * S;
     dim3 grid((M + kRowsPerBlock - 1) / kRowsPerBlock), block(256);
     if (H == 768)
-        hipLaunchKernelGGL((embed_ln_fast<TE, 3>), grid, block, 0, st, ids, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+        hipLaunchKernelGGL((embed_ln_fast<TE, 3>), grid, block, 0, st, ids, type_ids, type_vocab, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
     else if (H == 1024)
-        hipLaunchKernelGGL((embed_ln_fast<TE, 4>), grid, block, 0, st, ids, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+        hipLaunchKernelGGL((embed_ln_fast<TE, 4>), grid, block, 0, st, ids, type_ids, type_vocab, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
     else if (H == 256)
-        hipLaunchKernelGGL((embed_ln_fast<TE, 1>), grid, block, 0, st, ids, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+        hipLaunchKernelGGL((embed_ln_fast<TE, 1>), grid, block, 0, st, ids, type_ids, type_vocab, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
     else if (H == 512)
-        hipLaunchKernelGGL((embed_ln_fast<TE, 2>), grid, block, 0, st, ids, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+        hipLaunchKernelGGL((embed_ln_fast<TE, 2>), grid, block, 0, st, ids, type_ids, type_vocab, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
     else
-        hipLaunchKernelGGL((embed_ln_any<TE>), grid, block, 0, st, ids, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
+        hipLaunchKernelGGL((embed_ln_any<TE>), grid, block, 0, st, ids, type_ids, type_vocab, src, d_M, M, S, H, vocab, word, pos, type, gamma, beta, eps, of, ob);
     return hipGetLastError();
 }
 
@@ -418,16 +424,16 @@ hipError_t launch_layernorm(const LnGroup& g, int G, int M, const int32_t* d_M, 
     return hipGetLastError();
 }
 
-hipError_t launch_embed_ln(const int32_t* ids, const int32_t* src, const int32_t* d_M, int B, int S, int H, int vocab, const void* word, const void* pos,
+hipError_t launch_embed_ln(const int32_t* ids, const int32_t* type_ids, int type_vocab, const int32_t* src, const int32_t* d_M, int B, int S, int H, int vocab, const void* word, const void* pos,
                            const void* type, int emb_bf16, const float* gamma, const float* beta, float eps,
                            float* out_f32, bf16_t* out_bf16, hipStream_t stream)
 {
     if (B * S <= 0) return hipSuccess;
     __bf16* ob = reinterpret_cast<__bf16*>(out_bf16);
     if (emb_bf16)
-        return embed_dispatch<__bf16>(ids, src, d_M, B, S, H, vocab, (const __bf16*)word, (const __bf16*)pos, (const __bf16*)type,
+        return embed_dispatch<__bf16>(ids, type_ids, type_vocab, src, d_M, B, S, H, vocab, (const __bf16*)word, (const __bf16*)pos, (const __bf16*)type,
                                       gamma, beta, eps, out_f32, ob, stream);
-    return embed_dispatch<float>(ids, src, d_M, B, S, H, vocab, (const float*)word, (const float*)pos, (const float*)type,
+    return embed_dispatch<float>(ids, type_ids, type_vocab, src, d_M, B, S, H, vocab, (const float*)word, (const float*)pos, (const float*)type,
                                  gamma, beta, eps, out_f32, ob, stream);
 }
 

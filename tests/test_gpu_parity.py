@@ -464,3 +464,31 @@ def test_replicas_in_flight_match_serial(base_model):
         for i in range(len(batches)):
             assert torch.equal(outs[i], serial[i]), f"round {rounds}, batch {i}"
     reps[1].close()
+
+
+def test_segment_ids_match_oracle():
+    """Sentence-pair inputs: the typed forward adds the segment's row of the type table (fp32 mode to 1e-4,
+    bf16 mode to the logit tolerance); all-zero ids and NULL give the plain forward bit for bit."""
+    mini = ms.MTSpec("mini", vocab=50, hidden=32, heads=4, ffn=64, max_pos=24, n_trunk_layers=3,
+                     tasks=(ms.TaskSpec(1, 2, 2), ms.TaskSpec(3, 1, 3), ms.TaskSpec(2, 0, 1), ms.TaskSpec(0, 1, 2)),
+                     precision="fp32", batch=3, seq=12, len_lo=3, len_hi=12, input_seed=77, weights_seed=4242)
+    small = ms.MTSpec("pair_bf16", vocab=500, hidden=128, heads=2, ffn=256, max_pos=64, n_trunk_layers=2,
+                      tasks=(ms.TaskSpec(2, 2, 3), ms.TaskSpec(1, 1, 2), ms.TaskSpec(0, 1, 2)), precision="bf16",
+                      batch=6, seq=48, len_lo=5, len_hi=48, input_seed=91)
+    for spec, stress in ((mini, True), (small, True)):
+        tr, tri, tps = _params(spec, stress, std=0.1 if spec.precision == "fp32" else 0.02)
+        model = _load(spec, tr, tri, tps)
+        ids, mask, lengths = ms.make_inputs(spec)
+        tt = np.zeros_like(ids)
+        for b in range(ids.shape[0]):
+            tt[b, max(1, int(lengths[b]) // 2):] = 1
+        plain = model.forward(dev(ids), dev(mask)).cpu().numpy()
+        assert np.array_equal(model.forward(dev(ids), dev(mask), type_ids=dev(np.zeros_like(ids))).cpu().numpy(), plain)
+        got = model.forward(dev(ids), dev(mask), type_ids=dev(tt)).cpu().numpy()
+        ref = oracle.Oracle(spec, tr, [p for p, _ in tps]).mt_forward(ids, mask, type_ids=tt)
+        assert np.abs(got - plain).max() > 1e-5
+        if spec.precision == "fp32":
+            assert max(rel_err_per_task(spec, got, ref)) <= 1e-4
+        else:
+            assert np.abs(got - ref).max() <= 2e-2
+        model.close()
