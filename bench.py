@@ -195,19 +195,29 @@ def main():
     flops = gemm_flops_per_forward(spec, rows, B)
     n_full, n_first = layer_kinds(spec)
     assert n_full + n_first == n_layers
+    # An event record costs the command processor a few microseconds, so the event-bracketed durations sum to
+    # more than the same launches take back to back without events (ms_serial; kernels of one forward run
+    # gap-free on one stream).  The excess, spread evenly over the launches, is taken off every duration.
+    launches_total = sum(n for _, n in prof.values()) / args.steps
+    raw_sum_ms = sum(ms_tot for ms_tot, _ in prof.values()) / args.steps
+    event_overhead_ms = max(0.0, (raw_sum_ms - ms_serial) / launches_total)
     kernels = {}
+    dur = {}
     for k, (ms_tot, n) in prof.items():
         if n == 0:
             continue
-        ent = {"launches_per_step": n / args.steps, "ms_per_step": ms_tot / args.steps, "avg_us": 1e3 * ms_tot / n}
+        dur[k] = max(1e-6, ms_tot / args.steps - event_overhead_ms * n / args.steps)      # ms per step, corrected
+        ent = {"launches_per_step": n / args.steps, "ms_per_step": dur[k], "avg_us": 1e3 * dur[k] / (n / args.steps),
+               "ms_per_step_raw_events": ms_tot / args.steps}
         if k in flops:
-            ent["tflops"] = flops[k] * args.steps / (ms_tot * 1e-3) / 1e12
+            ent["tflops"] = flops[k] / (dur[k] * 1e-3) / 1e12
         kernels[k] = ent
     # the dominant kernel: the tiled matrix-core contraction over all token rows (the one-row-per-sequence
     # contractions of the branches' last layers run in the few-row kernel and are listed on their own)
     main = [k for k in flops if k != "gemm_first"]
     main_flops = sum(flops[k] for k in main)
-    gemm_ms = sum(prof[k][0] for k in main) / args.steps
+    gemm_ms = sum(dur[k] for k in main)
+    gemm_ms_raw = sum(prof[k][0] for k in main) / args.steps
     gemm_launches = sum(prof[k][1] for k in main) / args.steps
     gemm_tflops = main_flops / (gemm_ms * 1e-3) / 1e12
     bf16 = spec.precision == "bf16"
@@ -221,7 +231,8 @@ def main():
                 "frac_of_measured_peak": (gemm_tflops / measured_peak) if measured_peak else None,
                 "flops_per_launch": main_flops / gemm_launches, "avg_launch_us": 1e3 * gemm_ms / gemm_launches,
                 "flops_counted": "executed: real (unpadded) token rows only",
-                "launches_per_step": gemm_launches, "gemm_ms_per_step": gemm_ms}
+                "launches_per_step": gemm_launches, "gemm_ms_per_step": gemm_ms,
+                "avg_launch_us_raw_events": 1e3 * gemm_ms_raw / gemm_launches, "event_overhead_us_per_launch": 1e3 * event_overhead_ms}
 
     h = spec.hidden
     per_layer = 8.0 * S * h * h + 4.0 * S * h * spec.ffn + 4.0 * S * S * h

@@ -63,6 +63,7 @@ struct ClsScratch {   // per task with own layers: compact [max_batch] x ... buf
 struct ProfRec {
     int klass;
     hipEvent_t t0, t1;
+    bool owns_t0;      // false: t0 is the previous record's t1 (one event between back-to-back launches)
 };
 
 }  // namespace
@@ -229,21 +230,35 @@ struct Launcher {
     hipStream_t st;
     hipError_t first_err = hipSuccess;
 
+    bool chained = false;      // the previous launch of this forward left its end event as our start
+
+    bool take_event(hipEvent_t* e)
+    {
+        if (m->event_pool.empty()) {
+            if (hipEventCreate(e) != hipSuccess) { first_err = hipErrorOutOfMemory; return false; }
+        } else {
+            *e = m->event_pool.back();
+            m->event_pool.pop_back();
+        }
+        return true;
+    }
+    // Launches of a forward follow one another on one stream, so ONE event separates two of them: a launch's
+    // duration runs from the end of the previous launch to its own end (the first one records its own start).
     void begin(int klass)
     {
         if (!m->profiling || first_err != hipSuccess) return;
         ProfRec r;
         r.klass = klass;
-        for (hipEvent_t* e : {&r.t0, &r.t1}) {
-            if (m->event_pool.empty()) {
-                if (hipEventCreate(e) != hipSuccess) { first_err = hipErrorOutOfMemory; return; }
-            } else {
-                *e = m->event_pool.back();
-                m->event_pool.pop_back();
-            }
+        r.owns_t0 = !(chained && !m->prof.empty());
+        if (r.owns_t0) {
+            if (!take_event(&r.t0)) return;
+            (void)hipEventRecord(r.t0, st);
+        } else {
+            r.t0 = m->prof.back().t1;
         }
-        (void)hipEventRecord(r.t0, st);
+        if (!take_event(&r.t1)) return;
         m->prof.push_back(r);
+        chained = true;
     }
     void end()
     {
@@ -665,7 +680,7 @@ void mt_destroy(mt_model* m)
 {
     if (!m) return;
     for (auto& r : m->prof) {
-        (void)hipEventDestroy(r.t0);
+        if (r.owns_t0) (void)hipEventDestroy(r.t0);
         (void)hipEventDestroy(r.t1);
     }
     for (auto e : m->event_pool) (void)hipEventDestroy(e);
@@ -1029,7 +1044,9 @@ int mt_profile_read(mt_model* m, float* h_ms, int32_t* h_launches)
             h_ms[r.klass] += ms;
             h_launches[r.klass] += 1;
         }
-        m->event_pool.push_back(r.t0);
+    }
+    for (auto& r : m->prof) {
+        if (r.owns_t0) m->event_pool.push_back(r.t0);
         m->event_pool.push_back(r.t1);
     }
     m->prof.clear();
