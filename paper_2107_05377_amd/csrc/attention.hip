@@ -59,7 +59,70 @@ __global__ __launch_bounds__(256, MT_ATTN_MINW) void attention_bf16_kernel(AttnG
     const int32_t* __restrict__ mrow = mask ? mask + (size_t)b * S : nullptr;
     const int nblk = Sk / 32;
 
-    // ---- stage key validity
+    // ---- this wavefront's 32 queries: their fragments are fetched first, so that the round trip overlaps the staging
+    const int q0 = blockIdx.x * 128 + wave * 32;
+    const int q = q0 + l32;
+    const int qc = q < n_tok ? q : n_tok - 1;
+    bf16x8 qf[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        qf[kk] = *reinterpret_cast<const bf16x8*>(qkv + (size_t)qc * ld + a * 64 + kk * 16 + half * 8);
+
+    // ---- stage K (rows = keys, 8 chunks of 8 elements) and V transposed (item = a pair of adjacent keys x one
+    //      8-wide chunk of d).  All of a thread's global loads of a batch are issued before the first LDS write,
+    //      so a workgroup pays one memory round trip per batch instead of one per item.
+    constexpr int KU = 4, VU = 2;                 // per thread and batch of 128 keys: 4 key chunks, 2 value items
+    for (int kb = 0; kb < Sk; kb += 128) {
+        uint4 kv[KU], v0[VU], v1[VU];
+        int m0[VU], m1[VU];
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+            const int c = kb * 8 + u * 256 + tid;
+            const int key = c >> 3, ch = c & 7;
+            kv[u] = make_uint4(0, 0, 0, 0);
+            if (key < n_tok) kv[u] = *reinterpret_cast<const uint4*>(qkv + (size_t)key * ld + H + a * 64 + ch * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < VU; ++u) {
+            const int c = kb * 4 + u * 256 + tid;
+            const int pair = c >> 3, ch = c & 7;
+            const int k0 = pair * 2, k1 = k0 + 1;
+            v0[u] = make_uint4(0, 0, 0, 0);
+            v1[u] = make_uint4(0, 0, 0, 0);
+            m0[u] = 1;
+            m1[u] = 1;
+            if (k0 < n_tok) {
+                v0[u] = *reinterpret_cast<const uint4*>(qkv + (size_t)k0 * ld + 2 * H + a * 64 + ch * 8);
+                if (mrow) m0[u] = mrow[k0];
+            }
+            if (k1 < n_tok) {
+                v1[u] = *reinterpret_cast<const uint4*>(qkv + (size_t)k1 * ld + 2 * H + a * 64 + ch * 8);
+                if (mrow) m1[u] = mrow[k1];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+            const int c = kb * 8 + u * 256 + tid;
+            if ((c >> 3) < Sk) *reinterpret_cast<uint4*>(Ks + k_chunk_off(c >> 3, c & 7)) = kv[u];
+        }
+#pragma unroll
+        for (int u = 0; u < VU; ++u) {
+            const int c = kb * 4 + u * 256 + tid;
+            const int pair = c >> 3, ch = c & 7;
+            const int k0 = pair * 2;
+            if (k0 >= Sk) continue;
+            if (m0[u] == 0) v0[u] = make_uint4(0, 0, 0, 0);       // a masked key's value row must not leak
+            if (m1[u] == 0) v1[u] = make_uint4(0, 0, 0, 0);
+            const uint32_t w0[4] = {v0[u].x, v0[u].y, v0[u].z, v0[u].w}, w1[4] = {v1[u].x, v1[u].y, v1[u].z, v1[u].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t lo = (w0[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+                const uint32_t hi = (w1[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+                *reinterpret_cast<uint32_t*>(Vt + (size_t)(ch * 8 + e) * vt_stride + k0) = lo | (hi << 16);
+            }
+        }
+    }
+    // ---- key validity and which 32-key blocks hold a real key
     for (int k = tid; k < Sk; k += 256) kvalid[k] = (k < n_tok && (!mrow || mrow[k] != 0)) ? 1.0f : 0.0f;
     __syncthreads();
     if (tid < nblk) {
@@ -67,42 +130,11 @@ __global__ __launch_bounds__(256, MT_ATTN_MINW) void attention_bf16_kernel(AttnG
         for (int k = 0; k < 32; ++k) any |= (kvalid[tid * 32 + k] != 0.0f);
         blk_any[tid] = (tid == 0) ? 1 : any;
     }
-    // ---- stage K (rows = keys, 8 chunks of 8 elements)
-    for (int c = tid; c < Sk * 8; c += 256) {
-        const int key = c >> 3, ch = c & 7;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (key < n_tok) v = *reinterpret_cast<const uint4*>(qkv + (size_t)key * ld + H + a * 64 + ch * 8);
-        *reinterpret_cast<uint4*>(Ks + k_chunk_off(key, ch)) = v;
-    }
-    // ---- stage V transposed: each item is a pair of adjacent keys x one 8-wide chunk of d
-    for (int c = tid; c < (Sk / 2) * 8; c += 256) {
-        const int pair = c >> 3, ch = c & 7;
-        const int k0 = pair * 2, k1 = k0 + 1;
-        uint4 v0 = make_uint4(0, 0, 0, 0), v1 = make_uint4(0, 0, 0, 0);
-        if (kvalid[k0] != 0.0f) v0 = *reinterpret_cast<const uint4*>(qkv + (size_t)k0 * ld + 2 * H + a * 64 + ch * 8);
-        if (kvalid[k1] != 0.0f) v1 = *reinterpret_cast<const uint4*>(qkv + (size_t)k1 * ld + 2 * H + a * 64 + ch * 8);
-        const uint32_t w0[4] = {v0.x, v0.y, v0.z, v0.w}, w1[4] = {v1.x, v1.y, v1.z, v1.w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint32_t lo = (w0[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-            const uint32_t hi = (w1[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-            *reinterpret_cast<uint32_t*>(Vt + (size_t)(ch * 8 + e) * vt_stride + k0) = lo | (hi << 16);
-        }
-    }
     __syncthreads();
 
-    // ---- this wavefront's 32 queries
-    const int q0 = blockIdx.x * 128 + wave * 32;
     if (q0 >= n_tok) return;
-    const int q = q0 + l32;
     const bool q_real = (q < n_tok) && (!mrow || mrow[q < n_tok ? q : 0] != 0);
     if (__ballot(q_real) == 0ull) return;
-    const int qc = q < n_tok ? q : n_tok - 1;
-
-    bf16x8 qf[4];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-        qf[kk] = *reinterpret_cast<const bf16x8*>(qkv + (size_t)qc * ld + a * 64 + kk * 16 + half * 8);
 
     f32x16 o[2];
 #pragma unroll
@@ -153,13 +185,13 @@ __global__ __launch_bounds__(256, MT_ATTN_MINW) void attention_bf16_kernel(AttnG
         }
         mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
         const float m_new = fmaxf(m_run, mloc);
-        const float alpha = exp2f(m_run - m_new);     // 0 on the first chunk (m_run = -inf)
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);     // 0 on the first chunk (m_run = -inf)
         float lsum = 0.f;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = exp2f(sc[j][e] - m_new);
+                const float p = __builtin_amdgcn_exp2f(sc[j][e] - m_new);    // bare v_exp_f32: tiny weights flush to 0
                 sc[j][e] = p;
                 lsum += p;
             }
