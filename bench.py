@@ -35,15 +35,24 @@ def gemm_flops_per_forward(spec, rows, batch):
     """EXECUTED FLOPs of the linear layers, per profile class, for one forward over `rows` token rows.
 
     The library drops padded positions before the first layer, so `rows` is the number of real
-    tokens of the batch (sum of sequence lengths), not batch*seq; a first-token-only layer projects
-    keys and values for every row and everything else for one row per sequence."""
-    H, F = spec.hidden, spec.ffn
+    tokens of the batch (sum of sequence lengths), not batch*seq.  A first-token-only layer (bf16 path)
+    projects no keys or values: per sequence it computes the query, Wk^T q per head, the raw scores
+    x_j . (Wk^T q) over the sequence's rows, Wv applied to the per-head weighted row sums, and the output
+    projection and feed-forward layers on one row."""
+    H, F, A = spec.hidden, spec.ffn, spec.heads
     n_full, n_first = layer_kinds(spec)
-    return {"gemm_qkv": n_full * 2.0 * rows * 3 * H * H + n_first * 2.0 * rows * 2 * H * H,
+    kvfree = spec.precision == "bf16" and A <= 16
+    first = 2.0 * batch * (2 * H * H + 2 * H * F)                      # query, output projection, FFN1, FFN2
+    qkv_last = 0.0
+    if kvfree:
+        first += 2.0 * batch * 2 * H * H + 2.0 * rows * H * A          # Wk^T q and Wv xbar (H^2 each), raw scores
+    else:
+        qkv_last = 2.0 * rows * 2 * H * H                              # K|V projection over all rows
+    return {"gemm_qkv": n_full * 2.0 * rows * 3 * H * H + n_first * qkv_last,
             "gemm_out": n_full * 2.0 * rows * H * H,
             "gemm_ffn1": n_full * 2.0 * rows * F * H,
             "gemm_ffn2": n_full * 2.0 * rows * H * F,
-            "gemm_first": n_first * 2.0 * batch * (2 * H * H + 2 * H * F)}
+            "gemm_first": n_first * first}
 
 
 def stored_traffic(workload_name):
@@ -237,7 +246,8 @@ def main():
     h = spec.hidden
     per_layer = 8.0 * S * h * h + 4.0 * S * h * spec.ffn + 4.0 * S * S * h
     flops_per_seq_dense = n_layers * per_layer + spec.n_tasks * 2.0 * h * h          # dense, padded convention
-    executed_per_step = (sum(flops.values()) + n_full * 4.0 * h * sumsq + n_first * 4.0 * h * rows
+    first_attn = 2.0 * h * rows * spec.heads if (bf16 and spec.heads <= 16) else 4.0 * h * rows   # weighted row sums per head
+    executed_per_step = (sum(flops.values()) + n_full * 4.0 * h * sumsq + n_first * first_attn
                          + spec.n_tasks * 2.0 * B * 2 * h * h)
     e2e_tflops = executed_per_step / (ms_per_step * 1e-3) / 1e12
     e2e_tflops_dense = flops_per_seq_dense * seq_per_s / 1e12

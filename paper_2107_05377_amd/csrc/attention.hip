@@ -20,6 +20,8 @@
 // hidden states at padded positions are unspecified by contract.
 //
 // float32 path: plain per-query loops for the validation mode, any head width.
+#include <type_traits>
+
 #include "kernels.h"
 #include "device_util.h"
 
@@ -342,7 +344,120 @@ __global__ __launch_bounds__(64) void attention_cls_kernel(AttnClsGroup g, const
     }
 }
 
+// Softmax over a sequence's rows of precomputed first-token scores and the probability-weighted sum of the
+// layer input rows, per head (see PoolGroup).  One workgroup per (problem, sequence, 256-column slab); every
+// workgroup repeats the (tiny) softmax, then each thread owns one column of the slab for all heads.
+constexpr int kPoolMaxHeads = 16;
+template <int NA4>      // A_pad / 4: compile-time head count keeps the accumulators and the probability reads branch-free
+__global__ __launch_bounds__(256) void first_token_pool_kernel(PoolGroup g, const int32_t* __restrict__ seq_start,
+                                                               const int32_t* __restrict__ seq_len, int B, int Smax, int H, int A,
+                                                               int A_pad, float scale)
+{
+    extern __shared__ float pl[];                       // [Smax][A_pad] scores, then probabilities
+    const int grp = blockIdx.y, b = blockIdx.x;
+    const int row0 = seq_start[b];
+    const int n = min(seq_len[b], Smax);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* __restrict__ sc = g.scores[grp] + (size_t)row0 * A_pad;
+    for (int i0 = 0; i0 < n * A_pad; i0 += 256 * 8) {      // all of a thread's loads of a batch are in flight together
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * 256 + tid;
+            v[u] = i < n * A_pad ? sc[i] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * 256 + tid;
+            if (i < n * A_pad) pl[i] = v[u] * scale;
+        }
+    }
+    __syncthreads();
+    for (int a = wave; a < A; a += 4) {                 // one head per wavefront at a time, lanes over keys
+        float mx = -INFINITY;
+        for (int j = lane; j < n; j += 64) mx = fmaxf(mx, pl[j * A_pad + a]);
+        mx = wave_max(mx);
+        float sum = 0.f;
+        for (int j = lane; j < n; j += 64) {
+            const float e = expf(pl[j * A_pad + a] - mx);
+            pl[j * A_pad + a] = e;
+            sum += e;
+        }
+        sum = wave_sum(sum);
+        const float inv = 1.0f / sum;
+        for (int j = lane; j < n; j += 64) pl[j * A_pad + a] *= inv;
+    }
+    __syncthreads();
+    // every thread owns TWO adjacent columns (4-byte loads: sub-dword loads issue no faster than dword ones)
+    const int c = (blockIdx.z * 256 + tid) * 2;
+    if (c >= H || n <= 0) return;
+    float acc[NA4 * 4][2];
+#pragma unroll
+    for (int a = 0; a < NA4 * 4; ++a) acc[a][0] = acc[a][1] = 0.f;
+    const __bf16* __restrict__ x = static_cast<const __bf16*>(g.x[grp]) + (size_t)row0 * H + c;
+    // rows in batches of JU: the batch's row loads and probability reads are all issued before the first FMA
+    constexpr int JU = 8;
+    auto rows = [&](int j0, auto full) {
+        bf16x2 xv[JU];
+        float4 p4[JU][NA4];
+#pragma unroll
+        for (int u = 0; u < JU; ++u)
+            if (full || j0 + u < n) xv[u] = *reinterpret_cast<const bf16x2*>(x + (size_t)(j0 + u) * H);
+#pragma unroll
+        for (int u = 0; u < JU; ++u)
+            if (full || j0 + u < n) {
+#pragma unroll
+                for (int a4 = 0; a4 < NA4; ++a4) p4[u][a4] = *reinterpret_cast<const float4*>(pl + (j0 + u) * A_pad + a4 * 4);   // broadcast
+            }
+#pragma unroll
+        for (int u = 0; u < JU; ++u)
+            if (full || j0 + u < n) {
+                const float x0 = (float)xv[u][0], x1 = (float)xv[u][1];
+#pragma unroll
+                for (int a4 = 0; a4 < NA4; ++a4) {
+                    acc[a4 * 4 + 0][0] = fmaf(p4[u][a4].x, x0, acc[a4 * 4 + 0][0]);
+                    acc[a4 * 4 + 0][1] = fmaf(p4[u][a4].x, x1, acc[a4 * 4 + 0][1]);
+                    acc[a4 * 4 + 1][0] = fmaf(p4[u][a4].y, x0, acc[a4 * 4 + 1][0]);
+                    acc[a4 * 4 + 1][1] = fmaf(p4[u][a4].y, x1, acc[a4 * 4 + 1][1]);
+                    acc[a4 * 4 + 2][0] = fmaf(p4[u][a4].z, x0, acc[a4 * 4 + 2][0]);
+                    acc[a4 * 4 + 2][1] = fmaf(p4[u][a4].z, x1, acc[a4 * 4 + 2][1]);
+                    acc[a4 * 4 + 3][0] = fmaf(p4[u][a4].w, x0, acc[a4 * 4 + 3][0]);
+                    acc[a4 * 4 + 3][1] = fmaf(p4[u][a4].w, x1, acc[a4 * 4 + 3][1]);
+                }
+            }
+    };
+    int j0 = 0;
+    for (; j0 + JU <= n; j0 += JU) rows(j0, std::true_type{});
+    if (j0 < n) rows(j0, std::false_type{});
+    __bf16* out = static_cast<__bf16*>(g.xbar[grp]) + (size_t)b * A_pad * H + c;
+#pragma unroll
+    for (int a = 0; a < NA4 * 4; ++a)
+        if (a < A) {
+            const bf16x2 o = {(__bf16)acc[a][0], (__bf16)acc[a][1]};
+            *reinterpret_cast<bf16x2*>(out + (size_t)a * H) = o;
+        }
+}
+
 }  // namespace
+
+hipError_t launch_first_token_pool(const PoolGroup& g, int G, const int32_t* seq_start, const int32_t* seq_len, int B, int S, int H,
+                                   int A, int A_pad, hipStream_t stream)
+{
+    if (G <= 0 || B <= 0 || S <= 0) return hipSuccess;
+    if (!seq_start || !seq_len || G > kMaxGroup || A < 1 || A > kPoolMaxHeads || A_pad < A || A_pad > kPoolMaxHeads || A_pad % 4 != 0 || H % 2 != 0 ||
+        (size_t)S * A_pad * 4 > 64 * 1024)
+        return hipErrorInvalidValue;
+    dim3 grid(B, G, (H + 511) / 512), block(256);
+    const size_t lds = (size_t)S * A_pad * sizeof(float);
+    const float scale = 1.0f / sqrtf((float)(H / A));
+    switch (A_pad / 4) {
+        case 1: hipLaunchKernelGGL(first_token_pool_kernel<1>, grid, block, lds, stream, g, seq_start, seq_len, B, S, H, A, A_pad, scale); break;
+        case 2: hipLaunchKernelGGL(first_token_pool_kernel<2>, grid, block, lds, stream, g, seq_start, seq_len, B, S, H, A, A_pad, scale); break;
+        case 3: hipLaunchKernelGGL(first_token_pool_kernel<3>, grid, block, lds, stream, g, seq_start, seq_len, B, S, H, A, A_pad, scale); break;
+        default: hipLaunchKernelGGL(first_token_pool_kernel<4>, grid, block, lds, stream, g, seq_start, seq_len, B, S, H, A, A_pad, scale); break;
+    }
+    return hipGetLastError();
+}
 
 hipError_t launch_attention_cls(const AttnClsGroup& g, int G, int is_bf16, const int32_t* seq_start, const int32_t* seq_len,
                                 int B, int S, int H, int A, hipStream_t stream)

@@ -551,7 +551,9 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
     if ((uint64_t)s.M * (uint64_t)s.lda * 2 >= (1ull << 32) || (uint64_t)s.N * (uint64_t)(s.ldw ? s.ldw : s.K) * 2 >= (1ull << 32))
         return hipErrorInvalidValue;
     int sel = g_gemm_bf16_tile_override;
-    if ((sel == 0 && s.M <= 256) || sel == 13) return launch_gemm_skinny_bf16(g, s, stream);   // few rows: weight-streaming kernel
+    if ((sel == 0 && s.M <= 256) || sel == 13 || s.n_sub > 1 || s.d_sub_rows) {                                   // few rows: weight-streaming kernel
+        return launch_gemm_skinny_bf16(g, s, stream);
+    }
     if (sel == 0) {
         // Shape rule from measurements on MI355X (BERT-base widths, 1 and 8 problems, 2304 and 4096 rows).
         // The row bound s.M over-counts when padding is dropped on the device, so the rule keys on the

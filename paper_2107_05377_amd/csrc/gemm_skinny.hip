@@ -49,11 +49,18 @@ template <bool OUT_F32>
 __global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmGroup g, GemmShape s)
 {
     __shared__ __attribute__((aligned(16))) float part[4][SK_BM][SK_LDP];
-    const int M = s.d_M ? min(s.M, *s.d_M) : s.M;
+    const int nsub = s.n_sub > 1 ? s.n_sub : 1;
+    const int sub = blockIdx.z % nsub, gz = blockIdx.z / nsub;
+    const int grp = gz / s.splits, split = gz - grp * s.splits;
+    int M = s.d_M ? min(s.M, *s.d_M) : s.M;
+    size_t row_base = 0;                                   // ragged batch: this sub-problem's rows of A and C
+    if (s.d_sub_rows) {
+        M = min(s.M, s.d_sub_rows[sub]);
+        row_base = (size_t)s.d_sub_row0[sub];
+    }
     const int m0 = blockIdx.y * SK_BM;
     if (m0 >= M) return;
     const int n0 = blockIdx.x * SK_BN;
-    const int grp = blockIdx.z / s.splits, split = blockIdx.z - grp * s.splits;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
 
@@ -61,9 +68,9 @@ __global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmGroup g, Gemm
     const int k_len = s.K / s.splits / 4;
     const int k_begin = split * (s.K / s.splits) + wave * k_len;
     const __bf16* __restrict__ a_row =
-        static_cast<const __bf16*>(g.A[grp]) + (size_t)min(m0 + l32, M - 1) * s.lda + k_begin + half * 8;
+        static_cast<const __bf16*>(g.A[grp]) + (size_t)sub * s.sub_a + (row_base + min(m0 + l32, M - 1)) * s.lda + k_begin + half * 8;
     const __bf16* __restrict__ w_row =
-        static_cast<const __bf16*>(g.W[grp]) + (size_t)min(n0 + l32, s.N - 1) * (s.ldw ? s.ldw : s.K) + k_begin + half * 8;
+        static_cast<const __bf16*>(g.W[grp]) + (size_t)sub * s.sub_w + (size_t)min(n0 + l32, s.N - 1) * (s.ldw ? s.ldw : s.K) + k_begin + half * 8;
 
     f32x16 acc;
 #pragma unroll
@@ -102,7 +109,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmGroup g, Gemm
         v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
     }
     if (g.bias[grp]) {
-        const float4 b = *reinterpret_cast<const float4*>(g.bias[grp] + n);
+        const float4 b = *reinterpret_cast<const float4*>(g.bias[grp] + (size_t)sub * s.sub_bias + n);
         v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
     }
     v.x = skinny_act(v.x, s.act);
@@ -114,11 +121,11 @@ __global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmGroup g, Gemm
             const float4 t = *reinterpret_cast<const float4*>(g.residual[grp] + (size_t)m * s.ldr + n);
             v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
         }
-        float* C = static_cast<float*>(g.C[grp]) + (size_t)split * s.split_stride;
-        *reinterpret_cast<float4*>(C + (size_t)m * s.ldc + n) = v;
+        float* C = static_cast<float*>(g.C[grp]) + (size_t)split * s.split_stride + (size_t)sub * s.sub_c;
+        *reinterpret_cast<float4*>(C + (row_base + m) * s.ldc + n) = v;
     } else {
         bf16x4 o = {(__bf16)v.x, (__bf16)v.y, (__bf16)v.z, (__bf16)v.w};
-        *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(g.C[grp]) + (size_t)m * s.ldc + n) = o;
+        *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(g.C[grp]) + (size_t)sub * s.sub_c + (row_base + m) * s.ldc + n) = o;
     }
 }
 
@@ -131,9 +138,16 @@ hipError_t launch_gemm_skinny_bf16(const GemmGroup& g, const GemmShape& s, hipSt
     if (s.G <= 0 || s.M <= 0 || s.N <= 0) return hipSuccess;
     if (s.splits < 1 || (s.splits > 1 && (!s.out_f32 || s.act != ACT_NONE || g.bias[0] || g.residual[0]))) return hipErrorInvalidValue;
     if (s.K % (64 * s.splits) != 0 || s.N % 4 != 0 || s.lda % 8 != 0 || s.ldw % 8 != 0 || (s.ldw && s.ldw < s.K) || s.ldc % 4 != 0 || s.ldr % 4 != 0 || s.G > kMaxGroup ||
-        (!s.out_f32 && g.residual[0] != nullptr) || (long)s.G * s.splits > 65535)
+        (!s.out_f32 && g.residual[0] != nullptr))
         return hipErrorInvalidValue;
-    dim3 grid((s.N + SK_BN - 1) / SK_BN, (s.M + SK_BM - 1) / SK_BM, s.G * s.splits), block(256);
+    const int nsub = s.n_sub > 1 ? s.n_sub : 1;
+    if ((long)s.G * s.splits * nsub > 65535) return hipErrorInvalidValue;
+    if (nsub > 1 && (g.residual[0] != nullptr || s.d_M != nullptr || s.sub_a % 8 != 0 || s.sub_w % 8 != 0 || s.sub_c % 4 != 0 ||
+                     s.sub_bias % 4 != 0))
+        return hipErrorInvalidValue;
+    if ((s.d_sub_rows != nullptr) != (s.d_sub_row0 != nullptr) || (s.d_sub_rows && (s.d_M != nullptr || g.residual[0] != nullptr)))
+        return hipErrorInvalidValue;
+    dim3 grid((s.N + SK_BN - 1) / SK_BN, (s.M + SK_BM - 1) / SK_BM, s.G * s.splits * nsub), block(256);
     if (s.out_f32) hipLaunchKernelGGL((gemm_skinny_bf16_kernel<true>), grid, block, 0, stream, g, s);
     else hipLaunchKernelGGL((gemm_skinny_bf16_kernel<false>), grid, block, 0, stream, g, s);
     return hipGetLastError();

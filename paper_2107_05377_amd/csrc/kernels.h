@@ -35,6 +35,15 @@ struct GemmShape {
                             // partial product (float32, no epilogue) to C_g + p * split_stride elements
     int64_t split_stride;
     int64_t ldw;            // row stride of W in elements; 0 = dense (K)
+    // Few-row kernel only (launch_gemm_bf16 routes there when n_sub > 1): every problem g consists of n_sub
+    // sub-problems of the same shape, sub-problem u using A_g + u*sub_a, W_g + u*sub_w, C_g + u*sub_c and
+    // bias_g + u*sub_bias (element offsets); no residual.  With d_sub_row0 / d_sub_rows (device arrays [n_sub])
+    // sub-problem u additionally starts at row d_sub_row0[u] of A and C and has d_sub_rows[u] (<= M) rows:
+    // a ragged batch, e.g. one sub-problem per sequence of the padding-free row order.
+    int32_t n_sub;
+    int64_t sub_a, sub_w, sub_c, sub_bias;
+    const int32_t* d_sub_row0;
+    const int32_t* d_sub_rows;
 };
 
 // bf16 x bf16 -> fp32 accumulate on the matrix cores.  Needs K % 64 == 0, lda % 8 == 0, 16-byte aligned A/W rows.
@@ -127,6 +136,19 @@ struct AttnClsGroup {
 };
 hipError_t launch_attention_cls(const AttnClsGroup& g, int G, int is_bf16, const int32_t* seq_start, const int32_t* seq_len,
                                 int B, int S, int H, int A, hipStream_t stream);
+
+// First-token attention WITHOUT projected keys and values (bf16 path).  With q~[b][a] = Wk_a^T q[b][a] the
+// score of key j is q~[b][a] . x_j (+ a constant per row, which the softmax drops), and the head's context is
+// Wv_a (sum_j p_j x_j) + bv_a.  This kernel takes the raw scores[g] = [rows][A_pad] (float32, x_j . q~),
+// scales them, takes the softmax over each sequence's rows and writes the probability-weighted sum of the
+// layer input rows x[g] = [rows][H] (bf16) per head: xbar[g] = [B][A_pad][H] (bf16).
+struct PoolGroup {
+    const float* scores[kMaxGroup];
+    const void* x[kMaxGroup];
+    void* xbar[kMaxGroup];
+};
+hipError_t launch_first_token_pool(const PoolGroup& g, int G, const int32_t* seq_start, const int32_t* seq_len, int B, int S, int H,
+                                   int A, int A_pad, hipStream_t stream);
 
 // logits[g][b][c] = Wc_g[c][:] . pooled_g[b][:] + bc_g[c]; one wavefront per (g, b, c).  Wc bf16 or fp32.
 struct ClsGroup {

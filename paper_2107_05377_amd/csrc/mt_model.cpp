@@ -47,6 +47,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct LayerW {   // byte offsets into the weight arena
     size_t Wqkv, bqkv, Wo, bo, ln1g, ln1b, W1, b1, W2, b2, ln2g, ln2b;
+    size_t WkT = 0;   // bf16 mode, a task's last layer only: Wk transposed, [H][H] (first-token attention), else 0
 };
 struct TaskW {
     std::vector<LayerW> layers;
@@ -59,6 +60,7 @@ struct Scratch {   // byte offsets into the workspace; one set for the trunk and
 };
 struct ClsScratch {   // per task with own layers: compact [max_batch] x ... buffers of its last, first-token-only layer
     size_t in_f, in_a, q, ctx, y, x1f, x1a, u, out_f;
+    size_t qt = 0, scores = 0, xbar = 0;   // bf16 mode: Wk^T q [max_batch][A_pad][H], raw scores [M][A_pad], weighted row sums
 };
 struct ProfRec {
     int klass;
@@ -204,6 +206,14 @@ size_t stage_layer(const mt_model* m, const LayerW& L, const float* p, unsigned 
     const size_t H = m->cfg.hidden, F = m->cfg.ffn;
     const float* p0 = p;
     auto at = [&](size_t off) { return img + (off - img_base); };
+    if (L.WkT) {                    // Wk^T for the first-token attention of a task's last layer (bf16 mode)
+        const float* wk = p + (H * H + H);
+        std::vector<float> col(H);
+        for (size_t n = 0; n < H; ++n) {
+            for (size_t r = 0; r < H; ++r) col[r] = wk[r * H + n];
+            put_matrix(at(L.WkT) + n * H * 2, col.data(), H, true);
+        }
+    }
     for (int i = 0; i < 3; ++i) {   // Wq bq Wk bk Wv bv -> one [3H,H] matrix and one [3H] bias
         put_matrix(at(L.Wqkv) + (size_t)i * H * H * m->esz, p, H * H, m->bf16);
         p += H * H;
@@ -429,18 +439,23 @@ void run_last_layer_group(Launcher& L, const std::vector<LastIO>& io, const RowM
     GemmGroup g;
     memset(&g, 0, sizeof g);
     GemmShape s;
+    // keys and values are not projected at all when the first-token attention kernels cover the shape
+    const bool kvfree = bf && A <= 16 && (size_t)S * ((A + 3) / 4 * 4) * 4 <= 64 * 1024;
 
-    // K | V projection for every row: rows H..3H-1 of Wqkv, written to columns H..3H-1 of the qkv buffer
-    for (int i = 0; i < n; ++i) {
-        g.A[i] = io[i].in_a;
-        g.W[i] = W + io[i].w->Wqkv + (size_t)H * H * esz;
-        g.bias[i] = (const float*)(W + io[i].w->bqkv) + H;
-        g.residual[i] = nullptr;
-        g.C[i] = ws + io[i].scr->qkv + (size_t)H * esz;
-        g.N[i] = 2 * H;
+    if (!kvfree) {
+        // K | V projection for every row: rows H..3H-1 of Wqkv, written to columns H..3H-1 of the qkv buffer
+        for (int i = 0; i < n; ++i) {
+            g.A[i] = io[i].in_a;
+            g.W[i] = W + io[i].w->Wqkv + (size_t)H * H * esz;
+            g.bias[i] = (const float*)(W + io[i].w->bqkv) + H;
+            g.residual[i] = nullptr;
+            g.C[i] = ws + io[i].scr->qkv + (size_t)H * esz;
+            g.N[i] = 2 * H;
+        }
+        s = GemmShape{n, M, 2 * H, H, H, 3 * H, 0, ACT_NONE, bf ? 0 : 1, rm.n_rows, 1, 0};
+        L.gemm(MT_K_GEMM_QKV, g, s, false);
+
     }
-    s = GemmShape{n, M, 2 * H, H, H, 3 * H, 0, ACT_NONE, bf ? 0 : 1, rm.n_rows, 1, 0};
-    L.gemm(MT_K_GEMM_QKV, g, s, false);
 
     // first-token rows of the input (residual and operand copies), then their queries
     FirstRowsGroup fg;
@@ -464,16 +479,80 @@ void run_last_layer_group(Launcher& L, const std::vector<LastIO>& io, const RowM
     s = GemmShape{n, B, H, H, H, H, 0, ACT_NONE, bf ? 0 : 1, nullptr, 1, 0};
     L.gemm(MT_K_GEMM_FIRST, g, s, false);
 
-    AttnClsGroup ag;
-    memset(&ag, 0, sizeof ag);
-    for (int i = 0; i < n; ++i) {
-        ag.q[i] = ws + io[i].cls->q;
-        ag.kv[i] = ws + io[i].scr->qkv;
-        ag.ctx[i] = ws + io[i].cls->ctx;
+    if (!kvfree) {
+        AttnClsGroup ag;
+        memset(&ag, 0, sizeof ag);
+        for (int i = 0; i < n; ++i) {
+            ag.q[i] = ws + io[i].cls->q;
+            ag.kv[i] = ws + io[i].scr->qkv;
+            ag.ctx[i] = ws + io[i].cls->ctx;
+        }
+        L.begin(MT_K_ATTN);
+        L.check(launch_attention_cls(ag, n, bf ? 1 : 0, rm.seq_start, rm.seq_len, B, S, H, A, L.st));
+        L.end();
+
+    } else {
+        // First-token attention without projecting keys and values.  With q~[b][a] = Wk_a^T q[b][a], the score of
+        // key j is q~[b][a] . x_j plus a per-row constant (q . bk) that the softmax drops, and the head's context is
+        // Wv_a (sum_j p_j x_j) + bv_a.  Four small launches replace the K|V projection over all rows:
+        //   q~  : per head, [B x d] . WkT_a            (few-row kernel, one sub-problem per head)
+        //   s   : per sequence, x rows . q~[b]^T        (few-row kernel, ragged batch over sequences)
+        //   xbar: softmax over the sequence, weighted sum of its x rows per head
+        //   ctx : per head, xbar[b][a] . Wv_a^T + bv_a  (few-row kernel, one sub-problem per head)
+        const int d = H / A, A_pad = (A + 3) / 4 * 4;
+        for (int i = 0; i < n; ++i) {
+            g.A[i] = ws + io[i].cls->q;
+            g.W[i] = W + io[i].w->WkT;
+            g.bias[i] = nullptr;
+            g.C[i] = ws + io[i].cls->qt;
+            g.N[i] = H;
+        }
+        s = GemmShape{n, B, H, d, H, (int64_t)A_pad * H, 0, ACT_NONE, 0, nullptr, 1, 0, H};
+        s.n_sub = A;
+        s.sub_a = d;
+        s.sub_w = d;
+        s.sub_c = H;
+        L.gemm(MT_K_GEMM_FIRST, g, s, false);
+
+        for (int i = 0; i < n; ++i) {
+            g.A[i] = io[i].in_a;
+            g.W[i] = ws + io[i].cls->qt;
+            g.C[i] = ws + io[i].cls->scores;
+            g.N[i] = A_pad;
+        }
+        s = GemmShape{n, S, A_pad, H, H, A_pad, 0, ACT_NONE, 1, nullptr, 1, 0, 0};
+        s.n_sub = B;
+        s.sub_w = (int64_t)A_pad * H;
+        s.d_sub_row0 = rm.seq_start;
+        s.d_sub_rows = rm.seq_len;
+        L.gemm(MT_K_GEMM_FIRST, g, s, false);
+
+        PoolGroup pg;
+        memset(&pg, 0, sizeof pg);
+        for (int i = 0; i < n; ++i) {
+            pg.scores[i] = (const float*)(ws + io[i].cls->scores);
+            pg.x[i] = io[i].in_a;
+            pg.xbar[i] = ws + io[i].cls->xbar;
+        }
+        L.begin(MT_K_ATTN);
+        L.check(launch_first_token_pool(pg, n, rm.seq_start, rm.seq_len, B, S, H, A, A_pad, L.st));
+        L.end();
+
+        for (int i = 0; i < n; ++i) {
+            g.A[i] = ws + io[i].cls->xbar;
+            g.W[i] = W + io[i].w->Wqkv + (size_t)2 * H * H * esz;
+            g.bias[i] = (const float*)(W + io[i].w->bqkv) + 2 * H;
+            g.C[i] = ws + io[i].cls->ctx;
+            g.N[i] = d;
+        }
+        s = GemmShape{n, B, d, H, (int64_t)A_pad * H, H, 0, ACT_NONE, 0, nullptr, 1, 0, 0};
+        s.n_sub = A;
+        s.sub_a = H;
+        s.sub_w = (int64_t)d * H;
+        s.sub_c = d;
+        s.sub_bias = d;
+        L.gemm(MT_K_GEMM_FIRST, g, s, false);
     }
-    L.begin(MT_K_ATTN);
-    L.check(launch_attention_cls(ag, n, bf ? 1 : 0, rm.seq_start, rm.seq_len, B, S, H, A, L.st));
-    L.end();
 
     // projection (split along K: only B rows, so the weight stream is what has to be spread), LayerNorm
     auto splits_for = [&](int K, int want) {
@@ -613,6 +692,7 @@ int mt_create(const mt_config* cfg, mt_model** out)
         TaskW& tw = m->taskw[t];
         tw.begin = wb.off;
         for (int l = 0; l < m->tasks[t].n_layers; ++l) tw.layers.push_back(layout_layer(wb, H, F, m->esz));
+        if (m->bf16 && !tw.layers.empty()) tw.layers.back().WkT = wb.take(H * H * 2);
         tw.Wp = wb.take(H * H * m->esz * (m->bf16 ? 2 : 1));
         tw.bp = wb.take(H * 4);
         tw.Wc = wb.take((size_t)m->tasks[t].n_classes * H * m->esz);
@@ -654,6 +734,12 @@ int mt_create(const mt_config* cfg, mt_model** out)
             c.x1a = m->bf16 ? sb.take(MB * H * 2) : c.x1f;
             c.u = sb.take(MB * F * m->esz);
             c.out_f = sb.take(MB * H * 4);
+            if (m->bf16) {
+                const size_t A_pad = ((size_t)cfg->heads + 3) / 4 * 4;
+                c.qt = sb.take(MB * A_pad * H * 2);
+                c.scores = sb.take(M * A_pad * 4);
+                c.xbar = sb.take(MB * A_pad * H * 2);
+            }
             m->task_cls.push_back(c);
         } else {
             m->task_scr.push_back(Scratch{});

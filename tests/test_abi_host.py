@@ -49,8 +49,9 @@ def test_create_and_sizes():
     assert [L.mt_logit_offset(h, t) for t in range(8)] == [0, 2, 4, 6, 9, 11, 13, 15]
     assert L.mt_logit_offset(h, 8) == mt.MT_ERR_SHAPE
     wb = L.mt_weight_bytes(h)
-    # embeddings, 24 layers of 12 H^2, 8 poolers stored as [W | W] (2 H^2 each), 16 classifier rows
-    n_mat = (30522 + 512 + 2) * 768 + 24 * 12 * 768 * 768 + 8 * 2 * (768 * 768) + 16 * 768
+    # embeddings, 24 layers of 12 H^2, per task the pooler stored as [W | W] (2 H^2) and the transposed key
+    # matrix of its last layer (H^2), 16 classifier rows
+    n_mat = (30522 + 512 + 2) * 768 + 24 * 12 * 768 * 768 + 8 * 3 * (768 * 768) + 16 * 768
     assert 2 * n_mat <= wb <= 2 * n_mat * 1.02           # bf16 matrices dominate the arena
     assert L.mt_workspace_bytes(h) > 8 * 4096 * 3072 * 2
     L.mt_destroy(h)
