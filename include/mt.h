@@ -200,6 +200,19 @@ int mt_op_linear_batched(int32_t precision, int32_t G, const void* d_A, int64_t 
                          int64_t strideW, const float* d_bias, int64_t strideBias, const float* d_residual,
                          int64_t strideRes, void* d_C, int64_t strideC, int64_t ldc, int32_t M, int32_t N, int32_t K,
                          int32_t act_kind, int32_t out_f32, void* hip_stream);
+
+/* The few-row bf16 contraction with sub-problems, as the first-token attention of a branch's last layer uses
+ * it (Section 3.3: only the first token feeds the task head): n_sub equal-shaped problems
+ *   C_u[M,N] = A_u[M,K] W_u[N,K]^T + bias_u,   A_u = d_A + u*sub_a, W_u = d_W + u*sub_w, C_u = d_C + u*sub_c,
+ *   bias_u = d_bias + u*sub_bias (element offsets; lda/ldw/ldc row strides in elements, ldw 0 = K).
+ * With d_sub_row0 / d_sub_rows (device int32 [n_sub], both or neither) problem u instead starts at row
+ * d_sub_row0[u] of A and C and has min(M, d_sub_rows[u]) rows (a ragged batch; rows beyond are untouched).
+ * bf16 inputs; out_f32 != 0 stores float32, else bf16.  Needs K % 64 == 0, N % 4 == 0, 16-byte aligned rows.
+ * Errors: NULL, SHAPE. */
+int mt_op_linear_sub(const void* d_A, int64_t lda, const void* d_W, int64_t ldw, const float* d_bias, void* d_C, int64_t ldc,
+                     int32_t M, int32_t N, int32_t K, int32_t n_sub, int64_t sub_a, int64_t sub_w, int64_t sub_c,
+                     int64_t sub_bias, const int32_t* d_sub_row0, const int32_t* d_sub_rows, int32_t out_f32,
+                     void* hip_stream);
 /* ctx[b,s,a*d:(a+1)*d] = softmax(q k^T / sqrt(d) + mask) v per head; d_qkv is [B*S][3H] act
  * (columns Q | K | V), d_ctx [B*S][H] act. */
 int mt_op_attention(int32_t precision, const void* d_qkv, const int32_t* d_mask, void* d_ctx,

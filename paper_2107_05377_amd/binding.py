@@ -25,7 +25,7 @@ KERNEL_CLASSES = ["embed", "gemm_qkv", "attn", "gemm_out", "ln", "gemm_ffn1", "g
 EXPORTS = ["mt_create", "mt_destroy", "mt_weight_bytes", "mt_workspace_bytes", "mt_bind", "mt_load_weights",
            "mt_forward", "mt_logit_offset", "mt_n_logits", "mt_layer_count", "mt_last_error", "mt_error_name",
            "mt_read_hidden", "mt_profile_enable", "mt_profile_read", "mt_op_linear", "mt_op_attention",
-           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed"]
+           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed", "mt_op_linear_sub"]
 
 
 class mt_task_desc(C.Structure):
@@ -80,6 +80,7 @@ def lib():
         L.mt_op_attention.argtypes = [i32, vp, vp, vp, i32, i32, i32, i32, vp]
         L.mt_op_layernorm.argtypes = [vp, vp, vp, C.c_float, vp, vp, i32, i32, vp]
         L.mt_debug_set_gemm_tile.argtypes = [i32]
+        L.mt_op_linear_sub.argtypes = [vp, i64, vp, i64, vp, vp, i64, i32, i32, i32, i32, i64, i64, i64, i64, vp, vp, i32, vp]
         L.mt_debug_set_gemm_tile.restype = i32
         _lib = L
     return _lib
@@ -217,6 +218,17 @@ class Model:
         n = (C.c_int32 * len(KERNEL_CLASSES))()
         self._check(lib().mt_profile_read(self.h, ms, n))
         return {k: (float(ms[i]), int(n[i])) for i, k in enumerate(KERNEL_CLASSES)}
+
+
+def op_linear_sub(A, lda, W, ldw, bias, C, ldc, M, N, K, n_sub, sub_a, sub_w, sub_c, sub_bias=0, row0=None, rows=None,
+                  out_f32=False):
+    """mt_op_linear_sub on device tensors (raw strides and offsets in elements; C is written in place)."""
+    rc = lib().mt_op_linear_sub(_ptr(A), lda, _ptr(W), ldw, _ptr(bias) if bias is not None else None, _ptr(C), ldc, M, N, K,
+                                n_sub, sub_a, sub_w, sub_c, sub_bias, _ptr(row0) if row0 is not None else None,
+                                _ptr(rows) if rows is not None else None, 1 if out_f32 else 0, _stream())
+    if rc != MT_OK:
+        raise MTError(rc, "mt_op_linear_sub")
+    return C
 
 
 def mfma_peak(iters=4000):

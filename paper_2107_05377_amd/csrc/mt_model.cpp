@@ -1178,6 +1178,33 @@ int mt_op_linear(int32_t precision, const void* d_A, int64_t lda, const void* d_
     return e == hipSuccess ? MT_OK : MT_ERR_HIP;
 }
 
+int mt_op_linear_sub(const void* d_A, int64_t lda, const void* d_W, int64_t ldw, const float* d_bias, void* d_C, int64_t ldc,
+                     int32_t M, int32_t N, int32_t K, int32_t n_sub, int64_t sub_a, int64_t sub_w, int64_t sub_c,
+                     int64_t sub_bias, const int32_t* d_sub_row0, const int32_t* d_sub_rows, int32_t out_f32,
+                     void* hip_stream)
+{
+    if (!d_A || !d_W || !d_C) return MT_ERR_NULL;
+    if (M < 1 || N < 1 || K < 1 || n_sub < 1 || (d_sub_row0 == nullptr) != (d_sub_rows == nullptr)) return MT_ERR_SHAPE;
+    GemmGroup g;
+    memset(&g, 0, sizeof g);
+    g.A[0] = d_A;
+    g.W[0] = d_W;
+    g.C[0] = d_C;
+    g.bias[0] = d_bias;
+    g.N[0] = N;
+    GemmShape s{1, M, N, K, lda, ldc, 0, ACT_NONE, out_f32 ? 1 : 0, nullptr, 1, 0, ldw};
+    s.n_sub = n_sub;
+    s.sub_a = sub_a;
+    s.sub_w = sub_w;
+    s.sub_c = sub_c;
+    s.sub_bias = sub_bias;
+    s.d_sub_row0 = d_sub_row0;
+    s.d_sub_rows = d_sub_rows;
+    hipError_t e = launch_gemm_skinny_bf16(g, s, static_cast<hipStream_t>(hip_stream));
+    if (e == hipErrorInvalidValue) return MT_ERR_SHAPE;
+    return e == hipSuccess ? MT_OK : MT_ERR_HIP;
+}
+
 int mt_op_linear_batched(int32_t precision, int32_t G, const void* d_A, int64_t strideA, int64_t lda, const void* d_W,
                          int64_t strideW, const float* d_bias, int64_t strideBias, const float* d_residual,
                          int64_t strideRes, void* d_C, int64_t strideC, int64_t ldc, int32_t M, int32_t N, int32_t K,

@@ -120,6 +120,52 @@ def test_gemm_bf16_grouped_and_split_vs_oracle():
             assert np.abs(shared[g] - refs).max() <= 2 ** -8 * np.abs(refs).max() + 1e-3
 
 
+def test_gemm_sub_problems_and_ragged_batches_vs_oracle():
+    """The few-row kernel's sub-problem forms, as the first-token attention uses them: per-head problems carved out
+    of wider matrices by offsets and strides, and a ragged batch whose row ranges are read on the device."""
+    rng = np.random.default_rng(77)
+    B, A, d = 37, 3, 64                      # rows not a multiple of 32; 3 heads of width 64
+    H = A * d
+    # (1) per head: C[:, a, :] = Q[:, a*d:(a+1)*d] . WkT[:, a*d:(a+1)*d]^T   (K = d, strided operands, bf16 out)
+    Q = bf16_grid(rng.standard_normal((B, H)))
+    WkT = bf16_grid(rng.standard_normal((H, H)) * 0.1)
+    C1 = torch.full((B, A + 1, H), 7.0, dtype=torch.bfloat16, device="cuda")
+    mt.op_linear_sub(dev(Q, torch.bfloat16), H, dev(WkT, torch.bfloat16), H, None, C1, (A + 1) * H, B, H, d, A, d, d, H)
+    got = C1.float().cpu().numpy()
+    for a in range(A):
+        ref = oracle.linear(Q[:, a * d:(a + 1) * d].copy(), WkT[:, a * d:(a + 1) * d].copy(), None)
+        assert np.abs(got[:, a, :] - ref).max() <= 2 ** -8 * np.abs(ref).max() + 1e-3
+    assert (got[:, A, :] == 7.0).all()                                   # the pad slot is untouched
+    # (2) per head with bias, N = d: C[:, a*d:(a+1)*d] = X[:, a, :] . Wv[a*d:(a+1)*d, :]^T + bv[a*d:(a+1)*d]
+    X = bf16_grid(rng.standard_normal((B, A, H)))
+    Wv = bf16_grid(rng.standard_normal((H, H)) * 0.1)
+    bv = rng.standard_normal(H).astype(np.float32)
+    C2 = torch.zeros((B, H), dtype=torch.float32, device="cuda")
+    mt.op_linear_sub(dev(X, torch.bfloat16), A * H, dev(Wv, torch.bfloat16), 0, dev(bv), C2, H, B, d, H, A, H, d * H, d, d, out_f32=True)
+    got = C2.cpu().numpy()
+    for a in range(A):
+        ref = oracle.linear(X[:, a, :].copy(), Wv[a * d:(a + 1) * d].copy(), bv[a * d:(a + 1) * d].copy())
+        assert np.abs(got[:, a * d:(a + 1) * d] - ref).max() <= 2e-4 * max(1.0, np.abs(ref).max())
+    # (3) ragged batch: sequence u owns rows row0[u] .. row0[u]+rows[u]-1 of a packed row order (lengths 0..70,
+    #     crossing 32-row blocks) and has its own small W (12 rows, like one row per head)
+    lens = np.array([5, 33, 1, 64, 0, 70, 32, 17], dtype=np.int32)
+    row0 = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.int32)
+    R, Np, K = int(lens.sum()), 12, 192
+    Xr = bf16_grid(rng.standard_normal((R, K)))
+    Wq = bf16_grid(rng.standard_normal((len(lens), Np, K)) * 0.1)
+    C3 = torch.full((R + 3, Np), -5.0, dtype=torch.float32, device="cuda")
+    mt.op_linear_sub(dev(Xr, torch.bfloat16), K, dev(Wq, torch.bfloat16), 0, None, C3, Np, 80, Np, K, len(lens), 0, Np * K, 0,
+                     row0=dev(row0), rows=dev(lens), out_f32=True)
+    got = C3.cpu().numpy()
+    for u in range(len(lens)):
+        if lens[u] == 0:
+            continue
+        ref = oracle.linear(Xr[row0[u]:row0[u] + lens[u]].copy(), Wq[u].copy(), None)
+        assert np.abs(got[row0[u]:row0[u] + lens[u]] - ref).max() <= 2e-4 * max(1.0, np.abs(ref).max())
+    assert (got[R:] == -5.0).all()
+    torch.cuda.synchronize()
+
+
 def test_gemm_f32_vs_oracle():
     rng = np.random.default_rng(4)
     for (M, N, K) in ((70, 67, 33), (5, 3, 64), (130, 129, 100)):
