@@ -213,6 +213,16 @@ int mt_op_linear_sub(const void* d_A, int64_t lda, const void* d_W, int64_t ldw,
                      int32_t M, int32_t N, int32_t K, int32_t n_sub, int64_t sub_a, int64_t sub_w, int64_t sub_c,
                      int64_t sub_bias, const int32_t* d_sub_row0, const int32_t* d_sub_rows, int32_t out_f32,
                      void* hip_stream);
+
+/* The softmax and weighted row sum of the first-token attention (Section 3.3 head; see mt_op_linear_sub):
+ * for sequence b owning rows d_seq_start[b] .. +d_seq_len[b]-1 of the padding-free row order and head a < heads,
+ *   p = softmax_j(d_scores[row_j][a] / sqrt(hidden/heads)),  d_xbar[b][a][:] = sum_j p_j * d_x[row_j][:].
+ * d_scores float32 [rows][heads_pad], d_x bf16 [rows][hidden], d_xbar bf16 [batch][heads_pad][hidden] (pad heads
+ * are not written); heads <= heads_pad <= 16, heads_pad % 4 == 0, seq * heads_pad * 4 <= 64 KiB.
+ * Errors: NULL, SHAPE. */
+int mt_op_first_token_pool(const float* d_scores, const void* d_x, void* d_xbar, const int32_t* d_seq_start,
+                           const int32_t* d_seq_len, int32_t batch, int32_t seq, int32_t hidden, int32_t heads,
+                           int32_t heads_pad, void* hip_stream);
 /* ctx[b,s,a*d:(a+1)*d] = softmax(q k^T / sqrt(d) + mask) v per head; d_qkv is [B*S][3H] act
  * (columns Q | K | V), d_ctx [B*S][H] act. */
 int mt_op_attention(int32_t precision, const void* d_qkv, const int32_t* d_mask, void* d_ctx,

@@ -25,7 +25,7 @@ KERNEL_CLASSES = ["embed", "gemm_qkv", "attn", "gemm_out", "ln", "gemm_ffn1", "g
 EXPORTS = ["mt_create", "mt_destroy", "mt_weight_bytes", "mt_workspace_bytes", "mt_bind", "mt_load_weights",
            "mt_forward", "mt_logit_offset", "mt_n_logits", "mt_layer_count", "mt_last_error", "mt_error_name",
            "mt_read_hidden", "mt_profile_enable", "mt_profile_read", "mt_op_linear", "mt_op_attention",
-           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed", "mt_op_linear_sub"]
+           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed", "mt_op_linear_sub", "mt_op_first_token_pool"]
 
 
 class mt_task_desc(C.Structure):
@@ -80,6 +80,7 @@ def lib():
         L.mt_op_attention.argtypes = [i32, vp, vp, vp, i32, i32, i32, i32, vp]
         L.mt_op_layernorm.argtypes = [vp, vp, vp, C.c_float, vp, vp, i32, i32, vp]
         L.mt_debug_set_gemm_tile.argtypes = [i32]
+        L.mt_op_first_token_pool.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
         L.mt_op_linear_sub.argtypes = [vp, i64, vp, i64, vp, vp, i64, i32, i32, i32, i32, i64, i64, i64, i64, vp, vp, i32, vp]
         L.mt_debug_set_gemm_tile.restype = i32
         _lib = L
@@ -229,6 +230,17 @@ def op_linear_sub(A, lda, W, ldw, bias, C, ldc, M, N, K, n_sub, sub_a, sub_w, su
     if rc != MT_OK:
         raise MTError(rc, "mt_op_linear_sub")
     return C
+
+
+def op_first_token_pool(scores, x, seq_start, seq_len, batch, seq, hidden, heads, heads_pad):
+    """mt_op_first_token_pool on device tensors; returns xbar [batch][heads_pad][hidden] bf16 (pad heads zero)."""
+    import torch
+    xbar = torch.zeros((batch, heads_pad, hidden), dtype=torch.bfloat16, device=x.device)
+    rc = lib().mt_op_first_token_pool(_ptr(scores), _ptr(x), _ptr(xbar), _ptr(seq_start), _ptr(seq_len), batch, seq, hidden, heads,
+                                      heads_pad, _stream())
+    if rc != MT_OK:
+        raise MTError(rc, "mt_op_first_token_pool")
+    return xbar
 
 
 def mfma_peak(iters=4000):

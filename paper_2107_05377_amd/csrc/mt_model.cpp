@@ -1205,6 +1205,23 @@ int mt_op_linear_sub(const void* d_A, int64_t lda, const void* d_W, int64_t ldw,
     return e == hipSuccess ? MT_OK : MT_ERR_HIP;
 }
 
+int mt_op_first_token_pool(const float* d_scores, const void* d_x, void* d_xbar, const int32_t* d_seq_start,
+                           const int32_t* d_seq_len, int32_t batch, int32_t seq, int32_t hidden, int32_t heads,
+                           int32_t heads_pad, void* hip_stream)
+{
+    if (!d_scores || !d_x || !d_xbar || !d_seq_start || !d_seq_len) return MT_ERR_NULL;
+    if (batch < 1 || seq < 1 || hidden < 2 || heads < 1 || hidden % heads != 0) return MT_ERR_SHAPE;
+    PoolGroup pg;
+    memset(&pg, 0, sizeof pg);
+    pg.scores[0] = d_scores;
+    pg.x[0] = d_x;
+    pg.xbar[0] = d_xbar;
+    hipError_t e = launch_first_token_pool(pg, 1, d_seq_start, d_seq_len, batch, seq, hidden, heads, heads_pad,
+                                           static_cast<hipStream_t>(hip_stream));
+    if (e == hipErrorInvalidValue) return MT_ERR_SHAPE;
+    return e == hipSuccess ? MT_OK : MT_ERR_HIP;
+}
+
 int mt_op_linear_batched(int32_t precision, int32_t G, const void* d_A, int64_t strideA, int64_t lda, const void* d_W,
                          int64_t strideW, const float* d_bias, int64_t strideBias, const float* d_residual,
                          int64_t strideRes, void* d_C, int64_t strideC, int64_t ldc, int32_t M, int32_t N, int32_t K,

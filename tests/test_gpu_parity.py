@@ -166,6 +166,29 @@ def test_gemm_sub_problems_and_ragged_batches_vs_oracle():
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("H,A,A_pad", [(768, 12, 12), (128, 2, 4), (1024, 16, 16), (320, 5, 8)])
+def test_first_token_pool_vs_oracle(H, A, A_pad):
+    """Softmax over each sequence's rows of given raw scores and the weighted sum of its input rows, per head."""
+    rng = np.random.default_rng(5 + H)
+    lens = np.array([1, 9, 64, 8, 0, 128, 65, 7, 100], dtype=np.int32)
+    row0 = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.int32)
+    R, B, S = int(lens.sum()), len(lens), 128
+    scores = (rng.standard_normal((R, A_pad)) * 20.0).astype(np.float32)
+    X = bf16_grid(rng.standard_normal((R, H)))
+    got = mt.op_first_token_pool(dev(scores), dev(X, torch.bfloat16), dev(row0), dev(lens), B, S, H, A, A_pad).float().cpu().numpy()
+    scale = np.float32(1.0 / np.sqrt(np.float32(H // A)))
+    for b in range(B):
+        if lens[b] == 0:
+            continue
+        rows = slice(row0[b], row0[b] + lens[b])
+        for a in range(A):
+            p = oracle.softmax_row((scores[rows, a] * scale).astype(np.float32))
+            ref = p.astype(np.float64) @ X[rows].astype(np.float64)
+            assert np.abs(got[b, a] - ref).max() <= 2 ** -8 * max(np.abs(ref).max(), 1e-3) + 1e-4, (b, a)
+    assert (got[:, A:, :] == 0).all()
+    torch.cuda.synchronize()
+
+
 def test_gemm_f32_vs_oracle():
     rng = np.random.default_rng(4)
     for (M, N, K) in ((70, 67, 33), (5, 3, 64), (130, 129, 100)):
