@@ -119,7 +119,7 @@ def main():
                          "hardware byte counters by); untimed")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (sequences are independent, so N GPUs would run N "
+        print("bench.py: this benchmark measures one GPU only (sequences are independent, so N GPUs would run N "
               "replicas with no collectives); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 

@@ -6,12 +6,14 @@
 // their count being read from device memory so that the host never waits for it.
 //
 // Schedule.  The trunk (shared frozen layers) runs once up to the deepest fork among the enabled
-// tasks; the hidden state after every layer some task forks at is kept (a "tap").  Branches then
-// advance in lock step: stage s runs layer s of every enabled task that has at least s own layers,
-// as grouped launches with one problem per task, reading either the task's tap (s = 1) or its own
-// state.  A task's LAST own layer feeds only the pooler, which reads the first token: that layer computes
-// keys and values for all rows but queries, attention output, projection, FFN and LayerNorms for the
-// first-token rows only (exactly the same logits, ~5/6 of the layer's work saved).
+// tasks; the hidden state after every layer some task forks at is kept (a "tap").  Trunk and branches
+// advance as one wavefront of layer steps: step k runs trunk layer k+1 and, for every enabled task that
+// forked at or before k, that task's own layer k - fork, all as grouped launches with one problem per
+// layer instance, a branch reading its tap at its first own layer and its own state afterwards.
+// A task's LAST own layer feeds only the pooler, which reads the first token: that layer is evaluated for
+// the first-token rows only.  In bfloat16 mode it projects no keys or values either: the query is folded
+// into the key matrix (Wk^T q per head), scores are taken against the layer input rows directly, and the
+// value matrix is applied to the probability-weighted row sums (exactly the same attention, up to rounding).
 // Finally one grouped pooler launch and one grouped classifier launch write all logits.
 #include <hip/hip_runtime.h>
 
