@@ -560,14 +560,13 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
         // number of 256x256 tiles the bound implies and errs towards the smaller tile when few.
         //   many tiles: 256x256 with 8 wavefronts (least L2 traffic per flop); the GELU epilogue's vector
         //   work instead prefers 8 wavefronts of 64x64 on a 256x128 tile, two workgroups per CU;
-        //   few tiles (single problem): 128x128, two or three workgroups per CU, slice-scope fragment buffers
-        //   (4 MFMAs per K step cannot hide an LDS read behind one step).
+        //   few tiles (single problem): 128x128 (wide outputs) or 64x128 (narrow outputs), two workgroups per CU,
+        //   slice-scope fragment buffers (4 MFMAs per K step cannot hide an LDS read behind one step).
         const long t256 = (long)s.G * s.splits * ((s.M + 255) / 256) * ((s.N + 255) / 256);
         const bool gelu = s.act == ACT_GELU_ERF || s.act == ACT_GELU_TANH;
         if (t256 >= 256) sel = gelu ? 11 : MT_GEMM_BIG_TILE;
-        else if (s.K / s.splits >= 2048) sel = 1;
         else if (s.N >= 2048) sel = 19;
-        else sel = 18;
+        else sel = 25;                      // narrow output: 64-row tiles double the tile count, so K needs less splitting
     }
     switch (sel) {
         case 2: return launch_cfg<256, 128, 2, 2, 32, 3, 2>(g, s, stream);   // 72 KB LDS: two workgroups per CU
@@ -592,6 +591,9 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
         case 21: return launch_cfg<256, 128, 4, 2, 32, 3, 2, 1>(g, s, stream);
         case 22: return launch_cfg<256, 256, 2, 4, 32, 4, 2, 1>(g, s, stream);
         case 23: return launch_cfg<128, 128, 2, 2, 32, 5, 2, 1>(g, s, stream);  // 80 KB: two workgroups per CU, 4 slices ahead
+        case 24: return launch_cfg<64, 128, 2, 2, 32, 4, 2, 1>(g, s, stream);   // 48 KB: narrow outputs without a K split
+        case 25: return launch_cfg<64, 128, 2, 2, 64, 3, 2, 1>(g, s, stream);   // 72 KB
+        case 26: return launch_cfg<64, 256, 2, 2, 32, 4, 2, 1>(g, s, stream);   // 80 KB
         default: return launch_cfg<128, 128, 2, 2, 32, 4, 2>(g, s, stream);  // 64 KB LDS
     }
 }

@@ -55,7 +55,7 @@ SMALL = ms.MTSpec("small", vocab=500, hidden=128, heads=2, ffn=256, max_pos=64, 
 
 # ------------------------------------------------------------------ single operations
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 22, 23])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 22, 23, 24, 25, 26])
 def test_gemm_bf16_vs_oracle(tile):
     say(f"gemm_bf16 tile={tile}")
     rng = np.random.default_rng(10 + tile)
