@@ -44,6 +44,15 @@ namespace {
 #ifndef MT_GEMM_BIG_TILE
 #define MT_GEMM_BIG_TILE 9
 #endif
+#ifndef MT_GEMM_GELU_TILE
+#define MT_GEMM_GELU_TILE 11
+#endif
+#ifndef MT_GEMM_WIDE_TILE
+#define MT_GEMM_WIDE_TILE 19
+#endif
+#ifndef MT_GEMM_NARROW_TILE
+#define MT_GEMM_NARROW_TILE 25
+#endif
 #ifndef MT_GEMM_DSPER
 #define MT_GEMM_DSPER 1
 #endif
@@ -564,9 +573,9 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
         //   slice-scope fragment buffers (4 MFMAs per K step cannot hide an LDS read behind one step).
         const long t256 = (long)s.G * s.splits * ((s.M + 255) / 256) * ((s.N + 255) / 256);
         const bool gelu = s.act == ACT_GELU_ERF || s.act == ACT_GELU_TANH;
-        if (t256 >= 256) sel = gelu ? 11 : MT_GEMM_BIG_TILE;
-        else if (s.N >= 2048) sel = 19;
-        else sel = 25;                      // narrow output: 64-row tiles double the tile count, so K needs less splitting
+        if (t256 >= 256) sel = gelu ? MT_GEMM_GELU_TILE : MT_GEMM_BIG_TILE;
+        else if (s.N >= 2048) sel = MT_GEMM_WIDE_TILE;
+        else sel = MT_GEMM_NARROW_TILE;                      // narrow output: 64-row tiles double the tile count, so K needs less splitting
     }
     switch (sel) {
         case 2: return launch_cfg<256, 128, 2, 2, 32, 3, 2>(g, s, stream);   // 72 KB LDS: two workgroups per CU
