@@ -353,6 +353,22 @@ def test_bf16_mode_small_model_matches_oracle(stress):
     model.close()
 
 
+def test_bf16_mode_many_heads_takes_the_projected_key_value_form():
+    """More than 16 heads: the last layer of a branch projects keys and values for every row and attends with
+    one wavefront per (task, sequence, head) instead of the key/value-free form; same logits contract."""
+    spec = ms.MTSpec("wide", vocab=300, hidden=1280, heads=20, ffn=256, max_pos=48, n_trunk_layers=1,
+                     tasks=(ms.TaskSpec(1, 2, 3), ms.TaskSpec(0, 1, 2)), precision="bf16",
+                     batch=5, seq=40, len_lo=3, len_hi=40, input_seed=123)
+    tr, tri, tps = _params(spec, True, 0.03)
+    orc = oracle.Oracle(spec, tr, [p for p, _ in tps])
+    model = _load(spec, tr, tri, tps)
+    ids, mask, _ = ms.make_inputs(spec)
+    err = np.abs(model.forward(dev(ids), dev(mask)).cpu().numpy() - orc.mt_forward(ids, mask)).max()
+    say(f"  20 heads: max |dlogit| {err:.4g}")
+    assert err <= 2e-2
+    model.close()
+
+
 def test_bf16_mode_masks_with_holes_and_extreme_lengths():
     """Padding-free row order: masks that are not prefixes, a sequence of one token, full sequences."""
     spec = SMALL
