@@ -37,6 +37,10 @@ __device__ inline int k_chunk_off(int row, int chunk) { return row * 128 + ((chu
 #ifndef MT_ATTN_MINW
 #define MT_ATTN_MINW 2
 #endif
+#ifndef MT_ATTN_CB
+#define MT_ATTN_CB 4
+#endif
+constexpr int CB = MT_ATTN_CB;        // 32-key blocks per online-softmax chunk
 __global__ __launch_bounds__(256, MT_ATTN_MINW) void attention_bf16_kernel(AttnGroup g, const int32_t* __restrict__ mask,
                                                              const int32_t* __restrict__ seq_start,
                                                              const int32_t* __restrict__ seq_len, int B, int S, int H, int Sk_max,
@@ -145,19 +149,19 @@ __global__ __launch_bounds__(256, MT_ATTN_MINW) void attention_bf16_kernel(AttnG
         for (int e = 0; e < 16; ++e) o[dt][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    for (int c0 = 0; c0 < nblk; c0 += 4) {
-        int valid[4];
+    for (int c0 = 0; c0 < nblk; c0 += CB) {
+        int valid[CB];
         int any = 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < CB; ++j) {
             valid[j] = (c0 + j < nblk) ? blk_any[c0 + j] : 0;
             any |= valid[j];
         }
         if (!any) continue;
-        f32x16 sc[4];
+        f32x16 sc[CB];
         float mloc = -INFINITY;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < CB; ++j) {
             if (valid[j]) {
                 const int jb = c0 + j;
                 f32x16 acc;
@@ -190,7 +194,7 @@ __global__ __launch_bounds__(256, MT_ATTN_MINW) void attention_bf16_kernel(AttnG
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);     // 0 on the first chunk (m_run = -inf)
         float lsum = 0.f;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < CB; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const float p = __builtin_amdgcn_exp2f(sc[j][e] - m_new);    // bare v_exp_f32: tiny weights flush to 0
@@ -206,7 +210,7 @@ __global__ __launch_bounds__(256, MT_ATTN_MINW) void attention_bf16_kernel(AttnG
             for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
 
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < CB; ++j) {
             if (!valid[j]) continue;
             const int jb = c0 + j;
 #pragma unroll
