@@ -153,6 +153,12 @@ int mt_n_logits(const mt_model* m);
  * evaluated per request, n_trunk_layers + sum_t n_layers. */
 int mt_layer_count(const mt_model* m);
 
+/* Sequential layer steps of the wavefront schedule for the enabled tasks (h_task_mask as in mt_forward, NULL =
+ * all): trunk layer k+1 and every branch layer whose input exists run together in step k, so the count is
+ * max(D', max_t(fork_t + n_layers_t)) with D' the deepest enabled fork (Fig. 1(c)); a schedule that finished the
+ * trunk before starting any branch would need D' + max_t n_layers_t.  Host only.  Errors: NULL. */
+int mt_schedule_steps(const mt_model* m, const uint8_t* h_task_mask);
+
 /* Text of the last error on this model ("" if none).  mt_error_name maps a code to its name. */
 const char* mt_last_error(const mt_model* m);
 const char* mt_error_name(int code);

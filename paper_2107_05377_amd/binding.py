@@ -25,7 +25,7 @@ KERNEL_CLASSES = ["embed", "gemm_qkv", "attn", "gemm_out", "ln", "gemm_ffn1", "g
 EXPORTS = ["mt_create", "mt_destroy", "mt_weight_bytes", "mt_workspace_bytes", "mt_bind", "mt_load_weights",
            "mt_forward", "mt_logit_offset", "mt_n_logits", "mt_layer_count", "mt_last_error", "mt_error_name",
            "mt_read_hidden", "mt_profile_enable", "mt_profile_read", "mt_op_linear", "mt_op_attention",
-           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed", "mt_op_linear_sub", "mt_op_first_token_pool"]
+           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed", "mt_op_linear_sub", "mt_op_first_token_pool", "mt_schedule_steps"]
 
 
 class mt_task_desc(C.Structure):
@@ -74,6 +74,7 @@ def lib():
         L.mt_profile_enable.argtypes = [vp, i32]
         L.mt_profile_read.argtypes = [vp, vp, vp]
         L.mt_share_weights.argtypes = [vp, vp]
+        L.mt_schedule_steps.argtypes = [vp, vp]
         L.mt_debug_mfma_peak.argtypes = [i32, vp, C.c_size_t, vp, vp]
         L.mt_op_linear.argtypes = [i32, vp, i64, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, vp]
         L.mt_op_linear_batched.argtypes = [i32, i32, vp, i64, i64, vp, i64, vp, i64, vp, i64, vp, i64, i64, i32, i32, i32, i32, i32, vp]

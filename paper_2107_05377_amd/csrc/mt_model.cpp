@@ -800,6 +800,17 @@ int mt_layer_count(const mt_model* m)
     for (const auto& d : m->tasks) n += d.n_layers;
     return n;
 }
+int mt_schedule_steps(const mt_model* m, const uint8_t* h_task_mask)
+{
+    if (!m) return MT_ERR_NULL;
+    int steps = 0;
+    for (size_t t = 0; t < m->tasks.size(); ++t) {
+        if (h_task_mask && !h_task_mask[t]) continue;
+        steps = std::max(steps, m->tasks[t].fork_layer + m->tasks[t].n_layers);
+    }
+    return steps;
+}
+
 const char* mt_last_error(const mt_model* m) { return m ? m->err.c_str() : "null model"; }
 
 int mt_bind(mt_model* m, void* d_weights, size_t weight_bytes, void* d_workspace, size_t workspace_bytes)
@@ -981,8 +992,7 @@ int mt_forward_typed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_t
     //      sequence: a branch starts as soon as its tap exists instead of waiting for the whole trunk, so the
     //      number of sequential layer steps is max(D, max_t(fork_t + layers_t)) instead of D + max_t layers_t.
     //      A task's last own layer takes the first-token-only path.
-    int n_steps = depth;
-    for (int t : enabled) n_steps = std::max(n_steps, m->tasks[t].fork_layer + m->tasks[t].n_layers);
+    const int n_steps = mt_schedule_steps(m, h_task_mask);      // >= depth: every fork is a fork + 0 layers bound
     (void)max_y;
     for (int step = 0; step < n_steps; ++step) {
         std::vector<LayerIO> full;

@@ -148,6 +148,26 @@ def test_industrial_workload_layer_count():
     mt.lib().mt_destroy(h)
 
 
+def test_wavefront_schedule_step_counts():
+    """A branch starts as soon as its tap exists: steps = max over tasks of fork + own layers (Fig. 1(c))."""
+    L = mt.lib()
+    _, h, _ = _create(ms.get_config("base"))
+    assert L.mt_schedule_steps(h, None) == 8 + 2
+    L.mt_destroy(h)
+    spec = ms.get_config("hetero")                      # forks 11,10,9,8,7,6,6,8 with 1,1,2,2,3,3,3,2 own layers
+    _, h, _ = _create(spec)
+    assert L.mt_schedule_steps(h, None) == 12           # a trunk-first schedule would take 11 + 3 = 14
+    only = (C.c_uint8 * 8)(0, 0, 0, 0, 0, 1, 0, 0)      # task 5 alone: fork 6 + 3 layers
+    assert L.mt_schedule_steps(h, only) == 9
+    L.mt_destroy(h)
+    fig = ms.MTSpec("fig1c", vocab=100, hidden=64, heads=1, ffn=64, max_pos=16, n_trunk_layers=8,
+                    tasks=(ms.TaskSpec(4, 3, 2), ms.TaskSpec(8, 2, 2)), precision="fp32", batch=1, seq=8, len_lo=1, len_hi=8,
+                    input_seed=1)
+    _, h, _ = _create(fig)
+    assert L.mt_layer_count(h) == 13 and L.mt_schedule_steps(h, None) == 10
+    L.mt_destroy(h)
+
+
 def test_share_weights_checks():
     """A replica must match the owner's configuration, share its weight arena, bring a workspace of its own,
     and the owner must have something loaded."""
