@@ -145,6 +145,18 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
 int mt_forward_typed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask, int32_t batch, int32_t seq,
                const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream);
 
+/*
+ * Per-sequence task routing (Section 5.2 discusses that every task is computed for every request; a serving
+ * system that knows which tasks a request needs can skip the rest): h_route is a host array [batch][n_tasks],
+ * nonzero = sequence b wants task t.  The trunk runs once for the whole batch, as deep as the deepest wanted
+ * fork; tasks wanted by the same set of sequences form a group whose sequences are gathered into a row order of
+ * their own, on which the group's branch layers, poolers and classifiers run.  Logits of wanted (b, t) pairs are
+ * written to d_out_logits[b][mt_logit_offset(t)..]; all other entries are left untouched.  batch <= 1024.
+ * d_token_type_ids may be NULL.  Errors as mt_forward.  After this call mt_read_hidden serves trunk taps only.
+ */
+int mt_forward_routed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask,
+                      int32_t batch, int32_t seq, const uint8_t* h_route, float* d_out_logits, void* hip_stream);
+
 /* Column of task t's first logit, or MT_ERR_SHAPE.  mt_n_logits = C_tot. */
 int mt_logit_offset(const mt_model* m, int32_t task);
 int mt_n_logits(const mt_model* m);

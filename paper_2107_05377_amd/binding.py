@@ -25,7 +25,7 @@ KERNEL_CLASSES = ["embed", "gemm_qkv", "attn", "gemm_out", "ln", "gemm_ffn1", "g
 EXPORTS = ["mt_create", "mt_destroy", "mt_weight_bytes", "mt_workspace_bytes", "mt_bind", "mt_load_weights",
            "mt_forward", "mt_logit_offset", "mt_n_logits", "mt_layer_count", "mt_last_error", "mt_error_name",
            "mt_read_hidden", "mt_profile_enable", "mt_profile_read", "mt_op_linear", "mt_op_attention",
-           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed", "mt_op_linear_sub", "mt_op_first_token_pool", "mt_schedule_steps"]
+           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed", "mt_op_linear_sub", "mt_op_first_token_pool", "mt_schedule_steps", "mt_forward_routed"]
 
 
 class mt_task_desc(C.Structure):
@@ -63,6 +63,7 @@ def lib():
         L.mt_load_weights.argtypes = [vp, i32, vp, sz, vp]
         L.mt_forward.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_typed.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
+        L.mt_forward_routed.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_logit_offset.argtypes = [vp, i32]
         L.mt_n_logits.argtypes = [vp]
         L.mt_layer_count.argtypes = [vp]
@@ -204,6 +205,15 @@ class Model:
         else:
             assert type_ids.shape == ids.shape
             self._check(lib().mt_forward_typed(self.h, _ptr(ids), _ptr(type_ids), _ptr(mask), b, s, tm, _ptr(out), _stream()))
+        return out
+
+    def forward_routed(self, ids, mask, route, out, type_ids=None):
+        """route: [B][n_tasks] array-like of 0/1 (host); logits of wanted (b, t) pairs are written into `out`."""
+        b, s = ids.shape
+        r = np.ascontiguousarray(np.asarray(route) != 0, dtype=np.uint8)
+        assert r.shape == (b, self.cfg.n_tasks)
+        self._check(lib().mt_forward_routed(self.h, _ptr(ids), _ptr(type_ids) if type_ids is not None else None, _ptr(mask), b, s,
+                                            r.ctypes.data_as(C.c_void_p), _ptr(out), _stream()))
         return out
 
     def read_hidden(self, task: int, layer: int, batch: int, seq: int):

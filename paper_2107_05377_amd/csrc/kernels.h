@@ -158,6 +158,22 @@ struct ClsGroup {
     float* out[kMaxGroup];            // first logit column of the task, row stride ldo
     int32_t C[kMaxGroup];
 };
-hipError_t launch_classifier(const ClsGroup& g, int G, int B, int H, int maxC, int w_bf16, int64_t ldo, hipStream_t stream);
+// out_row: optional device array [B], logits row of compact row b (per-sequence routing); NULL = row b.
+hipError_t launch_classifier(const ClsGroup& g, int G, int B, int H, int maxC, int w_bf16, int64_t ldo, const int32_t* out_row,
+                             hipStream_t stream);
+
+// Per-sequence task routing: a sub-batch of the sequences, as a padding-free row order of its own.
+// idx lists the chosen sequences (ascending batch indices), passed by value with the launch.
+constexpr int kMaxRouted = 1024;
+struct RouteIdx {
+    uint16_t seq[kMaxRouted];
+};
+// From the batch's row map (g_start, g_len) builds the sub-batch's: c_start/c_len [n_sel], *c_n rows in all,
+// c_src[r] = row of the batch order that compact row r copies, c_seq[i] = idx.seq[i] (as int32, for the logits rows).
+hipError_t launch_route_map(const RouteIdx& idx, int n_sel, const int32_t* g_start, const int32_t* g_len, int32_t* c_start,
+                            int32_t* c_len, int32_t* c_src, int32_t* c_seq, int32_t* c_n, hipStream_t stream);
+// out_f[r] = in_f[c_src[r]] (float32 rows) and out_a[r] = in_a[c_src[r]] (act_bytes per element; both optional), r < *c_n <= max_rows.
+hipError_t launch_route_gather(const float* in_f, const void* in_a, float* out_f, void* out_a, const int32_t* c_src, const int32_t* c_n,
+                               int max_rows, int H, int act_bytes, hipStream_t stream);
 
 }  // namespace mt

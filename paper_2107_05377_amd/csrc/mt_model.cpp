@@ -69,6 +69,9 @@ struct ClsScratch {   // per task with own layers: compact [max_batch] x ... buf
     size_t in_f, in_a, q, ctx, y, x1f, x1a, u, out_f;
     size_t qt = 0, scores = 0, xbar = 0;   // bf16 mode: Wk^T q [max_batch][A_pad][H], raw scores [M][A_pad], weighted row sums
 };
+struct RouteMapOff {   // byte offsets of a sub-batch row map (per-sequence routing), one per task
+    size_t n, src, start, len, seq;
+};
 struct ProfRec {
     int klass;
     hipEvent_t t0, t1;
@@ -115,6 +118,7 @@ struct mt_model {
     bool profiling = false;
     std::vector<ProfRec> prof;
     std::vector<hipEvent_t> event_pool;
+    std::vector<RouteMapOff> route;
 
     std::string err;
 };
@@ -754,10 +758,19 @@ int mt_create(const mt_config* cfg, mt_model** out)
             m->task_cls.push_back(c);
         } else {
             m->task_scr.push_back(Scratch{});
-            m->task_xf.push_back(0);
-            m->task_xb.push_back(0);
+            m->task_xf.push_back(sb.take(M * H * 4));          // only per-sequence routing uses it: the sub-batch's tap rows
+            m->task_xb.push_back(m->bf16 ? sb.take(M * H * 2) : 0);
             m->task_cls.push_back(ClsScratch{});
         }
+    }
+    for (size_t t = 0; t < T; ++t) {
+        RouteMapOff r;
+        r.n = sb.take(4);
+        r.src = sb.take(M * 4);
+        r.start = sb.take(MB * 4);
+        r.len = sb.take(MB * 4);
+        r.seq = sb.take(MB * 4);
+        m->route.push_back(r);
     }
     m->rm_n = sb.take(4);
     m->rm_src = sb.take(M * 4);
@@ -934,8 +947,11 @@ int mt_load_weights(mt_model* m, int32_t scope, const void* h_blob, size_t nbyte
     return MT_OK;
 }
 
-int mt_forward_typed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask, int32_t batch, int32_t seq,
-               const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream)
+// The forward pass.  h_route == NULL: every enabled task (h_task_mask) runs on every sequence, branches interleaved
+// with the trunk.  h_route [batch][n_tasks]: per-sequence routing, a task runs on the sequences that ask for it.
+static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask,
+                        int32_t batch, int32_t seq, const uint8_t* h_task_mask, const uint8_t* h_route, float* d_out_logits,
+                        void* hip_stream)
 {
     if (!m) return MT_ERR_NULL;
     if (!d_input_ids || !d_attn_mask || !d_out_logits) return fail(m, MT_ERR_NULL, "mt_forward: null device pointer");
@@ -943,6 +959,14 @@ int mt_forward_typed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_t
     if (batch < 1 || seq < 1 || batch > m->cfg.max_batch || seq > m->cfg.max_seq)
         return fail(m, MT_ERR_SHAPE, "mt_forward: batch %d x seq %d outside 1..%d x 1..%d", batch, seq, m->cfg.max_batch, m->cfg.max_seq);
     const int T = (int)m->tasks.size();
+    if (h_route && batch > kMaxRouted) return fail(m, MT_ERR_SHAPE, "mt_forward_routed: at most %d sequences per call", kMaxRouted);
+    std::vector<uint8_t> route_any;                     // routed mode: does any sequence ask for task t
+    if (h_route) {
+        route_any.assign(T, 0);
+        for (int b = 0; b < batch; ++b)
+            for (int t = 0; t < T; ++t) route_any[t] |= h_route[(size_t)b * T + t] ? 1 : 0;
+        h_task_mask = route_any.data();
+    }
     std::vector<int> enabled;
     int depth = 0, max_y = 0;
     for (int t = 0; t < T; ++t) {
@@ -992,7 +1016,8 @@ int mt_forward_typed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_t
     //      sequence: a branch starts as soon as its tap exists instead of waiting for the whole trunk, so the
     //      number of sequential layer steps is max(D, max_t(fork_t + layers_t)) instead of D + max_t layers_t.
     //      A task's last own layer takes the first-token-only path.
-    const int n_steps = mt_schedule_steps(m, h_task_mask);      // >= depth: every fork is a fork + 0 layers bound
+    // routed mode: the trunk alone here, the branches follow per group of sequences
+    const int n_steps = h_route ? depth : mt_schedule_steps(m, h_task_mask);      // >= depth: every fork is a fork + 0 layers bound
     (void)max_y;
     for (int step = 0; step < n_steps; ++step) {
         std::vector<LayerIO> full;
@@ -1004,6 +1029,7 @@ int mt_forward_typed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_t
             full.push_back(LayerIO{cur_f, cur_b, &m->trunk[step], &m->trunk_scr, nf, nb});
         }
         for (int t : enabled) {
+            if (h_route) break;
             const mt_task_desc& d = m->tasks[t];
             const int stage = step - d.fork_layer;
             if (stage < 0 || stage >= d.n_layers) continue;
@@ -1040,8 +1066,9 @@ int mt_forward_typed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_t
 
     // ---- poolers and classifiers.  The pooler input stays float32-accurate in both modes: the bf16
     // path feeds the matrix cores with the [hi | lo] split of the first-token rows against [W | W].
-    for (size_t lo = 0; lo < enabled.size(); lo += kMaxGroup) {
-        const int n = (int)std::min(enabled.size() - lo, (size_t)kMaxGroup);
+    auto run_heads = [&](const std::vector<int>& list, const RowMap& hrm, int HB, bool gathered, const int32_t* out_row) {
+    for (size_t lo = 0; lo < list.size(); lo += kMaxGroup) {
+        const int n = (int)std::min(list.size() - lo, (size_t)kMaxGroup);
         GemmGroup g;
         memset(&g, 0, sizeof g);
         SplitGroup sg;
@@ -1050,9 +1077,10 @@ int mt_forward_typed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_t
         memset(&cg, 0, sizeof cg);
         int maxC = 0;
         for (int i = 0; i < n; ++i) {
-            const int t = enabled[lo + i];
+            const int t = list[lo + i];
             const mt_task_desc& d = m->tasks[t];
             const float* z = d.n_layers > 0 ? (const float*)(ws + m->task_cls[t].out_f)     // one row per sequence already
+                             : gathered     ? (const float*)(ws + m->task_xf[t])          // the sub-batch's copy of the tap
                                             : (const float*)(ws + m->tap_f[m->tap_of_layer[d.fork_layer]]);
             float* pooled = (float*)(ws + m->pooled + (size_t)t * m->cfg.max_batch * H * 4);
             sg.x[i] = z;
@@ -1073,27 +1101,107 @@ int mt_forward_typed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_t
         }
         L.begin(MT_K_POOL);
         if (bf) {
-            L.check(launch_cls_split(sg, n, B, H, rm.seq_start, S, B * S, L.st));
-            GemmShape s{n, B, H, 2 * H, 2 * H, H, 0, ACT_TANH, 1, nullptr, 1, 0};
+            L.check(launch_cls_split(sg, n, HB, H, hrm.seq_start, S, HB * S, L.st));
+            GemmShape s{n, HB, H, 2 * H, 2 * H, H, 0, ACT_TANH, 1, nullptr, 1, 0};
             L.check(launch_gemm_bf16(g, s, L.st));
         } else {
-            L.check(launch_gather_rows(sg, n, B, H, rm.seq_start, S, B * S, L.st));
-            GemmShape s{n, B, H, H, H, H, 0, ACT_TANH, 1, nullptr, 1, 0};
+            L.check(launch_gather_rows(sg, n, HB, H, hrm.seq_start, S, HB * S, L.st));
+            GemmShape s{n, HB, H, H, H, H, 0, ACT_TANH, 1, nullptr, 1, 0};
             L.check(launch_gemm_f32(g, s, 0, L.st));
         }
-        L.check(launch_classifier(cg, n, B, H, maxC, bf ? 1 : 0, m->C_tot, L.st));
+        L.check(launch_classifier(cg, n, HB, H, maxC, bf ? 1 : 0, m->C_tot, out_row, L.st));
         L.end();
+    }
+    };
+
+    if (!h_route) {
+        run_heads(enabled, rm, B, false, nullptr);
+    } else {
+        // ---- per-sequence routing: tasks wanted by the same set of sequences form a group; the group's sequences are
+        // gathered from each task's tap into a padding-free row order of their own, on which the task's layers,
+        // pooler and classifier run exactly as on a whole batch; logits land in the rows of the chosen sequences.
+        std::vector<char> done(T, 0);
+        for (int t0 : enabled) {
+            if (done[t0]) continue;
+            std::vector<int> grp_tasks;
+            for (int t : enabled) {
+                if (done[t]) continue;
+                bool same = true;
+                for (int b = 0; b < B && same; ++b) same = (h_route[(size_t)b * T + t] != 0) == (h_route[(size_t)b * T + t0] != 0);
+                if (same) {
+                    grp_tasks.push_back(t);
+                    done[t] = 1;
+                }
+            }
+            RouteIdx idx;
+            int nb = 0;
+            for (int b = 0; b < B; ++b)
+                if (h_route[(size_t)b * T + t0]) idx.seq[nb++] = (uint16_t)b;
+            const RouteMapOff& ro = m->route[t0];
+            RowMap crm{(int32_t*)(ws + ro.n), (int32_t*)(ws + ro.src), nullptr, (int32_t*)(ws + ro.start), (int32_t*)(ws + ro.len)};
+            int32_t* c_seq = (int32_t*)(ws + ro.seq);
+            L.begin(MT_K_EMBED);
+            L.check(launch_route_map(idx, nb, rm.seq_start, rm.seq_len, crm.seq_start, crm.seq_len, crm.src, c_seq, crm.n_rows, L.st));
+            for (int t : grp_tasks) {
+                const int tap = m->tap_of_layer[m->tasks[t].fork_layer];
+                L.check(launch_route_gather((const float*)(ws + m->tap_f[tap]), bf ? (const void*)(ws + m->tap_b[tap]) : nullptr,
+                                            (float*)(ws + m->task_xf[t]), bf ? (void*)(ws + m->task_xb[t]) : nullptr, crm.src, crm.n_rows,
+                                            nb * S, H, 2, L.st));
+            }
+            L.end();
+            int gy = 0;
+            for (int t : grp_tasks) gy = std::max(gy, m->tasks[t].n_layers);
+            for (int stage = 0; stage < gy; ++stage) {
+                std::vector<LayerIO> full;
+                std::vector<LastIO> last;
+                for (int t : grp_tasks) {
+                    const mt_task_desc& d = m->tasks[t];
+                    if (stage >= d.n_layers) continue;
+                    const float* in_f = (const float*)(ws + m->task_xf[t]);
+                    const void* in_b = bf ? (const void*)(ws + m->task_xb[t]) : nullptr;
+                    if (stage == d.n_layers - 1)
+                        last.push_back(LastIO{in_f, bf ? in_b : (const void*)in_f, &m->taskw[t].layers[stage], &m->task_scr[t], &m->task_cls[t]});
+                    else
+                        full.push_back(LayerIO{in_f, in_b, &m->taskw[t].layers[stage], &m->task_scr[t], (float*)(ws + m->task_xf[t]),
+                                               bf ? (void*)(ws + m->task_xb[t]) : nullptr});
+                }
+                for (size_t lo = 0; lo < full.size(); lo += kMaxGroup) {
+                    std::vector<LayerIO> part(full.begin() + lo, full.begin() + std::min(full.size(), lo + (size_t)kMaxGroup));
+                    run_layer_group(L, part, crm, nb, S);
+                }
+                for (size_t lo = 0; lo < last.size(); lo += kMaxGroup) {
+                    std::vector<LastIO> part(last.begin() + lo, last.begin() + std::min(last.size(), lo + (size_t)kMaxGroup));
+                    run_last_layer_group(L, part, crm, nb, S);
+                }
+            }
+            run_heads(grp_tasks, crm, nb, true, c_seq);
+        }
     }
 
     if (L.first_err != hipSuccess) return fail(m, MT_ERR_HIP, "mt_forward: launch failed: %s", hipGetErrorString(L.first_err));
-    for (int t : enabled) m->last_enabled[t] = 1;
+    if (!h_route)            // after a routed forward a task's state covers its own sub-batch only: not readable
+        for (int t : enabled) m->last_enabled[t] = 1;
     return MT_OK;
+}
+
+int mt_forward_typed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask, int32_t batch,
+                     int32_t seq, const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream)
+{
+    return forward_impl(m, d_input_ids, d_token_type_ids, d_attn_mask, batch, seq, h_task_mask, nullptr, d_out_logits, hip_stream);
 }
 
 int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_mask, int32_t batch, int32_t seq,
                const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream)
 {
-    return mt_forward_typed(m, d_input_ids, nullptr, d_attn_mask, batch, seq, h_task_mask, d_out_logits, hip_stream);
+    return forward_impl(m, d_input_ids, nullptr, d_attn_mask, batch, seq, h_task_mask, nullptr, d_out_logits, hip_stream);
+}
+
+int mt_forward_routed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask, int32_t batch,
+                      int32_t seq, const uint8_t* h_route, float* d_out_logits, void* hip_stream)
+{
+    if (!m) return MT_ERR_NULL;
+    if (!h_route) return fail(m, MT_ERR_NULL, "mt_forward_routed: null routing table");
+    return forward_impl(m, d_input_ids, d_token_type_ids, d_attn_mask, batch, seq, nullptr, h_route, d_out_logits, hip_stream);
 }
 
 int mt_read_hidden(mt_model* m, int32_t task, int32_t layer, float* d_out, size_t out_bytes, void* hip_stream)

@@ -336,9 +336,10 @@ __global__ __launch_bounds__(256) void place_first_rows_kernel(const float* __re
 }
 
 template <typename TW>
-__global__ __launch_bounds__(256) void classifier_kernel(ClsGroup g, int B, int H, int64_t ldo)
+__global__ __launch_bounds__(256) void classifier_kernel(ClsGroup g, int B, int H, int64_t ldo, const int32_t* __restrict__ out_row)
 {
     const int grp = blockIdx.y, b = blockIdx.x;
+    const int ob = out_row ? out_row[b] : b;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float* p = g.pooled[grp] + (size_t)b * H;
     for (int c = wave; c < g.C[grp]; c += 4) {
@@ -346,7 +347,74 @@ __global__ __launch_bounds__(256) void classifier_kernel(ClsGroup g, int B, int 
         float acc = 0.f;
         for (int i = lane; i < H; i += 64) acc = fmaf(p[i], (float)w[i], acc);
         acc = wave_sum(acc);
-        if (lane == 0) g.out[grp][(size_t)b * ldo + c] = acc + g.bc[grp][c];
+        if (lane == 0) g.out[grp][(size_t)ob * ldo + c] = acc + g.bc[grp][c];
+    }
+}
+
+// Row order of a sub-batch (per-sequence routing).  One workgroup: lengths of the chosen sequences, their prefix
+// sums (n_sel <= 1024, four per thread), then for every chosen sequence the batch rows its compact rows copy.
+__global__ __launch_bounds__(256) void route_map_kernel(RouteIdx idx, int n_sel, const int32_t* __restrict__ g_start,
+                                                        const int32_t* __restrict__ g_len, int32_t* __restrict__ c_start,
+                                                        int32_t* __restrict__ c_len, int32_t* __restrict__ c_src,
+                                                        int32_t* __restrict__ c_seq, int32_t* __restrict__ c_n)
+{
+    __shared__ int len_s[kMaxRouted];
+    __shared__ int start_s[kMaxRouted];
+    __shared__ int part[256];
+    const int tid = threadIdx.x;
+    int mine = 0;
+    for (int u = 0; u < 4; ++u) {
+        const int i = tid * 4 + u;
+        const int l = i < n_sel ? g_len[idx.seq[i]] : 0;
+        if (i < kMaxRouted) len_s[i] = l;
+        mine += l;
+    }
+    part[tid] = mine;
+    __syncthreads();
+    if (tid == 0) {                                   // 256 partial sums: a short serial scan
+        int run = 0;
+        for (int t = 0; t < 256; ++t) {
+            const int v = part[t];
+            part[t] = run;
+            run += v;
+        }
+        *c_n = run;
+    }
+    __syncthreads();
+    int run = part[tid];
+    for (int u = 0; u < 4; ++u) {
+        const int i = tid * 4 + u;
+        if (i < n_sel) {
+            start_s[i] = run;
+            c_start[i] = run;
+            c_len[i] = len_s[i];
+            c_seq[i] = idx.seq[i];
+            run += len_s[i];
+        }
+    }
+    __syncthreads();
+    for (int i = 0; i < n_sel; ++i) {
+        const int src0 = g_start[idx.seq[i]], dst0 = start_s[i];
+        for (int j = tid; j < len_s[i]; j += 256) c_src[dst0 + j] = src0 + j;
+    }
+}
+
+__global__ __launch_bounds__(256) void route_gather_kernel(const float* __restrict__ in_f, const void* __restrict__ in_a,
+                                                           float* __restrict__ out_f, void* __restrict__ out_a,
+                                                           const int32_t* __restrict__ c_src, const int32_t* __restrict__ c_n,
+                                                           int max_rows, int H, int act_bytes)
+{
+    const int r = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (r >= min(max_rows, *c_n)) return;
+    const size_t src = (size_t)c_src[r];
+    if (in_f && out_f)
+        for (int i = lane; i < H; i += 64) out_f[(size_t)r * H + i] = in_f[src * H + i];
+    if (in_a && out_a) {
+        const int words = H * act_bytes / 4;
+        const uint32_t* x = reinterpret_cast<const uint32_t*>(static_cast<const unsigned char*>(in_a) + src * H * act_bytes);
+        uint32_t* o = reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(out_a) + (size_t)r * H * act_bytes);
+        for (int i = lane; i < words; i += 64) o[i] = x[i];
     }
 }
 
@@ -403,11 +471,31 @@ hipError_t launch_unpack_rows(const float* x, const int32_t* row_of, int n_pos, 
     return hipGetLastError();
 }
 
-hipError_t launch_classifier(const ClsGroup& g, int G, int B, int H, int maxC, int w_bf16, int64_t ldo, hipStream_t stream)
+hipError_t launch_classifier(const ClsGroup& g, int G, int B, int H, int maxC, int w_bf16, int64_t ldo, const int32_t* out_row,
+                             hipStream_t stream)
 {
     if (G <= 0 || B <= 0 || maxC <= 0) return hipSuccess;
-    if (w_bf16) hipLaunchKernelGGL((classifier_kernel<__bf16>), dim3(B, G), dim3(256), 0, stream, g, B, H, ldo);
-    else hipLaunchKernelGGL((classifier_kernel<float>), dim3(B, G), dim3(256), 0, stream, g, B, H, ldo);
+    if (w_bf16) hipLaunchKernelGGL((classifier_kernel<__bf16>), dim3(B, G), dim3(256), 0, stream, g, B, H, ldo, out_row);
+    else hipLaunchKernelGGL((classifier_kernel<float>), dim3(B, G), dim3(256), 0, stream, g, B, H, ldo, out_row);
+    return hipGetLastError();
+}
+
+hipError_t launch_route_map(const RouteIdx& idx, int n_sel, const int32_t* g_start, const int32_t* g_len, int32_t* c_start,
+                            int32_t* c_len, int32_t* c_src, int32_t* c_seq, int32_t* c_n, hipStream_t stream)
+{
+    if (n_sel <= 0) return hipSuccess;
+    if (n_sel > kMaxRouted || !g_start || !g_len || !c_start || !c_len || !c_src || !c_seq || !c_n) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(route_map_kernel, dim3(1), dim3(256), 0, stream, idx, n_sel, g_start, g_len, c_start, c_len, c_src, c_seq, c_n);
+    return hipGetLastError();
+}
+
+hipError_t launch_route_gather(const float* in_f, const void* in_a, float* out_f, void* out_a, const int32_t* c_src, const int32_t* c_n,
+                               int max_rows, int H, int act_bytes, hipStream_t stream)
+{
+    if (max_rows <= 0) return hipSuccess;
+    if (!c_src || !c_n || (act_bytes != 2 && act_bytes != 4) || (H * act_bytes) % 4 != 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(route_gather_kernel, dim3((max_rows + kRowsPerBlock - 1) / kRowsPerBlock), dim3(256), 0, stream, in_f, in_a, out_f,
+                       out_a, c_src, c_n, max_rows, H, act_bytes);
     return hipGetLastError();
 }
 

@@ -577,3 +577,65 @@ def test_segment_ids_match_oracle():
         else:
             assert np.abs(got - ref).max() <= 2e-2
         model.close()
+
+
+@pytest.mark.parametrize("kind", ["fp32", "bf16"])
+def test_per_sequence_routing_matches_oracle(kind):
+    """Each sequence asks for its own subset of tasks: wanted logits equal the oracle's (sequences are independent,
+    so the oracle's full forward is the reference), everything else is left untouched."""
+    if kind == "fp32":
+        spec, std = MINI, 0.1
+    else:
+        spec, std = SMALL, 0.05
+    tr, tri, tps = _params(spec, True, std)
+    model = _load(spec, tr, tri, tps)
+    ids, mask, _ = ms.make_inputs(spec, batch_index=3)
+    B, T = ids.shape[0], spec.n_tasks
+    rng = np.random.default_rng(11)
+    route = (rng.random((B, T)) < 0.5).astype(np.uint8)
+    route[0, :] = 1                      # one sequence wants everything
+    route[1, :] = 0                      # one wants nothing
+    if T >= 3:
+        route[:, 2] = route[:, 1]        # two tasks with the same sequence set share a group
+    ref = oracle.Oracle(spec, tr, [p for p, _ in tps]).mt_forward(ids, mask)
+    out = torch.full((B, model.n_logits), 9.0, device="cuda")
+    model.forward_routed(dev(ids), dev(mask), route, out)
+    got = out.cpu().numpy()
+    col = 0
+    for t, task in enumerate(spec.tasks):
+        sl = slice(col, col + task.n_classes)
+        for b in range(B):
+            if route[b, t]:
+                if kind == "fp32":
+                    assert np.abs(got[b, sl] - ref[b, sl]).max() <= 1e-4 * max(np.abs(ref[:, sl]).max(), 1e-3), (b, t)
+                else:
+                    assert np.abs(got[b, sl] - ref[b, sl]).max() <= 2e-2, (b, t)
+            else:
+                assert (got[b, sl] == 9.0).all(), (b, t)
+        col += task.n_classes
+    # all-ones routing equals the plain forward up to the rounding differences of a different launch grouping
+    out2 = torch.zeros((B, model.n_logits), device="cuda")
+    model.forward_routed(dev(ids), dev(mask), np.ones((B, T)), out2)
+    plain = model.forward(dev(ids), dev(mask)).cpu().numpy()
+    assert np.abs(out2.cpu().numpy() - plain).max() <= (1e-5 if kind == "fp32" else 5e-3)
+    model.close()
+
+
+def test_per_sequence_routing_at_full_size(base_model):
+    """base workload, every sequence wanting a random half of the 8 tasks: wanted logits agree with the plain
+    forward (same model, other launch grouping: rounding-level differences), the rest is untouched."""
+    spec, model, _, _ = base_model
+    ids, mask, _ = ms.make_inputs(spec, batch_index=4)
+    B, T = ids.shape[0], spec.n_tasks
+    route = (np.random.default_rng(3).random((B, T)) < 0.5).astype(np.uint8)
+    plain = model.forward(dev(ids), dev(mask)).cpu().numpy()
+    out = torch.full((B, model.n_logits), -3.0, device="cuda")
+    model.forward_routed(dev(ids), dev(mask), route, out)
+    got = out.cpu().numpy()
+    col = 0
+    for t, task in enumerate(spec.tasks):
+        sl = slice(col, col + task.n_classes)
+        want = route[:, t] != 0
+        assert np.abs(got[want][:, sl] - plain[want][:, sl]).max() <= 5e-3
+        assert (got[~want][:, sl] == -3.0).all()
+        col += task.n_classes
