@@ -639,3 +639,72 @@ def test_per_sequence_routing_at_full_size(base_model):
         assert np.abs(got[want][:, sl] - plain[want][:, sl]).max() <= 5e-3
         assert (got[~want][:, sl] == -3.0).all()
         col += task.n_classes
+
+
+def _random_spec(rng, bf16):
+    """A small random merged model: random widths, forks anywhere in the trunk (including the embeddings), branches
+    of 0..3 own layers, 1..6 classes, ragged batch and sequence sizes."""
+    if bf16:
+        heads = int(rng.integers(1, 4))
+        hidden = 64 * heads
+        ffn = 64 * int(rng.integers(1, 5))
+    else:
+        heads = int(rng.choice([1, 2, 3, 4]))
+        hidden = heads * int(rng.choice([4, 8, 12, 20]))
+        ffn = int(rng.choice([8, 24, 40, 100]))
+    depth = int(rng.integers(0, 4))
+    n_tasks = int(rng.integers(1, 6))
+    tasks = []
+    for _ in range(n_tasks):
+        tasks.append(ms.TaskSpec(int(rng.integers(0, depth + 1)), int(rng.integers(0, 4)), int(rng.integers(1, 7))))
+    tasks[int(rng.integers(0, n_tasks))] = ms.TaskSpec(depth, int(rng.integers(0, 4)), int(rng.integers(1, 7)))   # someone forks at D
+    seq = int(rng.integers(2, 71))
+    return ms.MTSpec("rand", vocab=int(rng.integers(20, 400)), hidden=hidden, heads=heads, ffn=ffn, max_pos=seq + 3,
+                     n_trunk_layers=depth, tasks=tuple(tasks), precision="bf16" if bf16 else "fp32",
+                     batch=int(rng.integers(1, 8)), seq=seq, len_lo=1, len_hi=seq, input_seed=int(rng.integers(1, 10 ** 6)),
+                     weights_seed=int(rng.integers(1, 10 ** 6)))
+
+
+@pytest.mark.parametrize("seed,bf16", [(s, False) for s in range(10)] + [(100 + s, True) for s in range(8)])
+def test_random_small_models_match_oracle(seed, bf16):
+    rng = np.random.default_rng(seed)
+    spec = _random_spec(rng, bf16)
+    say(f"random model seed={seed}: H={spec.hidden} A={spec.heads} F={spec.ffn} D={spec.n_trunk_layers} "
+        f"tasks={[(t.fork_layer, t.n_layers, t.n_classes) for t in spec.tasks]} B={spec.batch} S={spec.seq}")
+    tr, tri, tps = _params(spec, True, 0.05 if bf16 else 0.1)
+    model = _load(spec, tr, tri, tps)
+    orc = oracle.Oracle(spec, tr, [p for p, _ in tps])
+    ids, mask, lengths = ms.make_inputs(spec)
+    if spec.seq >= 6 and spec.batch >= 2:                   # a hole in one mask (never at position 0)
+        j = 1 + int(rng.integers(0, max(1, int(lengths[1]) - 1)))
+        mask[1, j] = 0
+    ref = orc.mt_forward(ids, mask)
+    got = model.forward(dev(ids), dev(mask)).cpu().numpy()
+    if bf16:
+        assert np.abs(got - ref).max() <= 2e-2
+    else:
+        assert max(rel_err_per_task(spec, got, ref)) <= 1e-4
+    # a task mask and a routing table on the same model
+    tm = [int(rng.integers(0, 2)) for _ in spec.tasks]
+    tm[int(rng.integers(0, spec.n_tasks))] = 1
+    out = torch.full((spec.batch, model.n_logits), 5.0, device="cuda")
+    model.forward(dev(ids), dev(mask), out=out, task_mask=tm)
+    route = (rng.random((spec.batch, spec.n_tasks)) < 0.6).astype(np.uint8)
+    out_r = torch.full((spec.batch, model.n_logits), 5.0, device="cuda")
+    model.forward_routed(dev(ids), dev(mask), route, out_r)
+    o, o_r = out.cpu().numpy(), out_r.cpu().numpy()
+    tol = 2e-2 if bf16 else 1e-4 * max(np.abs(ref).max(), 1e-3)
+    col = 0
+    for t, task in enumerate(spec.tasks):
+        sl = slice(col, col + task.n_classes)
+        if tm[t]:
+            assert np.abs(o[:, sl] - ref[:, sl]).max() <= tol
+        else:
+            assert (o[:, sl] == 5.0).all()
+        for b in range(spec.batch):
+            if route[b, t]:
+                assert np.abs(o_r[b, sl] - ref[b, sl]).max() <= tol
+            else:
+                assert (o_r[b, sl] == 5.0).all()
+        col += task.n_classes
+    model.close()
