@@ -105,7 +105,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="base", help="tiny | base | hetero | latency | large | industrial")
+    ap.add_argument("--config", default="base", help="tiny | base | hetero | latency | large | industrial | wo_kd | mixed")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--in-flight", type=int, default=3,
                     help="batches in flight: forwards are issued round-robin to this many model replicas (shared "

@@ -97,6 +97,15 @@ def _industrial_tasks() -> Tuple[TaskSpec, ...]:
     return tuple(TaskSpec(8, 2 if t % 2 == 0 else 1, c) for t, c in enumerate(classes))
 
 
+def _table_tasks(tuples) -> Tuple[TaskSpec, ...]:
+    return tuple(TaskSpec(x, y, c) for (x, y), c in zip(tuples, _GLUE_CLASSES))
+
+
+# Table 2's task tables (fork x, own layers y) in the order QNLI RTE QQP MNLI SST-2 MRPC CoLA STS-B
+_WO_KD = ((2, 10), (7, 5), (2, 10), (4, 8), (6, 6), (7, 5), (4, 8), (4, 8))        # "Ours (w/o KD)": 7 + 60 layers
+_MIXED = ((2, 3), (7, 5), (2, 1), (4, 3), (6, 2), (7, 3), (4, 8), (4, 1))          # "Ours (mixed)":  7 + 26 layers
+
+
 CONFIGS = {
     "tiny": MTSpec("tiny", vocab=1000, hidden=64, heads=2, ffn=256, max_pos=32, n_trunk_layers=2,
                    tasks=(TaskSpec(2, 1, 2), TaskSpec(2, 1, 3)), precision="fp32",
@@ -117,12 +126,19 @@ CONFIGS = {
     "industrial": MTSpec("industrial", vocab=21128, hidden=768, heads=12, ffn=3072, max_pos=512, n_trunk_layers=8,
                          tasks=_industrial_tasks(), precision="bf16",
                          batch=16, seq=32, len_lo=4, len_hi=32, input_seed=1005),
+    # stress shapes for the schedule: the paper's undistilled and mixed task tables (Table 2), deep uneven branches
+    "wo_kd": MTSpec("wo_kd", vocab=30522, hidden=768, heads=12, ffn=3072, max_pos=512, n_trunk_layers=7,
+                    tasks=_table_tasks(_WO_KD), precision="bf16",
+                    batch=32, seq=128, len_lo=16, len_hi=128, input_seed=1006),
+    "mixed": MTSpec("mixed", vocab=30522, hidden=768, heads=12, ffn=3072, max_pos=512, n_trunk_layers=7,
+                    tasks=_table_tasks(_MIXED), precision="bf16",
+                    batch=32, seq=128, len_lo=16, len_hi=128, input_seed=1007),
 }
-_ORDER = ["tiny", "base", "hetero", "latency", "large", "industrial"]
+_ORDER = ["tiny", "base", "hetero", "latency", "large", "industrial", "wo_kd", "mixed"]
 
 
 def get_config(key) -> MTSpec:
-    """Look a workload up by name or by index 0..5 (tiny, base, hetero, latency, large, industrial)."""
+    """Look a workload up by name or by index 0..7 (tiny, base, hetero, latency, large, industrial, wo_kd, mixed)."""
     if isinstance(key, int):
         key = _ORDER[key]
     return CONFIGS[key]

@@ -168,6 +168,18 @@ def test_wavefront_schedule_step_counts():
     L.mt_destroy(h)
 
 
+def test_paper_task_tables_as_workloads():
+    """Table 2: the undistilled table needs 7 + 60 = 67 layers, the mixed one 7 + 26 = 33; in the wavefront schedule
+    the deepest chain decides the step count (fork 2 + 10 own layers, fork 4 + 8 own layers = 12)."""
+    L = mt.lib()
+    for name, total, steps in (("wo_kd", 67, 12), ("mixed", 33, 12)):
+        rc, h, _ = _create(ms.get_config(name))
+        assert rc == mt.MT_OK
+        assert L.mt_layer_count(h) == total
+        assert L.mt_schedule_steps(h, None) == steps
+        L.mt_destroy(h)
+
+
 def test_share_weights_checks():
     """A replica must match the owner's configuration, share its weight arena, bring a workspace of its own,
     and the owner must have something loaded."""

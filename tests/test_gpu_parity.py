@@ -398,7 +398,8 @@ def test_bf16_mode_masks_with_holes_and_extreme_lengths():
 
 
 @pytest.mark.parametrize("name,batch,rows", [("hetero", 64, [0, 33]), ("latency", 8, list(range(8))), ("latency", 1, [0]),
-                                             ("large", 128, [0, 77]), ("industrial", 16, [0, 5, 11])])
+                                             ("large", 128, [0, 77]), ("industrial", 16, [0, 5, 11]),
+                                             ("wo_kd", 8, [0, 5]), ("mixed", 8, [1, 6])])
 def test_bf16_other_workloads_sampled(name, batch, rows):
     """Forks at different trunk layers (a trunk tap per fork, branch stages of shrinking groups) and the
     small-batch serving shape, in the launch configuration the benchmark uses."""
