@@ -9,6 +9,7 @@ Parameter order (every linear is W[out][in] row-major, y = W x + b):
   trunk scope : word_emb[V,H] pos_emb[P,H] type_emb[2,H] emb_ln_g[H] emb_ln_b[H], then per layer
                 Wq[H,H] bq[H] Wk bk Wv bv Wo[H,H] bo ln1_g ln1_b W1[F,H] b1[F] W2[H,F] b2[H] ln2_g ln2_b
   task scope  : n_layers layers in the same order, then Wp[H,H] bp[H] Wc[C,H] bc[C]
+                (a token-level task has no pooler: its layers are followed by Wc[C,H] bc[C] only)
 """
 from __future__ import annotations
 
@@ -21,6 +22,7 @@ class TaskSpec:
     fork_layer: int   # x_t: number of shared frozen layers this task reads through
     n_layers: int     # y_t: task-specific layers
     n_classes: int    # C_t (1 = regression)
+    token_level: bool = False   # True: one label per token (tagging, slot filling), a linear head on every position
 
 
 @dataclass(frozen=True)
@@ -50,7 +52,18 @@ class MTSpec:
 
     @property
     def n_logits(self) -> int:
-        return sum(t.n_classes for t in self.tasks)
+        """Width of the per-sequence logit row: the sequence-level tasks' classes side by side."""
+        return sum(t.n_classes for t in self.tasks if not t.token_level)
+
+    @property
+    def n_token_logits(self) -> int:
+        """Width of the per-token logit row: the token-level tasks' classes side by side."""
+        return sum(t.n_classes for t in self.tasks if t.token_level)
+
+    def logit_offset(self, t: int) -> int:
+        """First column of task t inside the row of its own kind (per-sequence or per-token)."""
+        kind = self.tasks[t].token_level
+        return sum(u.n_classes for u in self.tasks[:t] if u.token_level == kind)
 
 
 def layer_tensors(h: int, f: int) -> List[Tuple[str, Tuple[int, ...]]]:
@@ -74,7 +87,9 @@ def task_tensors(spec: MTSpec, t: int) -> List[Tuple[str, Tuple[int, ...]]]:
     out = []
     for l in range(task.n_layers):
         out += [(f"L{l}.{n}", s) for n, s in layer_tensors(h, spec.ffn)]
-    out += [("Wp", (h, h)), ("bp", (h,)), ("Wc", (task.n_classes, h)), ("bc", (task.n_classes,))]
+    if not task.token_level:
+        out += [("Wp", (h, h)), ("bp", (h,))]
+    out += [("Wc", (task.n_classes, h)), ("bc", (task.n_classes,))]
     return out
 
 
@@ -95,6 +110,14 @@ def _industrial_tasks() -> Tuple[TaskSpec, ...]:
     # distilled layers, 10 keep one.  Class counts are stand-ins for intent / domain / emotion style label sets.
     classes = (2, 3, 5, 8, 12, 2, 4, 30, 2, 6, 3, 2, 16, 4, 2, 9, 3, 2, 50, 7, 2)
     return tuple(TaskSpec(8, 2 if t % 2 == 0 else 1, c) for t, c in enumerate(classes))
+
+
+def _assistant_tasks() -> Tuple[TaskSpec, ...]:
+    # Appendix E names tagging-style tasks (named entities, slot filling) next to the classifiers: the same
+    # 21-task table with three of the tasks labelling every token instead of the sequence.
+    token = {7: 30, 12: 16, 15: 9}       # slot labels, entity labels (BIO over 4 types), a small tag set
+    return tuple(TaskSpec(t.fork_layer, t.n_layers, t.n_classes, token_level=(i in token))
+                 for i, t in enumerate(_industrial_tasks()))
 
 
 def _table_tasks(tuples) -> Tuple[TaskSpec, ...]:
@@ -126,6 +149,9 @@ CONFIGS = {
     "industrial": MTSpec("industrial", vocab=21128, hidden=768, heads=12, ffn=3072, max_pos=512, n_trunk_layers=8,
                          tasks=_industrial_tasks(), precision="bf16",
                          batch=16, seq=32, len_lo=4, len_hi=32, input_seed=1005),
+    "assistant": MTSpec("assistant", vocab=21128, hidden=768, heads=12, ffn=3072, max_pos=512, n_trunk_layers=8,
+                        tasks=_assistant_tasks(), precision="bf16",
+                        batch=16, seq=32, len_lo=4, len_hi=32, input_seed=1008),
     # stress shapes for the schedule: the paper's undistilled and mixed task tables (Table 2), deep uneven branches
     "wo_kd": MTSpec("wo_kd", vocab=30522, hidden=768, heads=12, ffn=3072, max_pos=512, n_trunk_layers=7,
                     tasks=_table_tasks(_WO_KD), precision="bf16",
@@ -134,11 +160,11 @@ CONFIGS = {
                     tasks=_table_tasks(_MIXED), precision="bf16",
                     batch=32, seq=128, len_lo=16, len_hi=128, input_seed=1007),
 }
-_ORDER = ["tiny", "base", "hetero", "latency", "large", "industrial", "wo_kd", "mixed"]
+_ORDER = ["tiny", "base", "hetero", "latency", "large", "industrial", "wo_kd", "mixed", "assistant"]
 
 
 def get_config(key) -> MTSpec:
-    """Look a workload up by name or by index 0..7 (tiny, base, hetero, latency, large, industrial, wo_kd, mixed)."""
+    """Look a workload up by name or by index 0..8 (tiny, base, hetero, latency, large, industrial, wo_kd, mixed, assistant)."""
     if isinstance(key, int):
         key = _ORDER[key]
     return CONFIGS[key]

@@ -17,7 +17,7 @@ class _Cfg(C.Structure):
 
 
 class _Task(C.Structure):
-    _fields_ = [("fork_layer", C.c_int32), ("n_layers", C.c_int32), ("n_classes", C.c_int32)]
+    _fields_ = [("fork_layer", C.c_int32), ("n_layers", C.c_int32), ("n_classes", C.c_int32), ("token_level", C.c_int32)]
 
 
 def _fp(a):
@@ -42,6 +42,7 @@ def lib():
         L.orc_mt_forward.restype = C.c_int
         L.orc_st_forward.restype = C.c_int
         L.orc_mt_forward_typed.restype = C.c_int
+        L.orc_mt_forward_tokens.restype = C.c_int
         L.orc_st_forward_typed.restype = C.c_int
         _lib = L
     return _lib
@@ -71,7 +72,7 @@ def layer_param_count(h: int, f: int) -> int:
 
 def overhead(tasks) -> int:
     """tasks: iterable of (fork_layer x, n_layers y[, n_classes])."""
-    arr = (_Task * len(tasks))(*[_Task(int(t[0]), int(t[1]), int(t[2]) if len(t) > 2 else 1) for t in tasks])
+    arr = (_Task * len(tasks))(*[_Task(int(t[0]), int(t[1]), int(t[2]) if len(t) > 2 else 1, 0) for t in tasks])
     return int(lib().orc_overhead(arr, C.c_int(len(tasks))))
 
 
@@ -142,7 +143,8 @@ class Oracle:
     def __init__(self, spec, trunk_params, task_params):
         self.spec = spec
         self.cfg = _cfg_of(spec)
-        self.tasks = (_Task * len(spec.tasks))(*[_Task(t.fork_layer, t.n_layers, t.n_classes) for t in spec.tasks])
+        self.tasks = (_Task * len(spec.tasks))(*[_Task(t.fork_layer, t.n_layers, t.n_classes, int(getattr(t, "token_level", False)))
+                                               for t in spec.tasks])
         self.trunk = _f32(trunk_params)
         self.task_params = [_f32(p) for p in task_params]
         L = lib()
@@ -150,27 +152,34 @@ class Oracle:
         for t, p in enumerate(self.task_params):
             assert p.size == L.orc_task_param_count(C.byref(self.cfg), C.byref(self.tasks[t])), f"task {t} parameter count"
 
-    def mt_forward(self, ids, mask, want_hidden=False, type_ids=None):
-        """type_ids: optional [B,S] segment ids in [0, type_vocab); None = segment 0 everywhere."""
+    def mt_forward(self, ids, mask, want_hidden=False, type_ids=None, want_tokens=False):
+        """type_ids: optional [B,S] segment ids in [0, type_vocab); None = segment 0 everywhere.
+        want_tokens: also return the token-level tasks' logits [B,S,n_token_logits] (after the per-sequence ones)."""
         ids, mask = _i32(ids), _i32(mask)
         tt = _i32(type_ids) if type_ids is not None else None
         b, s = ids.shape
         sp = self.spec
         logits = np.empty((b, sp.n_logits), dtype=np.float32)
+        n_tok = sum(t.n_classes for t in sp.tasks if getattr(t, "token_level", False))
+        tok = np.empty((b, s, n_tok), dtype=np.float32)
         hidden = np.empty((sp.n_trunk_layers + 1, b, s, sp.hidden), dtype=np.float32) if want_hidden else None
         ptrs = (C.POINTER(C.c_float) * len(self.task_params))(*[_fp(p) for p in self.task_params])
-        rc = lib().orc_mt_forward_typed(C.byref(self.cfg), self.tasks, _fp(self.trunk), ptrs, _ip(ids),
-                                        _ip(tt) if tt is not None else None, _ip(mask),
-                                        C.c_int64(b), C.c_int64(s), _fp(logits), _fp(hidden))
+        rc = lib().orc_mt_forward_tokens(C.byref(self.cfg), self.tasks, _fp(self.trunk), ptrs, _ip(ids),
+                                         _ip(tt) if tt is not None else None, _ip(mask),
+                                         C.c_int64(b), C.c_int64(s), _fp(logits) if logits.size else None,
+                                         _fp(tok) if n_tok else None, _fp(hidden))
         if rc != 0:
             raise ValueError("invalid task table")
-        return (logits, hidden) if want_hidden else logits
+        res = (logits,) + ((tok,) if want_tokens else ()) + ((hidden,) if want_hidden else ())
+        return res if len(res) > 1 else logits
 
     def st_forward(self, t, ids, mask, type_ids=None):
         ids, mask = _i32(ids), _i32(mask)
         tt = _i32(type_ids) if type_ids is not None else None
         b, s = ids.shape
-        logits = np.empty((b, self.spec.tasks[t].n_classes), dtype=np.float32)
+        task = self.spec.tasks[t]
+        shape = (b, s, task.n_classes) if getattr(task, "token_level", False) else (b, task.n_classes)
+        logits = np.empty(shape, dtype=np.float32)
         rc = lib().orc_st_forward_typed(C.byref(self.cfg), C.byref(self.tasks[t]), _fp(self.trunk), _fp(self.task_params[t]),
                                         _ip(ids), _ip(tt) if tt is not None else None, _ip(mask), C.c_int64(b), C.c_int64(s),
                                         _fp(logits))

@@ -73,8 +73,10 @@ def _layer(P, pre, X, mask, heads, eps, tanh_form):
     return out
 
 
-def student_logits(trunk, task, ids, mask, *, fork_layer, n_layers, heads, eps=1e-12, tanh_form=False, type_ids=None):
-    """Logits of one student for ONE sequence.  trunk/task: dicts from unpack(); ids, mask: length-S lists."""
+def student_logits(trunk, task, ids, mask, *, fork_layer, n_layers, heads, eps=1e-12, tanh_form=False, type_ids=None,
+                   token_level=False):
+    """Logits of one student for ONE sequence.  trunk/task: dicts from unpack(); ids, mask: length-S lists.
+    token_level: the student labels every token: a list of S rows of C logits, no pooler."""
     S = len(ids)
     word, pos, typ = trunk["word_emb"], trunk["pos_emb"], trunk["type_emb"]
     H = word.shape[1]
@@ -87,5 +89,7 @@ def student_logits(trunk, task, ids, mask, *, fork_layer, n_layers, heads, eps=1
         X = _layer(trunk, f"L{l}.", X, mask, heads, eps, tanh_form)
     for l in range(n_layers):
         X = _layer(task, f"L{l}.", X, mask, heads, eps, tanh_form)
+    if token_level:
+        return [_affine(task["Wc"].tolist(), task["bc"].tolist(), X[s]) for s in range(S)]
     pooled = [math.tanh(v) for v in _affine(task["Wp"].tolist(), task["bp"].tolist(), X[0])]
     return _affine(task["Wc"].tolist(), task["bc"].tolist(), pooled)

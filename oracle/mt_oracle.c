@@ -49,6 +49,7 @@ typedef struct {
     int32_t fork_layer;  /* x_t */
     int32_t n_layers;    /* y_t */
     int32_t n_classes;   /* C_t */
+    int32_t token_level; /* 0: pooler + head on the first token; 1: a linear head on every token, no pooler */
 } orc_task;
 
 #ifdef _OPENMP
@@ -190,7 +191,8 @@ int64_t orc_trunk_param_count(const orc_config *c)
 int64_t orc_task_param_count(const orc_config *c, const orc_task *t)
 {
     int64_t H = c->hidden;
-    return (int64_t)t->n_layers * orc_layer_param_count(H, c->ffn) + H * H + H + (int64_t)t->n_classes * H + t->n_classes;
+    return (int64_t)t->n_layers * orc_layer_param_count(H, c->ffn) + (t->token_level ? 0 : H * H + H)
+         + (int64_t)t->n_classes * H + t->n_classes;
 }
 
 typedef struct {
@@ -291,6 +293,24 @@ void orc_head(const orc_config *c, const float *hp, int n_classes, const float *
     free(first); free(pool); free(lg);
 }
 
+/*
+ * Token-level head (tagging tasks such as entity recognition and slot filling, which Appendix E lists among the
+ * deployed tasks): every position's final hidden state goes through one linear layer, as in BERT's token
+ * classification set-up; there is no pooler.  logits[(b*S+s)*ld + j] = Wc[j] . Z[b][s] + bc[j], for every
+ * position, padded ones included.  hp points at Wc.
+ */
+void orc_token_head(const orc_config *c, const float *hp, int n_classes, const float *Z, int64_t B, int64_t S,
+                    float *logits, int64_t ld_logits)
+{
+    const int64_t H = c->hidden, M = B * S;
+    const float *Wc = hp, *bc = Wc + (int64_t)n_classes * H;
+    float *lg = (float *)malloc(sizeof(float) * (size_t)(M * n_classes));
+    orc_linear(Z, M, H, Wc, bc, n_classes, lg);
+    for (int64_t r = 0; r < M; ++r)
+        for (int j = 0; j < n_classes; ++j) logits[r * ld_logits + j] = lg[r * n_classes + j];
+    free(lg);
+}
+
 /* Total transformer layers evaluated per request: max_t x_t + sum_t y_t (Section 4.1). */
 int orc_overhead(const orc_task *tasks, int n_tasks)
 {
@@ -303,13 +323,15 @@ int orc_overhead(const orc_task *tasks, int n_tasks)
 }
 
 /*
- * Merged model.  logits: [B][sum_t C_t], task t's columns start at sum_{u<t} C_u.
+ * Merged model.  logits: [B][sum of C_t over sequence-level tasks]; token_logits: [B][S][sum of C_t over token-level
+ * tasks] (may be NULL when there is no such task).  Inside its row a task's columns start at the sum of C_u over
+ * the earlier tasks u of the same kind.
  * hidden_out (optional): [n_trunk_layers+1][B][S][H], the embeddings followed by every trunk layer output.
- * Returns 0, or -1 on an invalid task table.
+ * Returns 0, or -1 on an invalid task table or a missing output buffer.
  */
-int orc_mt_forward_typed(const orc_config *c, const orc_task *tasks, const float *trunk, const float *const *task_params,
-                         const int32_t *ids, const int32_t *type_ids, const int32_t *mask, int64_t B, int64_t S, float *logits,
-                         float *hidden_out);
+int orc_mt_forward_tokens(const orc_config *c, const orc_task *tasks, const float *trunk, const float *const *task_params,
+                          const int32_t *ids, const int32_t *type_ids, const int32_t *mask, int64_t B, int64_t S, float *logits,
+                          float *token_logits, float *hidden_out);
 
 int orc_mt_forward(const orc_config *c, const orc_task *tasks, const float *trunk, const float *const *task_params,
                    const int32_t *ids, const int32_t *mask, int64_t B, int64_t S, float *logits, float *hidden_out)
@@ -322,13 +344,22 @@ int orc_mt_forward_typed(const orc_config *c, const orc_task *tasks, const float
                          const int32_t *ids, const int32_t *type_ids, const int32_t *mask, int64_t B, int64_t S, float *logits,
                          float *hidden_out)
 {
+    return orc_mt_forward_tokens(c, tasks, trunk, task_params, ids, type_ids, mask, B, S, logits, NULL, hidden_out);
+}
+
+int orc_mt_forward_tokens(const orc_config *c, const orc_task *tasks, const float *trunk, const float *const *task_params,
+                          const int32_t *ids, const int32_t *type_ids, const int32_t *mask, int64_t B, int64_t S, float *logits,
+                          float *token_logits, float *hidden_out)
+{
     const int64_t H = c->hidden, F = c->ffn, MH = B * S * H;
     const int D = c->n_trunk_layers;
-    int ctot = 0;
+    int ctot = 0, ctok = 0;
     for (int t = 0; t < c->n_tasks; ++t) {
         if (tasks[t].fork_layer < 0 || tasks[t].fork_layer > D || tasks[t].n_layers < 0 || tasks[t].n_classes < 1) return -1;
-        ctot += tasks[t].n_classes;
+        if (tasks[t].token_level) ctok += tasks[t].n_classes;
+        else ctot += tasks[t].n_classes;
     }
+    if ((ctot > 0 && !logits) || (ctok > 0 && !token_logits)) return -1;
     const float *layers = trunk + ((int64_t)c->vocab + c->max_pos + c->type_vocab) * H + 2 * H;
     const int64_t lsz = orc_layer_param_count(H, F);
 
@@ -340,7 +371,7 @@ int orc_mt_forward_typed(const orc_config *c, const orc_task *tasks, const float
 
     float *za = (float *)malloc(sizeof(float) * (size_t)MH);
     float *zb = (float *)malloc(sizeof(float) * (size_t)MH);
-    int col = 0;
+    int col = 0, tcol = 0;
     for (int t = 0; t < c->n_tasks; ++t) {
         const float *z = taps + (int64_t)tasks[t].fork_layer * MH;
         for (int l = 0; l < tasks[t].n_layers; ++l) {
@@ -348,14 +379,20 @@ int orc_mt_forward_typed(const orc_config *c, const orc_task *tasks, const float
             orc_encoder_layer(c, task_params[t] + l * lsz, z, mask, B, S, dst);
             z = dst;
         }
-        orc_head(c, task_params[t] + (int64_t)tasks[t].n_layers * lsz, tasks[t].n_classes, z, B, S, logits + col, ctot);
-        col += tasks[t].n_classes;
+        const float *hp = task_params[t] + (int64_t)tasks[t].n_layers * lsz;
+        if (tasks[t].token_level) {
+            orc_token_head(c, hp, tasks[t].n_classes, z, B, S, token_logits + tcol, ctok);
+            tcol += tasks[t].n_classes;
+        } else {
+            orc_head(c, hp, tasks[t].n_classes, z, B, S, logits + col, ctot);
+            col += tasks[t].n_classes;
+        }
     }
     free(za); free(zb); free(taps);
     return 0;
 }
 
-/* Student model of one task on its own.  logits: [B][C_t]. */
+/* Student model of one task on its own.  logits: [B][C_t], or [B][S][C_t] for a token-level task. */
 int orc_st_forward_typed(const orc_config *c, const orc_task *task, const float *trunk, const float *task_param,
                          const int32_t *ids, const int32_t *type_ids, const int32_t *mask, int64_t B, int64_t S, float *logits);
 
@@ -384,7 +421,10 @@ int orc_st_forward_typed(const orc_config *c, const orc_task *task, const float 
         orc_encoder_layer(c, task_param + l * lsz, cur, mask, B, S, nxt);
         float *tmp = cur; cur = nxt; nxt = tmp;
     }
-    orc_head(c, task_param + (int64_t)task->n_layers * lsz, task->n_classes, cur, B, S, logits, task->n_classes);
+    if (task->token_level)
+        orc_token_head(c, task_param + (int64_t)task->n_layers * lsz, task->n_classes, cur, B, S, logits, task->n_classes);
+    else
+        orc_head(c, task_param + (int64_t)task->n_layers * lsz, task->n_classes, cur, B, S, logits, task->n_classes);
     free(xa); free(xb);
     return 0;
 }

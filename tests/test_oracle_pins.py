@@ -265,6 +265,89 @@ def test_segment_ids_relabelling_invariance():
     np.testing.assert_array_equal(oracle.Oracle(spec, tr2, tp).mt_forward(ids, mask, type_ids=1 - tt), lg)
 
 
+# ------------------------------------------------------------------ token-level heads (tagging / slot-filling tasks, Appendix E)
+
+TOK = ms.MTSpec("tok", vocab=50, hidden=32, heads=4, ffn=64, max_pos=24, n_trunk_layers=2,
+                tasks=(ms.TaskSpec(1, 1, 2), ms.TaskSpec(2, 1, 5, token_level=True), ms.TaskSpec(2, 0, 3),
+                       ms.TaskSpec(0, 2, 4, token_level=True), ms.TaskSpec(1, 0, 32, token_level=True)),
+                precision="fp32", batch=3, seq=10, len_lo=2, len_hi=10, input_seed=78, weights_seed=4243)
+
+
+def test_token_head_layout_and_brute_force():
+    spec = TOK
+    assert spec.n_logits == 5 and spec.n_token_logits == 41
+    assert [spec.logit_offset(t) for t in range(5)] == [0, 0, 2, 5, 9]
+    tr, tri, tp, tpi = build(spec, stress=True, std=0.1)
+    assert tp[1].size == oracle.layer_param_count(32, 64) + 5 * 32 + 5          # no pooler in a token-level scope
+    ids, mask, _ = ms.make_inputs(spec)
+    orc = oracle.Oracle(spec, tr, tp)
+    lg, tok = orc.mt_forward(ids, mask, want_tokens=True)
+    assert lg.shape == (3, 5) and tok.shape == (3, 10, 41)
+    T = brute_tiny.unpack(tr, tri)
+    for t, task in enumerate(spec.tasks):
+        K = brute_tiny.unpack(tp[t], tpi[t])
+        c0 = spec.logit_offset(t)
+        for b in range(ids.shape[0]):
+            ref = np.array(brute_tiny.student_logits(T, K, ids[b].tolist(), mask[b].tolist(), fork_layer=task.fork_layer,
+                                                     n_layers=task.n_layers, heads=spec.heads, eps=spec.ln_eps,
+                                                     token_level=task.token_level))
+            got = tok[b, :, c0:c0 + task.n_classes] if task.token_level else lg[b, c0:c0 + task.n_classes]
+            assert got.shape == ref.shape and np.abs(got - ref).max() <= 5e-6
+        # the merged model's columns are the student's own outputs
+        alone = orc.st_forward(t, ids, mask)
+        np.testing.assert_array_equal(alone, tok[:, :, c0:c0 + task.n_classes] if task.token_level else lg[:, c0:c0 + task.n_classes])
+
+
+def test_token_head_with_unit_rows_reads_the_hidden_state():
+    """A token-level task without own layers whose head is [I | 0] with zero bias returns the trunk's hidden state at
+    its fork, position by position: the head is a plain per-token linear map and nothing else."""
+    spec = TOK
+    tr, tri, tp, tpi = build(spec, stress=True, std=0.1)
+    H = spec.hidden
+    off = {n: o for n, _, o in tpi[4]}
+    tp[4][off["Wc"]:off["Wc"] + 32 * H] = np.eye(32, H, dtype=np.float32).ravel()
+    tp[4][off["bc"]:off["bc"] + 32] = 0.0
+    ids, mask, _ = ms.make_inputs(spec)
+    lg, tok, hidden = oracle.Oracle(spec, tr, tp).mt_forward(ids, mask, want_tokens=True, want_hidden=True)
+    np.testing.assert_array_equal(tok[:, :, 9:41], hidden[1][:, :, :32])
+    # ... and a bias shifts every position by the same vector
+    tp[4][off["bc"]:off["bc"] + 32] = np.arange(32, dtype=np.float32)
+    _, tok2 = oracle.Oracle(spec, tr, tp).mt_forward(ids, mask, want_tokens=True)
+    np.testing.assert_allclose(tok2[:, :, 9:41] - tok[:, :, 9:41], np.broadcast_to(np.arange(32, dtype=np.float32), (3, 10, 32)),
+                               rtol=0, atol=1e-5)
+
+
+def test_token_logits_ignore_padding_and_other_sequences():
+    spec = TOK
+    tr, _, tp, _ = build(spec, stress=True, std=0.1)
+    ids, mask, lens = ms.make_inputs(spec)
+    orc = oracle.Oracle(spec, tr, tp)
+    _, tok = orc.mt_forward(ids, mask, want_tokens=True)
+    ids2 = ids.copy()
+    ids2[mask == 0] = (ids2[mask == 0] + 7) % spec.vocab              # other tokens under the padding
+    _, tok2 = orc.mt_forward(ids2, mask, want_tokens=True)
+    assert int((mask == 0).sum()) > 0
+    np.testing.assert_allclose(tok2[mask == 1], tok[mask == 1], rtol=0, atol=1e-6)
+    for b in range(ids.shape[0]):                                      # each sequence on its own, cut to its length
+        n = int(lens[b])
+        _, one = orc.mt_forward(ids[b:b + 1, :n], mask[b:b + 1, :n], want_tokens=True)
+        np.testing.assert_allclose(one[0], tok[b, :n], rtol=0, atol=2e-6)
+
+
+def test_token_tasks_need_their_output_buffer():
+    spec = TOK
+    tr, _, tp, _ = build(spec)
+    ids, mask, _ = ms.make_inputs(spec)
+    orc = oracle.Oracle(spec, tr, tp)
+    import ctypes as C
+    from oracle import binding as ob
+    lg = np.empty((3, 5), dtype=np.float32)
+    ptrs = (C.POINTER(C.c_float) * 5)(*[ob._fp(p) for p in orc.task_params])
+    rc = ob.lib().orc_mt_forward_typed(C.byref(orc.cfg), orc.tasks, ob._fp(orc.trunk), ptrs, ob._ip(ids), None, ob._ip(mask),
+                                       C.c_int64(3), C.c_int64(10), ob._fp(lg), None)
+    assert rc == -1
+
+
 # ------------------------------------------------------------------ P2 / P3: merging is exact, tasks are isolated
 
 @pytest.mark.parametrize("spec", [ms.get_config("tiny"), MINI])
