@@ -28,7 +28,7 @@
 extern "C" {
 #endif
 
-#define MT_ABI_VERSION 1u
+#define MT_ABI_VERSION 2u
 
 enum {
     MT_OK = 0,
@@ -42,6 +42,7 @@ enum {
 
 enum { MT_BF16 = 0, MT_FP32_CHECK = 1 };     /* mt_config.precision */
 enum { MT_GELU_ERF = 0, MT_GELU_TANH = 1 };  /* mt_config.gelu */
+enum { MT_HEAD_SEQUENCE = 0, MT_HEAD_TOKEN = 1 };  /* mt_task_desc.head */
 
 typedef struct mt_model mt_model; /* opaque, library-owned host object */
 
@@ -51,11 +52,17 @@ typedef struct mt_model mt_model; /* opaque, library-owned host object */
  *               (0 = directly after the embeddings); 0 <= x_t <= n_trunk_layers.
  *   n_layers    y_t >= 0 task-specific encoder layers.
  *   n_classes   C_t >= 1 logits (1 = regression output, returned unchanged).
+ *   head        MT_HEAD_SEQUENCE: tanh pooler on the first token, then a linear classifier: one row of C_t
+ *               logits per sequence (the GLUE-style tasks of Section 4).
+ *               MT_HEAD_TOKEN: one linear classifier applied to every token's final hidden state, no pooler:
+ *               C_t logits per position (the tagging tasks - entity recognition, slot filling - that
+ *               Appendix E lists among the deployed tasks).
  */
 typedef struct {
     int32_t fork_layer;
     int32_t n_layers;
     int32_t n_classes;
+    int32_t head;
 } mt_task_desc;
 
 /*
@@ -114,6 +121,7 @@ int mt_share_weights(mt_model* m, const mt_model* owner);
  *   trunk scope: word_emb[V,H] pos_emb[P,H] type_emb[TV,H] emb_ln_g[H] emb_ln_b[H], then per layer
  *     Wq[H,H] bq[H] Wk bk Wv bv Wo[H,H] bo ln1_g ln1_b W1[F,H] b1[F] W2[H,F] b2[H] ln2_g ln2_b
  *   task scope : y_t layers in that order, then Wp[H,H] bp[H] Wc[C,H] bc[C]
+ *                (MT_HEAD_TOKEN: y_t layers, then Wc[C,H] bc[C] only)
  * The call converts on the host, copies on `hip_stream` and waits for the copy, so h_blob may be
  * released on return.  Errors: NULL, STATE (not bound), BLOB (magic/scope/size mismatch), HIP.
  */
@@ -128,10 +136,11 @@ int mt_load_weights(mt_model* m, int32_t scope, const void* h_blob, size_t nbyte
  *   h_task_mask host array [n_tasks] of 0/1, or NULL for all tasks.  Disabled tasks are not computed
  *               and their logit columns are left untouched; the trunk runs only as deep as the
  *               deepest enabled fork;
- *   d_out_logits [batch][C_tot] float32 row-major, C_tot = sum of n_classes, task t's columns start
- *               at mt_logit_offset(m, t).  Raw logits (no softmax).
+ *   d_out_logits [batch][C_tot] float32 row-major, C_tot = sum of n_classes over the MT_HEAD_SEQUENCE tasks,
+ *               task t's columns start at mt_logit_offset(m, t).  Raw logits (no softmax).
  * Hidden states at padded positions are unspecified and never influence a real token.
- * Errors: NULL, STATE (not bound / a needed scope not loaded), SHAPE (batch, seq out of range), HIP.
+ * Errors: NULL (also: an enabled task has a token-level head, which needs mt_forward_tokens), STATE (not
+ * bound / a needed scope not loaded), SHAPE (batch, seq out of range), HIP.
  */
 int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_mask, int32_t batch, int32_t seq,
                const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream);
@@ -146,20 +155,39 @@ int mt_forward_typed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_t
                const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream);
 
 /*
+ * The forward pass of a model that has token-level tasks (MT_HEAD_TOKEN).  As mt_forward_typed, plus
+ *   d_out_token_logits [batch][seq][C_tok] float32, C_tok = sum of n_classes over the MT_HEAD_TOKEN tasks, task t's
+ *               columns start at mt_token_logit_offset(m, t).  Columns of enabled token-level tasks are written at
+ *               every position: the logits where d_attn_mask is 1, zeros where it is 0; columns of disabled
+ *               tasks are left untouched.
+ * d_out_logits may be NULL when no enabled task has a sequence head, d_out_token_logits when none has a token
+ * head.  A token-level task's last layer is evaluated for all tokens, a sequence-level task's for the first only.
+ * Errors as mt_forward.
+ */
+int mt_forward_tokens(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask,
+                      int32_t batch, int32_t seq, const uint8_t* h_task_mask, float* d_out_logits, float* d_out_token_logits,
+                      void* hip_stream);
+
+/*
  * Per-sequence task routing (Section 5.2 discusses that every task is computed for every request; a serving
  * system that knows which tasks a request needs can skip the rest): h_route is a host array [batch][n_tasks],
  * nonzero = sequence b wants task t.  The trunk runs once for the whole batch, as deep as the deepest wanted
  * fork; tasks wanted by the same set of sequences form a group whose sequences are gathered into a row order of
  * their own, on which the group's branch layers, poolers and classifiers run.  Logits of wanted (b, t) pairs are
  * written to d_out_logits[b][mt_logit_offset(t)..]; all other entries are left untouched.  batch <= 1024.
- * d_token_type_ids may be NULL.  Errors as mt_forward.  After this call mt_read_hidden serves trunk taps only.
+ * d_token_type_ids may be NULL.  Errors as mt_forward, and CONFIG when a wanted task has a token-level head (not
+ * routed).  After this call mt_read_hidden serves trunk taps only.
  */
 int mt_forward_routed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask,
                       int32_t batch, int32_t seq, const uint8_t* h_route, float* d_out_logits, void* hip_stream);
 
-/* Column of task t's first logit, or MT_ERR_SHAPE.  mt_n_logits = C_tot. */
+/* Column of task t's first logit inside the row of its kind (the per-sequence row for MT_HEAD_SEQUENCE, the
+ * per-token row for MT_HEAD_TOKEN), or MT_ERR_SHAPE (task out of range) / MT_ERR_CONFIG (task is of the other
+ * kind).  mt_n_logits = C_tot, mt_n_token_logits = C_tok. */
 int mt_logit_offset(const mt_model* m, int32_t task);
 int mt_n_logits(const mt_model* m);
+int mt_token_logit_offset(const mt_model* m, int32_t task);
+int mt_n_token_logits(const mt_model* m);
 
 /* The paper's cost measure (Section 4.1, "Overhead" of Table 2): the number of transformer layers
  * evaluated per request, n_trunk_layers + sum_t n_layers. */
@@ -180,7 +208,8 @@ const char* mt_error_name(int code);
  *   task < 0 : the trunk after `layer` shared layers (only layers some task forks at are kept);
  *   task >= 0: task's branch output after its last own layer, of which only the first token of every
  *              sequence is computed (the pooler reads nothing else): position 0 holds it, the rest is 0;
- *              for a task without own layers this is its trunk tap (`layer` ignored)
+ *              for a task without own layers this is its trunk tap (`layer` ignored); for a token-level task
+ *              the whole state (padded positions 0)
  * into d_out on `hip_stream`.  For validation.  Errors: NULL, STATE, SHAPE.
  */
 int mt_read_hidden(mt_model* m, int32_t task, int32_t layer, float* d_out, size_t out_bytes, void* hip_stream);

@@ -333,6 +333,10 @@ int orc_mt_forward_tokens(const orc_config *c, const orc_task *tasks, const floa
                           const int32_t *ids, const int32_t *type_ids, const int32_t *mask, int64_t B, int64_t S, float *logits,
                           float *token_logits, float *hidden_out);
 
+int orc_mt_forward_typed(const orc_config *c, const orc_task *tasks, const float *trunk, const float *const *task_params,
+                         const int32_t *ids, const int32_t *type_ids, const int32_t *mask, int64_t B, int64_t S, float *logits,
+                         float *hidden_out);
+
 int orc_mt_forward(const orc_config *c, const orc_task *tasks, const float *trunk, const float *const *task_params,
                    const int32_t *ids, const int32_t *mask, int64_t B, int64_t S, float *logits, float *hidden_out)
 {

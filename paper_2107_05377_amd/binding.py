@@ -19,17 +19,19 @@ LIB_PATH = os.path.join(HERE, "libmt_hip.so")
 MT_OK, MT_ERR_NULL, MT_ERR_CONFIG, MT_ERR_SHAPE, MT_ERR_STATE, MT_ERR_BLOB, MT_ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 MT_BF16, MT_FP32_CHECK = 0, 1
 MT_GELU_ERF, MT_GELU_TANH = 0, 1
-MT_ABI_VERSION = 1
+MT_ABI_VERSION = 2
+MT_HEAD_SEQUENCE, MT_HEAD_TOKEN = 0, 1
 KERNEL_CLASSES = ["embed", "gemm_qkv", "attn", "gemm_out", "ln", "gemm_ffn1", "gemm_ffn2", "pool", "gemm_first"]
 
 EXPORTS = ["mt_create", "mt_destroy", "mt_weight_bytes", "mt_workspace_bytes", "mt_bind", "mt_load_weights",
            "mt_forward", "mt_logit_offset", "mt_n_logits", "mt_layer_count", "mt_last_error", "mt_error_name",
            "mt_read_hidden", "mt_profile_enable", "mt_profile_read", "mt_op_linear", "mt_op_attention",
-           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed", "mt_op_linear_sub", "mt_op_first_token_pool", "mt_schedule_steps", "mt_forward_routed"]
+           "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed", "mt_op_linear_sub", "mt_op_first_token_pool", "mt_schedule_steps", "mt_forward_routed",
+           "mt_forward_tokens", "mt_token_logit_offset", "mt_n_token_logits"]
 
 
 class mt_task_desc(C.Structure):
-    _fields_ = [("fork_layer", C.c_int32), ("n_layers", C.c_int32), ("n_classes", C.c_int32)]
+    _fields_ = [("fork_layer", C.c_int32), ("n_layers", C.c_int32), ("n_classes", C.c_int32), ("head", C.c_int32)]
 
 
 class mt_config(C.Structure):
@@ -64,7 +66,10 @@ def lib():
         L.mt_forward.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_typed.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_routed.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
+        L.mt_forward_tokens.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
         L.mt_logit_offset.argtypes = [vp, i32]
+        L.mt_token_logit_offset.argtypes = [vp, i32]
+        L.mt_n_token_logits.argtypes = [vp]
         L.mt_n_logits.argtypes = [vp]
         L.mt_layer_count.argtypes = [vp]
         L.mt_last_error.argtypes = [vp]
@@ -98,7 +103,9 @@ class MTError(RuntimeError):
 
 def make_config(spec, *, max_batch=None, max_seq=None, precision=None):
     """mt_config for an mt_synth.MTSpec-like object (fields vocab, hidden, ..., tasks)."""
-    tasks = (mt_task_desc * len(spec.tasks))(*[mt_task_desc(t.fork_layer, t.n_layers, t.n_classes) for t in spec.tasks])
+    tasks = (mt_task_desc * len(spec.tasks))(*[mt_task_desc(t.fork_layer, t.n_layers, t.n_classes,
+                                                            MT_HEAD_TOKEN if getattr(t, "token_level", False) else MT_HEAD_SEQUENCE)
+                                               for t in spec.tasks])
     prec = precision if precision is not None else (MT_BF16 if spec.precision == "bf16" else MT_FP32_CHECK)
     cfg = mt_config(C.sizeof(mt_config), MT_ABI_VERSION, spec.vocab, spec.hidden, spec.heads, spec.ffn, spec.max_pos,
                     spec.type_vocab, spec.n_trunk_layers, len(spec.tasks), tasks, prec,
@@ -135,6 +142,7 @@ class Model:
         self.device = device
         self.weights = self.workspace = None
         self.n_logits = lib().mt_n_logits(self.h)
+        self.n_token_logits = lib().mt_n_token_logits(self.h)
         if bind:
             self.bind()
 
@@ -164,6 +172,9 @@ class Model:
 
     def logit_offset(self, t):
         return lib().mt_logit_offset(self.h, t)
+
+    def token_logit_offset(self, t):
+        return lib().mt_token_logit_offset(self.h, t)
 
     def bind(self):
         import torch
@@ -206,6 +217,23 @@ class Model:
             assert type_ids.shape == ids.shape
             self._check(lib().mt_forward_typed(self.h, _ptr(ids), _ptr(type_ids), _ptr(mask), b, s, tm, _ptr(out), _stream()))
         return out
+
+    def forward_tokens(self, ids, mask, out=None, out_tokens=None, task_mask=None, type_ids=None):
+        """mt_forward_tokens: returns (logits [B, C_tot], token logits [B, S, C_tok]), float32 CUDA tensors (enqueued,
+        not synced)."""
+        import torch
+        b, s = ids.shape
+        if out is None:
+            out = torch.zeros((b, self.n_logits), dtype=torch.float32, device=ids.device)
+        if out_tokens is None:
+            out_tokens = torch.zeros((b, s, self.n_token_logits), dtype=torch.float32, device=ids.device)
+        tm = None
+        if task_mask is not None:
+            tm = (C.c_uint8 * len(task_mask))(*[1 if v else 0 for v in task_mask])
+        self._check(lib().mt_forward_tokens(self.h, _ptr(ids), _ptr(type_ids) if type_ids is not None else None, _ptr(mask), b, s, tm,
+                                            _ptr(out) if out.numel() else None, _ptr(out_tokens) if out_tokens.numel() else None,
+                                            _stream()))
+        return out, out_tokens
 
     def forward_routed(self, ids, mask, route, out, type_ids=None):
         """route: [B][n_tasks] array-like of 0/1 (host); logits of wanted (b, t) pairs are written into `out`."""

@@ -162,6 +162,18 @@ struct ClsGroup {
 hipError_t launch_classifier(const ClsGroup& g, int G, int B, int H, int maxC, int w_bf16, int64_t ldo, const int32_t* out_row,
                              hipStream_t stream);
 
+// Token-level heads: out[g][p*ldo + c] = Wc[g][c] . x[g][row_of[p]] + bc[g][c] for every position p = b*S+s that is a
+// kept row (row_of[p] in [0, *n_rows)), zeros for the positions that are not.  x is float32 in the padding-free order.
+struct TokGroup {
+    const float* x[kMaxGroup];        // [rows][H]
+    const void* Wc[kMaxGroup];        // [C][H]
+    const float* bc[kMaxGroup];
+    float* out[kMaxGroup];            // first logit column of the task at position 0, position stride ldo
+    int32_t C[kMaxGroup];
+};
+hipError_t launch_token_classifier(const TokGroup& g, int G, int n_pos, int H, int w_bf16, int64_t ldo, const int32_t* row_of,
+                                   const int32_t* n_rows, hipStream_t stream);
+
 // Per-sequence task routing: a sub-batch of the sequences, as a padding-free row order of its own.
 // idx lists the chosen sequences (ascending batch indices), passed by value with the launch.
 constexpr int kMaxRouted = 1024;

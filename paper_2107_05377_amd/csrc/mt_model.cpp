@@ -85,8 +85,8 @@ struct mt_model {
     std::vector<mt_task_desc> tasks;
     bool bf16 = true;
     size_t esz = 2;   // bytes per matrix / activation element
-    int C_tot = 0;
-    std::vector<int> logit_off;
+    int C_tot = 0, C_tok = 0;            // widths of the per-sequence and of the per-token logit row
+    std::vector<int> logit_off;          // task -> first column inside the row of its kind
 
     // weight arena
     size_t w_word = 0, w_pos = 0, w_type = 0, w_embg = 0, w_embb = 0, w_trunk_end = 0;
@@ -676,6 +676,7 @@ int mt_create(const mt_config* cfg, mt_model** out)
     for (int t = 0; t < cfg->n_tasks; ++t) {
         const mt_task_desc& d = cfg->tasks[t];
         if (d.fork_layer < 0 || d.fork_layer > cfg->n_trunk_layers || d.n_layers < 0 || d.n_classes < 1) return MT_ERR_CONFIG;
+        if (d.head != MT_HEAD_SEQUENCE && d.head != MT_HEAD_TOKEN) return MT_ERR_CONFIG;
         deepest = std::max(deepest, d.fork_layer);
     }
     if (deepest != cfg->n_trunk_layers) return MT_ERR_CONFIG;   // the trunk is exactly as deep as the deepest fork
@@ -689,8 +690,9 @@ int mt_create(const mt_config* cfg, mt_model** out)
     m->esz = m->bf16 ? 2 : 4;
     const size_t H = cfg->hidden, F = cfg->ffn, T = cfg->n_tasks, D = cfg->n_trunk_layers;
     for (const auto& d : m->tasks) {
-        m->logit_off.push_back(m->C_tot);
-        m->C_tot += d.n_classes;
+        int& width = d.head == MT_HEAD_TOKEN ? m->C_tok : m->C_tot;
+        m->logit_off.push_back(width);
+        width += d.n_classes;
     }
 
     // ---- weight arena: trunk region, then one private region per task
@@ -707,9 +709,10 @@ int mt_create(const mt_config* cfg, mt_model** out)
         TaskW& tw = m->taskw[t];
         tw.begin = wb.off;
         for (int l = 0; l < m->tasks[t].n_layers; ++l) tw.layers.push_back(layout_layer(wb, H, F, m->esz));
-        if (m->bf16 && !tw.layers.empty()) tw.layers.back().WkT = wb.take(H * H * 2);
-        tw.Wp = wb.take(H * H * m->esz * (m->bf16 ? 2 : 1));
-        tw.bp = wb.take(H * 4);
+        const bool seq_head = m->tasks[t].head == MT_HEAD_SEQUENCE;
+        if (m->bf16 && seq_head && !tw.layers.empty()) tw.layers.back().WkT = wb.take(H * H * 2);
+        tw.Wp = seq_head ? wb.take(H * H * m->esz * (m->bf16 ? 2 : 1)) : 0;
+        tw.bp = seq_head ? wb.take(H * 4) : 0;
         tw.Wc = wb.take((size_t)m->tasks[t].n_classes * H * m->esz);
         tw.bc = wb.take((size_t)m->tasks[t].n_classes * 4);
         tw.end = wb.off;
@@ -735,7 +738,12 @@ int mt_create(const mt_config* cfg, mt_model** out)
     m->trunk_scr = layout_scratch(sb, M, H, F, m->esz, m->bf16, m->bf16 ? 4 : 1);
     const size_t MB = (size_t)cfg->max_batch;
     for (size_t t = 0; t < T; ++t) {
-        if (m->tasks[t].n_layers > 0) {
+        if (m->tasks[t].n_layers > 0 && m->tasks[t].head == MT_HEAD_TOKEN) {   // every layer runs on all rows
+            m->task_scr.push_back(layout_scratch(sb, M, H, F, m->esz, m->bf16, 1));
+            m->task_xf.push_back(sb.take(M * H * 4));
+            m->task_xb.push_back(m->bf16 ? sb.take(M * H * 2) : 0);
+            m->task_cls.push_back(ClsScratch{});
+        } else if (m->tasks[t].n_layers > 0) {
             m->task_scr.push_back(layout_scratch(sb, M, H, F, m->esz, m->bf16, 1));
             m->task_xf.push_back(sb.take(M * H * 4));
             m->task_xb.push_back(m->bf16 ? sb.take(M * H * 2) : 0);
@@ -803,9 +811,18 @@ int mt_logit_offset(const mt_model* m, int32_t task)
 {
     if (!m) return MT_ERR_NULL;
     if (task < 0 || task >= (int)m->tasks.size()) return MT_ERR_SHAPE;
+    if (m->tasks[task].head != MT_HEAD_SEQUENCE) return MT_ERR_CONFIG;
     return m->logit_off[task];
 }
 int mt_n_logits(const mt_model* m) { return m ? m->C_tot : MT_ERR_NULL; }
+int mt_token_logit_offset(const mt_model* m, int32_t task)
+{
+    if (!m) return MT_ERR_NULL;
+    if (task < 0 || task >= (int)m->tasks.size()) return MT_ERR_SHAPE;
+    if (m->tasks[task].head != MT_HEAD_TOKEN) return MT_ERR_CONFIG;
+    return m->logit_off[task];
+}
+int mt_n_token_logits(const mt_model* m) { return m ? m->C_tok : MT_ERR_NULL; }
 int mt_layer_count(const mt_model* m)
 {
     if (!m) return MT_ERR_NULL;
@@ -852,7 +869,7 @@ int mt_share_weights(mt_model* m, const mt_model* owner)
                 m->tasks.size() == owner->tasks.size();
     for (size_t t = 0; same && t < m->tasks.size(); ++t)
         same = m->tasks[t].fork_layer == owner->tasks[t].fork_layer && m->tasks[t].n_layers == owner->tasks[t].n_layers &&
-               m->tasks[t].n_classes == owner->tasks[t].n_classes;
+               m->tasks[t].n_classes == owner->tasks[t].n_classes && m->tasks[t].head == owner->tasks[t].head;
     if (!same) return fail(m, MT_ERR_CONFIG, "mt_share_weights: the two models were created from different configurations");
     if (!m->d_w || m->d_w != owner->d_w) return fail(m, MT_ERR_STATE, "mt_share_weights: not bound to the owner's weight arena");
     if (m->d_ws == owner->d_ws) return fail(m, MT_ERR_STATE, "mt_share_weights: the replica needs a workspace of its own");
@@ -885,8 +902,9 @@ int mt_load_weights(mt_model* m, int32_t scope, const void* h_blob, size_t nbyte
         want_tensors = 5 + 16 * (size_t)m->cfg.n_trunk_layers;
     } else {
         const mt_task_desc& d = m->tasks[scope];
-        want_floats = (size_t)d.n_layers * lf + H * H + H + (size_t)d.n_classes * H + d.n_classes;
-        want_tensors = 16 * (size_t)d.n_layers + 4;
+        const bool seq_head = d.head == MT_HEAD_SEQUENCE;
+        want_floats = (size_t)d.n_layers * lf + (seq_head ? H * H + H : 0) + (size_t)d.n_classes * H + d.n_classes;
+        want_tensors = 16 * (size_t)d.n_layers + (seq_head ? 4 : 2);
     }
     if ((size_t)hdr[1] != want_tensors) return fail(m, MT_ERR_BLOB, "mt_load_weights: %d tensors, expected %zu", hdr[1], want_tensors);
     if (nbytes != 16 + want_floats * 4)
@@ -922,7 +940,10 @@ int mt_load_weights(mt_model* m, int32_t scope, const void* h_blob, size_t nbyte
         const TaskW& tw = m->taskw[scope];
         const size_t C = m->tasks[scope].n_classes;
         for (const LayerW& L : tw.layers) p += stage_layer(m, L, p, img, begin);
-        if (m->bf16) {   // rows of [W | W]
+        const bool seq_head = m->tasks[scope].head == MT_HEAD_SEQUENCE;
+        if (!seq_head) {
+            // a token-level scope carries no pooler
+        } else if (m->bf16) {   // rows of [W | W]
             std::vector<uint16_t> row(H);
             for (size_t r = 0; r < H; ++r) {
                 put_matrix(reinterpret_cast<unsigned char*>(row.data()), p + r * H, H, true);
@@ -932,8 +953,10 @@ int mt_load_weights(mt_model* m, int32_t scope, const void* h_blob, size_t nbyte
         } else {
             put_matrix(at(tw.Wp), p, H * H, false);
         }
-        p += H * H;
-        memcpy(at(tw.bp), p, H * 4); p += H;
+        if (seq_head) {
+            p += H * H;
+            memcpy(at(tw.bp), p, H * 4); p += H;
+        }
         put_matrix(at(tw.Wc), p, C * H, m->bf16); p += C * H;
         memcpy(at(tw.bc), p, C * 4); p += C;
     }
@@ -951,10 +974,10 @@ int mt_load_weights(mt_model* m, int32_t scope, const void* h_blob, size_t nbyte
 // with the trunk.  h_route [batch][n_tasks]: per-sequence routing, a task runs on the sequences that ask for it.
 static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask,
                         int32_t batch, int32_t seq, const uint8_t* h_task_mask, const uint8_t* h_route, float* d_out_logits,
-                        void* hip_stream)
+                        float* d_out_token_logits, void* hip_stream)
 {
     if (!m) return MT_ERR_NULL;
-    if (!d_input_ids || !d_attn_mask || !d_out_logits) return fail(m, MT_ERR_NULL, "mt_forward: null device pointer");
+    if (!d_input_ids || !d_attn_mask) return fail(m, MT_ERR_NULL, "mt_forward: null device pointer");
     if (!m->d_w || !m->d_ws) return fail(m, MT_ERR_STATE, "mt_forward: call mt_bind first");
     if (batch < 1 || seq < 1 || batch > m->cfg.max_batch || seq > m->cfg.max_seq)
         return fail(m, MT_ERR_SHAPE, "mt_forward: batch %d x seq %d outside 1..%d x 1..%d", batch, seq, m->cfg.max_batch, m->cfg.max_seq);
@@ -972,6 +995,13 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
     for (int t = 0; t < T; ++t) {
         if (h_task_mask && !h_task_mask[t]) continue;
         if (!m->task_loaded[t]) return fail(m, MT_ERR_STATE, "mt_forward: task %d has no weights loaded", t);
+        if (m->tasks[t].head == MT_HEAD_TOKEN) {
+            if (h_route) return fail(m, MT_ERR_CONFIG, "mt_forward_routed: task %d has a token-level head, which is not routed", t);
+            if (!d_out_token_logits)
+                return fail(m, MT_ERR_NULL, "mt_forward: task %d has a token-level head: pass a token logits buffer (mt_forward_tokens)", t);
+        } else if (!d_out_logits) {
+            return fail(m, MT_ERR_NULL, "mt_forward: null logits buffer");
+        }
         enabled.push_back(t);
         depth = std::max(depth, m->tasks[t].fork_layer);
         max_y = std::max(max_y, m->tasks[t].n_layers);
@@ -1043,7 +1073,7 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
                 in_f = (const float*)(ws + m->task_xf[t]);
                 in_b = bf ? (const void*)(ws + m->task_xb[t]) : nullptr;
             }
-            if (stage == d.n_layers - 1) {
+            if (stage == d.n_layers - 1 && d.head == MT_HEAD_SEQUENCE) {
                 last.push_back(LastIO{in_f, bf ? in_b : (const void*)in_f, &m->taskw[t].layers[stage], &m->task_scr[t], &m->task_cls[t]});
             } else {
                 full.push_back(LayerIO{in_f, in_b, &m->taskw[t].layers[stage], &m->task_scr[t], (float*)(ws + m->task_xf[t]),
@@ -1066,7 +1096,10 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
 
     // ---- poolers and classifiers.  The pooler input stays float32-accurate in both modes: the bf16
     // path feeds the matrix cores with the [hi | lo] split of the first-token rows against [W | W].
-    auto run_heads = [&](const std::vector<int>& list, const RowMap& hrm, int HB, bool gathered, const int32_t* out_row) {
+    auto run_heads = [&](const std::vector<int>& all, const RowMap& hrm, int HB, bool gathered, const int32_t* out_row) {
+    std::vector<int> list;
+    for (int t : all)
+        if (m->tasks[t].head == MT_HEAD_SEQUENCE) list.push_back(t);
     for (size_t lo = 0; lo < list.size(); lo += kMaxGroup) {
         const int n = (int)std::min(list.size() - lo, (size_t)kMaxGroup);
         GemmGroup g;
@@ -1114,8 +1147,34 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
     }
     };
 
+    // ---- token-level heads: one linear layer on every kept row of the task's final state, scattered to [B][S][C_tok]
+    auto run_token_heads = [&](const std::vector<int>& all) {
+        std::vector<int> list;
+        for (int t : all)
+            if (m->tasks[t].head == MT_HEAD_TOKEN) list.push_back(t);
+        for (size_t lo = 0; lo < list.size(); lo += kMaxGroup) {
+            const int n = (int)std::min(list.size() - lo, (size_t)kMaxGroup);
+            TokGroup tg;
+            memset(&tg, 0, sizeof tg);
+            for (int i = 0; i < n; ++i) {
+                const int t = list[lo + i];
+                const mt_task_desc& d = m->tasks[t];
+                tg.x[i] = d.n_layers > 0 ? (const float*)(ws + m->task_xf[t])
+                                         : (const float*)(ws + m->tap_f[m->tap_of_layer[d.fork_layer]]);
+                tg.Wc[i] = W + m->taskw[t].Wc;
+                tg.bc[i] = (const float*)(W + m->taskw[t].bc);
+                tg.out[i] = d_out_token_logits + m->logit_off[t];
+                tg.C[i] = d.n_classes;
+            }
+            L.begin(MT_K_POOL);
+            L.check(launch_token_classifier(tg, n, B * S, H, bf ? 1 : 0, m->C_tok, rm.row_of, rm.n_rows, L.st));
+            L.end();
+        }
+    };
+
     if (!h_route) {
         run_heads(enabled, rm, B, false, nullptr);
+        run_token_heads(enabled);
     } else {
         // ---- per-sequence routing: tasks wanted by the same set of sequences form a group; the group's sequences are
         // gathered from each task's tap into a padding-free row order of their own, on which the task's layers,
@@ -1187,13 +1246,22 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
 int mt_forward_typed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask, int32_t batch,
                      int32_t seq, const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream)
 {
-    return forward_impl(m, d_input_ids, d_token_type_ids, d_attn_mask, batch, seq, h_task_mask, nullptr, d_out_logits, hip_stream);
+    return forward_impl(m, d_input_ids, d_token_type_ids, d_attn_mask, batch, seq, h_task_mask, nullptr, d_out_logits, nullptr,
+                        hip_stream);
+}
+
+int mt_forward_tokens(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask,
+                      int32_t batch, int32_t seq, const uint8_t* h_task_mask, float* d_out_logits, float* d_out_token_logits,
+                      void* hip_stream)
+{
+    return forward_impl(m, d_input_ids, d_token_type_ids, d_attn_mask, batch, seq, h_task_mask, nullptr, d_out_logits,
+                        d_out_token_logits, hip_stream);
 }
 
 int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_mask, int32_t batch, int32_t seq,
                const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream)
 {
-    return forward_impl(m, d_input_ids, nullptr, d_attn_mask, batch, seq, h_task_mask, nullptr, d_out_logits, hip_stream);
+    return forward_impl(m, d_input_ids, nullptr, d_attn_mask, batch, seq, h_task_mask, nullptr, d_out_logits, nullptr, hip_stream);
 }
 
 int mt_forward_routed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask, int32_t batch,
@@ -1201,7 +1269,7 @@ int mt_forward_routed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_
 {
     if (!m) return MT_ERR_NULL;
     if (!h_route) return fail(m, MT_ERR_NULL, "mt_forward_routed: null routing table");
-    return forward_impl(m, d_input_ids, d_token_type_ids, d_attn_mask, batch, seq, nullptr, h_route, d_out_logits, hip_stream);
+    return forward_impl(m, d_input_ids, d_token_type_ids, d_attn_mask, batch, seq, nullptr, h_route, d_out_logits, nullptr, hip_stream);
 }
 
 int mt_read_hidden(mt_model* m, int32_t task, int32_t layer, float* d_out, size_t out_bytes, void* hip_stream)
@@ -1220,13 +1288,16 @@ int mt_read_hidden(mt_model* m, int32_t task, int32_t layer, float* d_out, size_
         if (task >= (int)m->tasks.size()) return fail(m, MT_ERR_SHAPE, "mt_read_hidden: task %d out of range", task);
         if (!m->last_enabled[task]) return fail(m, MT_ERR_STATE, "mt_read_hidden: task %d was not computed", task);
         const mt_task_desc& d = m->tasks[task];
-        if (d.n_layers > 0) {   // only the first-token rows of a branch's final state exist
+        if (d.n_layers > 0 && d.head == MT_HEAD_TOKEN) {
+            src = m->d_ws + m->task_xf[task];
+        } else if (d.n_layers > 0) {   // only the first-token rows of a branch's final state exist
             hipError_t e = launch_place_first_rows((const float*)(m->d_ws + m->task_cls[task].out_f), m->last_B, m->last_S,
                                                    m->cfg.hidden, d_out, static_cast<hipStream_t>(hip_stream));
             if (e != hipSuccess) return fail(m, MT_ERR_HIP, "mt_read_hidden: %s", hipGetErrorString(e));
             return MT_OK;
+        } else {
+            src = m->d_ws + m->tap_f[m->tap_of_layer[d.fork_layer]];
         }
-        src = m->d_ws + m->tap_f[m->tap_of_layer[d.fork_layer]];
     }
     hipError_t e = launch_unpack_rows((const float*)src, (const int32_t*)(m->d_ws + m->rm_rowof), m->last_B * m->last_S, m->cfg.hidden,
                                       d_out, static_cast<hipStream_t>(hip_stream));

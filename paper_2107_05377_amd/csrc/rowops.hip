@@ -351,6 +351,49 @@ __global__ __launch_bounds__(256) void classifier_kernel(ClsGroup g, int B, int 
     }
 }
 
+// Token-level head.  A workgroup owns 16 consecutive positions, each of its 4 wavefronts 4 of them, so that a row
+// of Wc is fetched once per 4 positions; lanes stride over the hidden dimension, float32 accumulation.
+constexpr int kTokPosPerWave = 4;
+template <typename TW>
+__global__ __launch_bounds__(256) void token_classifier_kernel(TokGroup g, int n_pos, int H, int64_t ldo,
+                                                               const int32_t* __restrict__ row_of,
+                                                               const int32_t* __restrict__ n_rows)
+{
+    const int grp = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int p0 = (blockIdx.x * 4 + wave) * kTokPosPerWave;
+    if (p0 >= n_pos) return;
+    const int kept = *n_rows;
+    const int C = g.C[grp];
+    const float* xr[kTokPosPerWave];
+    bool live[kTokPosPerWave];
+#pragma unroll
+    for (int j = 0; j < kTokPosPerWave; ++j) {
+        const int p = p0 + j;
+        const int r = p < n_pos ? row_of[p] : -1;
+        live[j] = r >= 0 && r < kept;
+        xr[j] = g.x[grp] + (size_t)(live[j] ? r : 0) * H;
+    }
+    const bool any = live[0] || live[1] || live[2] || live[3];
+    for (int c = 0; c < C; ++c) {
+        float acc[kTokPosPerWave] = {0.f, 0.f, 0.f, 0.f};
+        if (any) {
+            const TW* w = static_cast<const TW*>(g.Wc[grp]) + (size_t)c * H;
+            for (int i = lane; i < H; i += 64) {
+                const float wv = (float)w[i];
+#pragma unroll
+                for (int j = 0; j < kTokPosPerWave; ++j) acc[j] = fmaf(live[j] ? xr[j][i] : 0.f, wv, acc[j]);
+            }
+        }
+        const float bias = g.bc[grp][c];
+#pragma unroll
+        for (int j = 0; j < kTokPosPerWave; ++j) {
+            const float v = wave_sum(acc[j]);
+            if (lane == 0 && p0 + j < n_pos) g.out[grp][(size_t)(p0 + j) * ldo + c] = live[j] ? v + bias : 0.f;
+        }
+    }
+}
+
 // Row order of a sub-batch (per-sequence routing).  One workgroup: lengths of the chosen sequences, their prefix
 // sums (n_sel <= 1024, four per thread), then for every chosen sequence the batch rows its compact rows copy.
 __global__ __launch_bounds__(256) void route_map_kernel(RouteIdx idx, int n_sel, const int32_t* __restrict__ g_start,
@@ -451,6 +494,17 @@ hipError_t launch_place_first_rows(const float* x, int B, int S, int H, float* o
     const int n_pos = B * S;
     hipLaunchKernelGGL(place_first_rows_kernel, dim3((n_pos + kRowsPerBlock - 1) / kRowsPerBlock), dim3(256), 0, stream, x, n_pos, S, H,
                        out);
+    return hipGetLastError();
+}
+
+hipError_t launch_token_classifier(const TokGroup& g, int G, int n_pos, int H, int w_bf16, int64_t ldo, const int32_t* row_of,
+                                   const int32_t* n_rows, hipStream_t stream)
+{
+    if (G <= 0 || n_pos <= 0) return hipSuccess;
+    if (G > kMaxGroup || !row_of || !n_rows || H < 1) return hipErrorInvalidValue;
+    const dim3 grid((n_pos + 4 * kTokPosPerWave - 1) / (4 * kTokPosPerWave), G);
+    if (w_bf16) hipLaunchKernelGGL((token_classifier_kernel<__bf16>), grid, dim3(256), 0, stream, g, n_pos, H, ldo, row_of, n_rows);
+    else hipLaunchKernelGGL((token_classifier_kernel<float>), grid, dim3(256), 0, stream, g, n_pos, H, ldo, row_of, n_rows);
     return hipGetLastError();
 }
 

@@ -148,6 +148,43 @@ def test_industrial_workload_layer_count():
     mt.lib().mt_destroy(h)
 
 
+def test_token_level_heads_layout_and_checks():
+    """Tagging tasks (Appendix E) sit in a per-token logit row of their own; their scope has no pooler."""
+    spec = ms.get_config("assistant")
+    assert spec.n_tasks == 21 and [t for t, k in enumerate(spec.tasks) if k.token_level] == [7, 12, 15]
+    rc, h, _ = _create(spec)
+    assert rc == mt.MT_OK
+    L = mt.lib()
+    assert L.mt_layer_count(h) == 40
+    assert L.mt_n_token_logits(h) == 30 + 16 + 9 == spec.n_token_logits
+    assert L.mt_n_logits(h) == spec.n_logits == sum(t.n_classes for t in spec.tasks) - 55
+    assert [L.mt_token_logit_offset(h, t) for t in (7, 12, 15)] == [0, 30, 46]
+    assert L.mt_token_logit_offset(h, 0) == mt.MT_ERR_CONFIG and L.mt_logit_offset(h, 7) == mt.MT_ERR_CONFIG
+    assert L.mt_token_logit_offset(h, 21) == mt.MT_ERR_SHAPE
+    assert [L.mt_logit_offset(h, t) for t in (0, 6, 8)] == [spec.logit_offset(t) for t in (0, 6, 8)]
+    # the same table with sequence heads only stores, for each of the three tasks, a pooler as [W | W] (2 H^2) and the
+    # transposed key matrix of its last layer (H^2): 3 * 3 H^2 bf16 values more
+    rc2, h2, _ = _create(ms.get_config("industrial"))
+    assert rc2 == mt.MT_OK
+    diff = L.mt_weight_bytes(h2) - L.mt_weight_bytes(h)
+    assert 2 * 9 * 768 * 768 <= diff <= 2 * 9 * 768 * 768 + 3 * 768 * 4 + 4096
+    L.mt_destroy(h2)
+    # a token-level task needs the token buffer, and is not routed
+    fake = C.c_void_p(0x10000)     # never dereferenced: the calls below fail their host-side checks first
+    assert L.mt_bind(h, fake, 1 << 40, fake, 1 << 40) == mt.MT_OK
+    cfg = mt.make_config(spec)
+    cfg.tasks[3].head = 2
+    hb = C.c_void_p()
+    assert L.mt_create(C.byref(cfg), C.byref(hb)) == mt.MT_ERR_CONFIG
+    # blob size of a token-level scope: layers + Wc + bc, two tensors after the layers
+    flat, idx = ms.make_task_params(spec, 7)
+    assert len(idx) == 16 * spec.tasks[7].n_layers + 2
+    blob = mt.pack_blob(7, len(idx) + 2, flat)
+    buf = C.create_string_buffer(blob, len(blob))
+    assert L.mt_load_weights(h, 7, C.cast(buf, C.c_void_p), len(blob), None) == mt.MT_ERR_BLOB
+    L.mt_destroy(h)
+
+
 def test_wavefront_schedule_step_counts():
     """A branch starts as soon as its tap exists: steps = max over tasks of fork + own layers (Fig. 1(c))."""
     L = mt.lib()

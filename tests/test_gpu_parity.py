@@ -709,3 +709,116 @@ def test_random_small_models_match_oracle(seed, bf16):
                 assert (o_r[b, sl] == 5.0).all()
         col += task.n_classes
     model.close()
+
+
+# ------------------------------------------------------------------ token-level heads (tagging tasks, Appendix E)
+
+TOKF = ms.MTSpec("tokf", vocab=50, hidden=32, heads=4, ffn=64, max_pos=24, n_trunk_layers=2,
+                 tasks=(ms.TaskSpec(1, 1, 2), ms.TaskSpec(2, 1, 5, token_level=True), ms.TaskSpec(2, 0, 3),
+                        ms.TaskSpec(0, 2, 4, token_level=True), ms.TaskSpec(1, 0, 32, token_level=True)),
+                 precision="fp32", batch=3, seq=10, len_lo=2, len_hi=10, input_seed=78, weights_seed=4243)
+TOKB = ms.MTSpec("tokb", vocab=500, hidden=128, heads=2, ffn=256, max_pos=80, n_trunk_layers=3,
+                 tasks=(ms.TaskSpec(3, 2, 2), ms.TaskSpec(1, 1, 7, token_level=True), ms.TaskSpec(2, 0, 1),
+                        ms.TaskSpec(3, 0, 3, token_level=True), ms.TaskSpec(0, 3, 12, token_level=True), ms.TaskSpec(3, 1, 4)),
+                 precision="bf16", batch=9, seq=71, len_lo=1, len_hi=71, input_seed=79, weights_seed=4244)
+
+
+def _token_case(spec, stress, std, mask_edit=None, batch_index=0):
+    tr, tri, tps = _params(spec, stress, std)
+    model = _load(spec, tr, tri, tps)
+    orc = oracle.Oracle(spec, tr, [p for p, _ in tps])
+    ids, mask, lengths = ms.make_inputs(spec, batch_index=batch_index)
+    if mask_edit is not None:
+        mask = mask.copy()
+        mask_edit(mask)
+    ref, ref_tok = orc.mt_forward(ids, mask, want_tokens=True)
+    return model, orc, ids, mask, ref, ref_tok
+
+
+@pytest.mark.parametrize("stress", [False, True])
+def test_token_heads_fp32_mode_match_oracle(stress):
+    spec = TOKF
+    say(f"token-level heads, fp32 mode, stress={stress}")
+    model, orc, ids, mask, ref, ref_tok = _token_case(spec, stress, 0.1)
+    assert model.n_logits == 5 and model.n_token_logits == 41
+    assert [model.token_logit_offset(t) for t in (1, 3, 4)] == [0, 5, 9]
+    got, tok = model.forward_tokens(dev(ids), dev(mask))
+    got, tok = got.cpu().numpy(), tok.cpu().numpy()
+    real = mask.astype(bool)
+    assert np.abs(got - ref).max() <= 1e-4 * max(np.abs(ref).max(), 1e-3)
+    for t in (1, 3, 4):
+        c0, c1 = spec.logit_offset(t), spec.logit_offset(t) + spec.tasks[t].n_classes
+        scale = max(np.abs(ref_tok[:, :, c0:c1][real]).max(), 1e-3)
+        assert np.abs(tok[:, :, c0:c1][real] - ref_tok[:, :, c0:c1][real]).max() <= 1e-4 * scale, t
+    assert (tok[~real] == 0).all() and (~real).any()
+    # the whole final state of a token-level branch is kept and readable
+    h = model.read_hidden(3, 0, *ids.shape).cpu().numpy()
+    assert (h[~real] == 0).all() and np.abs(h[real]).max() > 0.1
+    # the plain entry point refuses a token-level task instead of dropping its output, and serves the others
+    with pytest.raises(mt.MTError):
+        model.forward(dev(ids), dev(mask))
+    seq_only = [0 if t.token_level else 1 for t in spec.tasks]
+    assert np.array_equal(model.forward(dev(ids), dev(mask), task_mask=seq_only).cpu().numpy(), got)
+    with pytest.raises(mt.MTError):
+        model.forward_routed(dev(ids), dev(mask), np.ones((spec.batch, spec.n_tasks)), torch.zeros((spec.batch, 5), device="cuda"))
+    # disabled token-level tasks leave their columns alone
+    o = torch.full((spec.batch, 5), 3.0, device="cuda")
+    ot = torch.full((spec.batch, spec.seq, 41), 3.0, device="cuda")
+    model.forward_tokens(dev(ids), dev(mask), out=o, out_tokens=ot, task_mask=[0, 1, 0, 0, 1])
+    assert (o == 3.0).all() and (ot[:, :, 5:9] == 3.0).all()
+    assert torch.equal(ot[:, :, :5].cpu(), torch.from_numpy(tok[:, :, :5])) and torch.equal(ot[:, :, 9:].cpu(), torch.from_numpy(tok[:, :, 9:]))
+    model.close()
+
+
+def test_token_heads_bf16_mode_match_oracle():
+    spec = TOKB
+    say("token-level heads, bf16 mode, ragged lengths, a mask with holes")
+
+    def edit(mask):
+        mask[0, :] = 1
+        mask[1, 1:] = 0
+        mask[2, :] = 1
+        mask[2, [3, 4, 17, 40, 70]] = 0
+    for bi, ed in ((0, None), (1, edit)):
+        model, orc, ids, mask, ref, ref_tok = _token_case(spec, True, 0.05, ed, batch_index=bi)
+        got, tok = model.forward_tokens(dev(ids), dev(mask))
+        got, tok = got.cpu().numpy(), tok.cpu().numpy()
+        real = mask.astype(bool)
+        e_seq, e_tok = np.abs(got - ref).max(), np.abs(tok[real] - ref_tok[real]).max()
+        say(f"  batch {bi}: max |dlogit| per sequence {e_seq:.4g}, per token {e_tok:.4g} over {int(real.sum())} tokens")
+        assert e_seq <= 2e-2 and e_tok <= 2e-2
+        assert (tok[~real] == 0).all()
+        # tag decisions: wherever the oracle's margin exceeds twice the tolerance the chosen label agrees
+        for t in (1, 3, 4):
+            c0, c1 = spec.logit_offset(t), spec.logit_offset(t) + spec.tasks[t].n_classes
+            g, o = tok[:, :, c0:c1][real], ref_tok[:, :, c0:c1][real]
+            srt = np.sort(o, axis=1)
+            safe = (srt[:, -1] - srt[:, -2]) > 4e-2
+            assert (g.argmax(1) == o.argmax(1))[safe].all()
+        # smaller batch and sequence than the maximum on the same model
+        ids2, mask2, _ = ms.make_inputs(spec, batch=2, seq=33, batch_index=7)
+        r2, rt2 = orc.mt_forward(ids2, mask2, want_tokens=True)
+        g2, t2 = model.forward_tokens(dev(ids2), dev(mask2))
+        assert np.abs(g2.cpu().numpy() - r2).max() <= 2e-2
+        assert np.abs(t2.cpu().numpy()[mask2.astype(bool)] - rt2[mask2.astype(bool)]).max() <= 2e-2
+        model.close()
+
+
+def test_token_heads_assistant_workload_sampled():
+    """21 tasks on 8 shared layers, three of them tagging every token, at the serving shape of the benchmark."""
+    spec = ms.get_config("assistant")
+    say("workload assistant: building weights")
+    tr, tri, tps = _params(spec, False)
+    model = _load(spec, tr, tri, tps)
+    ids, mask, lengths = ms.make_inputs(spec)
+    got, tok = model.forward_tokens(dev(ids), dev(mask))
+    got, tok = got.cpu().numpy(), tok.cpu().numpy()
+    rows = [0, 7, 13]
+    say("  oracle on rows", rows)
+    ref, ref_tok = oracle.Oracle(spec, tr, [p for p, _ in tps]).mt_forward(ids[rows], mask[rows], want_tokens=True)
+    real = mask[rows].astype(bool)
+    e_seq, e_tok = np.abs(got[rows] - ref).max(), np.abs(tok[rows][real] - ref_tok[real]).max()
+    say(f"  max |dlogit| per sequence {e_seq:.4g}, per token {e_tok:.4g}")
+    assert e_seq <= 2e-2 and e_tok <= 2e-2
+    assert (tok[~mask.astype(bool)] == 0).all() and np.isfinite(tok).all()
+    model.close()
