@@ -26,8 +26,9 @@ def layer_kinds(spec):
 
     Only position 0 of a branch's output feeds its pooler, so the library computes the last own layer
     of every branch for that position alone (its keys and values still come from every row)."""
-    n_full = spec.n_trunk_layers + sum(max(t.n_layers - 1, 0) for t in spec.tasks)
-    n_first = sum(1 for t in spec.tasks if t.n_layers >= 1)
+    tok = [getattr(t, "token_level", False) for t in spec.tasks]       # a tagging task needs every row of its last layer
+    n_full = spec.n_trunk_layers + sum(t.n_layers if k else max(t.n_layers - 1, 0) for t, k in zip(spec.tasks, tok))
+    n_first = sum(1 for t, k in zip(spec.tasks, tok) if t.n_layers >= 1 and not k)
     return n_full, n_first
 
 
@@ -53,6 +54,13 @@ def gemm_flops_per_forward(spec, rows, batch):
             "gemm_ffn1": n_full * 2.0 * rows * F * H,
             "gemm_ffn2": n_full * 2.0 * rows * H * F,
             "gemm_first": n_first * first}
+
+
+def forward(model, batch, out=None, out_tokens=None):
+    """One forward of the whole model: the token-level entry point when the model has tagging tasks."""
+    if model.n_token_logits > 0:
+        return model.forward_tokens(*batch, out=out, out_tokens=out_tokens)[0]
+    return model.forward(*batch, out=out)
 
 
 def stored_traffic(workload_name):
@@ -86,13 +94,14 @@ def latency_sweep(mt, ms, spec, model, calls):
             ids, mask, _ = ms.make_inputs(spec, batch=b, batch_index=i)
             sets.append((torch.from_numpy(ids).cuda(), torch.from_numpy(mask).cuda()))
         out = torch.zeros((b, model.n_logits), dtype=torch.float32, device="cuda")
+        tok = torch.zeros((b, spec.seq, model.n_token_logits), dtype=torch.float32, device="cuda") if model.n_token_logits else None
         for i in range(50):
-            model.forward(*sets[i % 8], out=out)
+            forward(model, sets[i % 8], out, tok)
         torch.cuda.synchronize()
         t = np.empty(calls)
         for i in range(calls):
             t0 = time.perf_counter()
-            model.forward(*sets[i % 8], out=out)
+            forward(model, sets[i % 8], out, tok)
             torch.cuda.synchronize()
             t[i] = time.perf_counter() - t0
         res.append({"batch": b, "calls": calls, "p50_ms": float(np.percentile(t, 50) * 1e3), "p99_ms": float(np.percentile(t, 99) * 1e3),
@@ -105,7 +114,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="base", help="tiny | base | hetero | latency | large | industrial | wo_kd | mixed")
+    ap.add_argument("--config", default="base", help="tiny | base | hetero | latency | large | industrial | wo_kd | mixed | assistant")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--in-flight", type=int, default=3,
                     help="batches in flight: forwards are issued round-robin to this many model replicas (shared "
@@ -153,6 +162,8 @@ def main():
     models = [model] + [model.replica() for _ in range(n_fly - 1)]
     streams = [torch.cuda.Stream() for _ in range(n_fly)]          # default priority
     outs = [torch.zeros_like(out) for _ in range(n_fly)]
+    tok_outs = [torch.zeros((B, S, model.n_token_logits), dtype=torch.float32, device="cuda") if model.n_token_logits else None
+                for _ in range(n_fly)]
 
     def run_steps(k, fly):
         """k forwards, round-robin over the replicas' streams; returns elapsed milliseconds."""
@@ -164,7 +175,7 @@ def main():
         for i in range(k):
             j = i % fly
             with torch.cuda.stream(streams[j]):
-                models[j].forward(*batches[i % n_batches], out=outs[j])
+                forward(models[j], batches[i % n_batches], outs[j], tok_outs[j])
         for st in streams[:fly]:
             stream.wait_stream(st)
         e1.record(stream)
@@ -192,7 +203,7 @@ def main():
     # ---- per-kernel durations from HIP events around every launch, same stream, same steps
     model.profile_enable(True)
     for i in range(args.steps):
-        model.forward(*batches[i % n_batches], out=out)
+        forward(model, batches[i % n_batches], out, tok_outs[0])
     torch.cuda.synchronize()
     prof = model.profile_read()
     model.profile_enable(False)
@@ -267,7 +278,7 @@ def main():
             t0 = time.time()
             ref = orc.mt_forward(ids[:n], mask[:n])
             dt += time.time() - t0
-            got = model.forward(*batches[bi]).cpu().numpy()[:n]
+            got = forward(model, batches[bi]).cpu().numpy()[:n]
             err = max(err, float(np.abs(got - ref).max()))
             left -= n
             n_done += n

@@ -342,13 +342,13 @@ __global__ __launch_bounds__(256) void classifier_kernel(ClsGroup g, int B, int 
     const int ob = out_row ? out_row[b] : b;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float* p = g.pooled[grp] + (size_t)b * H;
-    for (int c = wave; c < g.C[grp]; c += 4) {
-        const TW* w = static_cast<const TW*>(g.Wc[grp]) + (size_t)c * H;
-        float acc = 0.f;
-        for (int i = lane; i < H; i += 64) acc = fmaf(p[i], (float)w[i], acc);
-        acc = wave_sum(acc);
-        if (lane == 0) g.out[grp][(size_t)ob * ldo + c] = acc + g.bc[grp][c];
-    }
+    const int c = blockIdx.z * 4 + wave;            // one wavefront per class
+    if (c >= g.C[grp]) return;
+    const TW* w = static_cast<const TW*>(g.Wc[grp]) + (size_t)c * H;
+    float acc = 0.f;
+    for (int i = lane; i < H; i += 64) acc = fmaf(p[i], (float)w[i], acc);
+    acc = wave_sum(acc);
+    if (lane == 0) g.out[grp][(size_t)ob * ldo + c] = acc + g.bc[grp][c];
 }
 
 // Token-level head.  A workgroup owns 16 consecutive positions, each of its 4 wavefronts 4 of them, so that a row
@@ -390,6 +390,54 @@ __global__ __launch_bounds__(256) void token_classifier_kernel(TokGroup g, int n
         for (int j = 0; j < kTokPosPerWave; ++j) {
             const float v = wave_sum(acc[j]);
             if (lane == 0 && p0 + j < n_pos) g.out[grp][(size_t)(p0 + j) * ldo + c] = live[j] ? v + bias : 0.f;
+        }
+    }
+}
+
+// The same for H = NV * 256: one wavefront per position keeps its row in registers (NV float4 per lane) and takes
+// the classes four at a time, so the loads of four weight rows are in flight together.
+template <typename TW, int NV>
+__global__ __launch_bounds__(256) void token_classifier_rows_kernel(TokGroup g, int n_pos, int64_t ldo,
+                                                                    const int32_t* __restrict__ row_of,
+                                                                    const int32_t* __restrict__ n_rows)
+{
+    constexpr int H = NV * 256;
+    const int grp = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (p >= n_pos) return;
+    const int C = g.C[grp];
+    float* out = g.out[grp] + (size_t)p * ldo;
+    const int r = row_of[p];
+    if (r < 0 || r >= *n_rows) {
+        for (int c = lane; c < C; c += 64) out[c] = 0.f;
+        return;
+    }
+    const float* x = g.x[grp] + (size_t)r * H;
+    float4 xv[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) xv[v] = load4<float>(x + (v * 64 + lane) * 4);
+    const TW* W = static_cast<const TW*>(g.Wc[grp]);
+    for (int c0 = 0; c0 < C; c0 += 4) {
+        float acc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const TW* w = W + (size_t)min(c0 + u, C - 1) * H;
+            float a = 0.f;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const float4 wv = load4<TW>(w + (v * 64 + lane) * 4);
+                a = fmaf(xv[v].x, wv.x, a);
+                a = fmaf(xv[v].y, wv.y, a);
+                a = fmaf(xv[v].z, wv.z, a);
+                a = fmaf(xv[v].w, wv.w, a);
+            }
+            acc[u] = a;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float v = wave_sum(acc[u]);
+            if (lane == 0 && c0 + u < C) out[c0 + u] = v + g.bc[grp][c0 + u];
         }
     }
 }
@@ -502,6 +550,19 @@ hipError_t launch_token_classifier(const TokGroup& g, int G, int n_pos, int H, i
 {
     if (G <= 0 || n_pos <= 0) return hipSuccess;
     if (G > kMaxGroup || !row_of || !n_rows || H < 1) return hipErrorInvalidValue;
+    if (H % 256 == 0 && H <= 1280) {          // classifier rows are then 16-byte aligned for either element type
+        const dim3 rgrid((n_pos + 3) / 4, G);
+#define MT_TOK_ROWS(NV)                                                                                                            \
+    case NV:                                                                                                                       \
+        if (w_bf16) hipLaunchKernelGGL((token_classifier_rows_kernel<__bf16, NV>), rgrid, dim3(256), 0, stream, g, n_pos, ldo, row_of, n_rows); \
+        else hipLaunchKernelGGL((token_classifier_rows_kernel<float, NV>), rgrid, dim3(256), 0, stream, g, n_pos, ldo, row_of, n_rows);         \
+        break;
+        switch (H / 256) {
+            MT_TOK_ROWS(1) MT_TOK_ROWS(2) MT_TOK_ROWS(3) MT_TOK_ROWS(4) MT_TOK_ROWS(5)
+        }
+#undef MT_TOK_ROWS
+        return hipGetLastError();
+    }
     const dim3 grid((n_pos + 4 * kTokPosPerWave - 1) / (4 * kTokPosPerWave), G);
     if (w_bf16) hipLaunchKernelGGL((token_classifier_kernel<__bf16>), grid, dim3(256), 0, stream, g, n_pos, H, ldo, row_of, n_rows);
     else hipLaunchKernelGGL((token_classifier_kernel<float>), grid, dim3(256), 0, stream, g, n_pos, H, ldo, row_of, n_rows);
@@ -529,8 +590,9 @@ hipError_t launch_classifier(const ClsGroup& g, int G, int B, int H, int maxC, i
                              hipStream_t stream)
 {
     if (G <= 0 || B <= 0 || maxC <= 0) return hipSuccess;
-    if (w_bf16) hipLaunchKernelGGL((classifier_kernel<__bf16>), dim3(B, G), dim3(256), 0, stream, g, B, H, ldo, out_row);
-    else hipLaunchKernelGGL((classifier_kernel<float>), dim3(B, G), dim3(256), 0, stream, g, B, H, ldo, out_row);
+    const dim3 grid(B, G, (maxC + 3) / 4);
+    if (w_bf16) hipLaunchKernelGGL((classifier_kernel<__bf16>), grid, dim3(256), 0, stream, g, B, H, ldo, out_row);
+    else hipLaunchKernelGGL((classifier_kernel<float>), grid, dim3(256), 0, stream, g, B, H, ldo, out_row);
     return hipGetLastError();
 }
 

@@ -822,3 +822,33 @@ def test_token_heads_assistant_workload_sampled():
     assert e_seq <= 2e-2 and e_tok <= 2e-2
     assert (tok[~mask.astype(bool)] == 0).all() and np.isfinite(tok).all()
     model.close()
+
+
+@pytest.mark.parametrize("precision,hidden,heads", [("fp32", 256, 4), ("bf16", 256, 4), ("fp32", 512, 2), ("bf16", 1280, 20)])
+def test_token_heads_wide_rows(precision, hidden, heads):
+    """Hidden sizes that are multiples of 256 take the token classifier that keeps a row in registers; class counts
+    that are not multiples of four, a task without own layers, one sequence of a single token."""
+    spec = ms.MTSpec("tokw", vocab=300, hidden=hidden, heads=heads, ffn=256, max_pos=40, n_trunk_layers=1,
+                     tasks=(ms.TaskSpec(1, 1, 6, token_level=True), ms.TaskSpec(1, 0, 1, token_level=True),
+                            ms.TaskSpec(0, 1, 3), ms.TaskSpec(0, 1, 67, token_level=True)),
+                     precision=precision, batch=5, seq=37, len_lo=1, len_hi=37, input_seed=80, weights_seed=4245)
+
+    def edit(mask):
+        mask[0, 1:] = 0
+        mask[1, :] = 1
+    # weight scale: 0.1 in float32 mode; in bf16 mode 0.05, and 0.03 at H = 1280 as in the many-heads case above (the
+    # absolute logit tolerance is meant for logits of order one, which a wider model reaches with smaller weights)
+    std = 0.1 if precision == "fp32" else (0.03 if hidden > 1024 else 0.05)
+    model, orc, ids, mask, ref, ref_tok = _token_case(spec, True, std, edit)
+    got, tok = model.forward_tokens(dev(ids), dev(mask))
+    got, tok = got.cpu().numpy(), tok.cpu().numpy()
+    real = mask.astype(bool)
+    e_seq, e_tok = np.abs(got - ref).max(), np.abs(tok[real] - ref_tok[real]).max()
+    say(f"  logit scale: per sequence {np.abs(ref).max():.3g}, per token {np.abs(ref_tok[real]).max():.3g}")
+    say(f"  {precision} H={hidden}: max |dlogit| per sequence {e_seq:.4g}, per token {e_tok:.4g}")
+    if precision == "bf16":
+        assert e_seq <= 2e-2 and e_tok <= 2e-2
+    else:
+        assert e_seq <= 1e-4 * max(np.abs(ref).max(), 1e-3) and e_tok <= 1e-4 * max(np.abs(ref_tok[real]).max(), 1e-3)
+    assert (tok[~real] == 0).all()
+    model.close()
