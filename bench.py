@@ -109,6 +109,72 @@ def latency_sweep(mt, ms, spec, model, calls):
     return res
 
 
+def qps_stream(ms, spec, model, rates, n_requests, seed=7):
+    """Open-loop request stream (Appendix E reports the 99th-percentile latency of the deployed model under a
+    request rate): single-sequence requests arrive as a Poisson process; the server loop takes whatever has
+    arrived (at most the model's batch size), copies the ids and masks from pinned host memory, runs one forward,
+    copies the logits back and waits for them.  A request's latency runs from its arrival to that moment, so it
+    includes queueing, both PCIe copies and the launch path."""
+    import numpy as np
+    import torch
+    B, S = spec.batch, spec.seq
+    pool_ids, pool_mask = [], []
+    for i in range(8):
+        ids, mask, _ = ms.make_inputs(spec, batch=B, batch_index=i)
+        pool_ids.append(ids)
+        pool_mask.append(mask)
+    pool_ids, pool_mask = np.concatenate(pool_ids), np.concatenate(pool_mask)         # 8*B single-sequence requests
+    h_ids = torch.empty((B, S), dtype=torch.int32).pin_memory()
+    h_mask = torch.empty((B, S), dtype=torch.int32).pin_memory()
+    d_ids = torch.empty((B, S), dtype=torch.int32, device="cuda")
+    d_mask = torch.empty((B, S), dtype=torch.int32, device="cuda")
+    out = torch.zeros((B, model.n_logits), dtype=torch.float32, device="cuda")
+    tok = torch.zeros((B, S, model.n_token_logits), dtype=torch.float32, device="cuda") if model.n_token_logits else None
+    h_out = torch.empty((B, model.n_logits), dtype=torch.float32).pin_memory()
+    h_tok = torch.empty((B, S, model.n_token_logits), dtype=torch.float32).pin_memory() if model.n_token_logits else None
+    np_ids, np_mask = h_ids.numpy(), h_mask.numpy()
+
+    def serve(req):
+        n = len(req)
+        np_ids[:n] = pool_ids[req]
+        np_mask[:n] = pool_mask[req]
+        d_ids[:n].copy_(h_ids[:n], non_blocking=True)
+        d_mask[:n].copy_(h_mask[:n], non_blocking=True)
+        forward(model, (d_ids[:n], d_mask[:n]), out[:n], tok[:n] if tok is not None else None)
+        h_out[:n].copy_(out[:n], non_blocking=True)
+        if tok is not None:
+            h_tok[:n].copy_(tok[:n], non_blocking=True)
+        torch.cuda.synchronize()
+
+    for n in (1, B):                                   # warm both ends of the batch range
+        for _ in range(20):
+            serve(np.arange(n))
+    res = []
+    rng = np.random.default_rng(seed)
+    for rate in rates:
+        arrive = np.cumsum(rng.exponential(1.0 / rate, n_requests))
+        which = rng.integers(0, len(pool_ids), n_requests)
+        done = np.empty(n_requests)
+        nxt, n_batches = 0, 0
+        t0 = time.perf_counter()
+        while nxt < n_requests:
+            now = time.perf_counter() - t0
+            hi = min(int(np.searchsorted(arrive, now, side="right")), nxt + B)
+            if hi == nxt:                                # nothing waiting: idle until the next arrival
+                while time.perf_counter() - t0 < arrive[nxt]:
+                    pass
+                continue
+            serve(which[nxt:hi])
+            done[nxt:hi] = time.perf_counter() - t0
+            nxt = hi
+            n_batches += 1
+        lat = (done - arrive) * 1e3
+        res.append({"offered_qps": float(rate), "served_qps": float(n_requests / done[-1]), "requests": int(n_requests),
+                    "mean_batch": float(n_requests / n_batches), "p50_ms": float(np.percentile(lat, 50)),
+                    "p99_ms": float(np.percentile(lat, 99)), "max_ms": float(lat.max())})
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -123,6 +189,9 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=64, help="sequences the CPU oracle is timed on")
     ap.add_argument("--latency-calls", type=int, default=2000,
                     help="config 'latency' only: forwards timed one by one (host clock, stream sync per call) per batch size")
+    ap.add_argument("--qps", default="", help="comma-separated request rates (requests/s): also serve an open-loop Poisson "
+                                              "stream of single-sequence requests at each rate and report p50/p99 latency")
+    ap.add_argument("--qps-requests", type=int, default=20000, help="requests per rate of --qps")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="before the warm-up, run one plain 256 MiB device copy (a kernel of known traffic to scale "
                          "hardware byte counters by); untimed")
@@ -313,6 +382,8 @@ def main():
     }
     if spec.name in ("latency", "industrial"):
         line["latency"] = latency_sweep(mt, ms, spec, model, args.latency_calls)
+    if args.qps:
+        line["qps_stream"] = qps_stream(ms, spec, model, [float(r) for r in args.qps.split(",")], args.qps_requests)
     print(json.dumps(line))
 
 
