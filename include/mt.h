@@ -70,8 +70,9 @@ typedef struct {
  * n_trunk_layers must equal max_t fork_layer (the shared depth of the "Layers" column of Table 2).
  * precision MT_BF16: matrices and embedding tables are stored as bfloat16 (round to nearest even
  * from the float32 blob), contractions run on bf16 matrix cores with float32 accumulation; it needs
- * hidden/heads == 64, hidden % 64 == 0 and ffn % 64 == 0.  MT_FP32_CHECK: everything float32 on
- * the vector ALUs, any shape, meant for validation.
+ * hidden/heads == 64, hidden % 64 == 0, ffn % 64 == 0 and max_seq <= 608 (the attention kernel keeps one
+ * sequence's keys and values of a head in the 160 KB LDS).  MT_FP32_CHECK: everything float32 on
+ * the vector ALUs, any shape, max_seq <= 4096, meant for validation.
  * max_batch*max_seq bounds the workspace; max_seq <= max_pos.
  */
 typedef struct {

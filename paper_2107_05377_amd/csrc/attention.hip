@@ -484,9 +484,14 @@ hipError_t launch_attention_bf16(const AttnGroup& g, int G, const int32_t* mask,
 {
     if (!mask && !(seq_start && seq_len)) return hipErrorInvalidValue;
     if (G <= 0 || B <= 0 || S <= 0) return hipSuccess;
-    if (H != A * 64 || G > kMaxGroup || S > 1024) return hipErrorInvalidValue;
+    if (H != A * 64 || G > kMaxGroup || S > kAttnBf16MaxSeq) return hipErrorInvalidValue;
     const int Sk = (S + 31) / 32 * 32;
     const size_t lds = (size_t)Sk * 128 + (size_t)64 * (Sk + 4) * 2 + (size_t)Sk * 4 + (size_t)(Sk / 32) * 4;
+    static_assert(kAttnBf16MaxSeq % 32 == 0 &&
+                      (size_t)kAttnBf16MaxSeq * 128 + (size_t)64 * (kAttnBf16MaxSeq + 4) * 2 + (size_t)kAttnBf16MaxSeq * 4 +
+                              (size_t)(kAttnBf16MaxSeq / 32) * 4 <= 160 * 1024 &&
+                      (size_t)(kAttnBf16MaxSeq + 32) * 260 + 512 > 160 * 1024,
+                  "kAttnBf16MaxSeq is the largest multiple of 32 whose keys and values fit the LDS");
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (lds > 64 * 1024 && !attr_set) {

@@ -70,6 +70,9 @@ hipError_t launch_build_row_map(const int32_t* mask, int B, int S, const RowMap&
 // out[b*S+s][:] = x[row_of[b*S+s]][:] or 0 (float32, H columns)
 hipError_t launch_unpack_rows(const float* x, const int32_t* row_of, int n_pos, int H, float* out, hipStream_t stream);
 
+// Longest sequence the bf16 attention kernel takes: the keys and values of one (sequence, head) are staged in
+// LDS as a whole, 260 bytes per key (rounded up to 32 keys) within the CU's 160 KB.
+constexpr int kAttnBf16MaxSeq = 608;
 struct AttnGroup {
     const void* qkv[kMaxGroup];   // [rows][3H]: Q | K | V
     void* ctx[kMaxGroup];         // [rows][H]

@@ -669,7 +669,7 @@ int mt_create(const mt_config* cfg, mt_model** out)
     if (cfg->gelu != MT_GELU_ERF && cfg->gelu != MT_GELU_TANH) return MT_ERR_CONFIG;
     if (!(cfg->ln_eps >= 0.0f)) return MT_ERR_CONFIG;
     if (cfg->precision == MT_BF16 &&
-        (cfg->hidden != cfg->heads * 64 || cfg->hidden % 64 != 0 || cfg->ffn % 64 != 0 || cfg->max_seq > 1024))
+        (cfg->hidden != cfg->heads * 64 || cfg->hidden % 64 != 0 || cfg->ffn % 64 != 0 || cfg->max_seq > kAttnBf16MaxSeq))
         return MT_ERR_CONFIG;
     if (cfg->precision == MT_FP32_CHECK && cfg->max_seq > 4096) return MT_ERR_CONFIG;
     int deepest = 0;

@@ -91,6 +91,7 @@ def test_config_validation():
         dataclasses.replace(base, hidden=770, heads=11),
         dataclasses.replace(base, seq=1024, max_pos=512),                             # max_seq > max_pos
         dataclasses.replace(base, tasks=()),
+        dataclasses.replace(base, seq=609, max_pos=1024),                             # bf16 attention keeps a sequence's keys in LDS
     ]
     for spec in bad:
         rc, h, _ = _create(spec)

@@ -6,6 +6,7 @@ have the same argmax (a consequence of the 2e-2 bound); ties break to the lowest
 Single operations: float32 outputs of the bf16 GEMM carry only accumulation-order error (inputs are
 bf16-representable on both sides), bf16 outputs add one rounding of relative size 2^-8.
 """
+import ctypes
 import dataclasses
 import sys
 
@@ -851,4 +852,58 @@ def test_token_heads_wide_rows(precision, hidden, heads):
     else:
         assert e_seq <= 1e-4 * max(np.abs(ref).max(), 1e-3) and e_tok <= 1e-4 * max(np.abs(ref_tok[real]).max(), 1e-3)
     assert (tok[~real] == 0).all()
+    model.close()
+
+
+# ------------------------------------------------------------------ the largest sizes the library accepts
+
+def test_bf16_longest_sequence():
+    """max_seq = 608 (the bf16 path's limit): one full-length sequence, one of a single token, one in between, with a
+    token-level task so that every row of the last layer is checked too."""
+    spec = ms.MTSpec("long", vocab=400, hidden=128, heads=2, ffn=256, max_pos=1024, n_trunk_layers=2,
+                     tasks=(ms.TaskSpec(2, 2, 3), ms.TaskSpec(1, 1, 2), ms.TaskSpec(2, 1, 5, token_level=True), ms.TaskSpec(0, 0, 2)),
+                     precision="bf16", batch=3, seq=608, len_lo=300, len_hi=600, input_seed=81, weights_seed=4246)
+
+    def edit(mask):
+        mask[0, :] = 1
+        mask[1, 1:] = 0
+    model, orc, ids, mask, ref, ref_tok = _token_case(spec, True, 0.05, edit)
+    got, tok = model.forward_tokens(dev(ids), dev(mask))
+    got, tok = got.cpu().numpy(), tok.cpu().numpy()
+    real = mask.astype(bool)
+    e_seq, e_tok = np.abs(got - ref).max(), np.abs(tok[real] - ref_tok[real]).max()
+    say(f"  S=608: max |dlogit| per sequence {e_seq:.4g}, per token {e_tok:.4g} over {int(real.sum())} tokens")
+    assert e_seq <= 2e-2 and e_tok <= 2e-2 and (tok[~real] == 0).all()
+    # one more sequence or one more position than the model was created for is refused on the host
+    with pytest.raises(mt.MTError):
+        model.forward(dev(np.zeros((4, 608), np.int32)), dev(np.ones((4, 608), np.int32)), task_mask=[1, 1, 0, 1])
+    with pytest.raises(mt.MTError):
+        model.forward(dev(np.zeros((3, 609), np.int32)), dev(np.ones((3, 609), np.int32)), task_mask=[1, 1, 0, 1])
+    model.close()
+    cfg = mt.make_config(dataclasses.replace(spec, seq=609))
+    h = ctypes.c_void_p()
+    assert mt.lib().mt_create(ctypes.byref(cfg), ctypes.byref(h)) == mt.MT_ERR_CONFIG
+
+
+def test_routing_at_the_largest_batch():
+    """1024 sequences (the routed call's limit), every sequence with its own random task set."""
+    spec = ms.MTSpec("wide_batch", vocab=300, hidden=128, heads=2, ffn=256, max_pos=8, n_trunk_layers=1,
+                     tasks=(ms.TaskSpec(1, 1, 2), ms.TaskSpec(0, 2, 3), ms.TaskSpec(1, 0, 4)),
+                     precision="bf16", batch=1024, seq=6, len_lo=1, len_hi=6, input_seed=82, weights_seed=4247)
+    tr, tri, tps = _params(spec, True, 0.05)
+    model = _load(spec, tr, tri, tps)
+    ids, mask, _ = ms.make_inputs(spec)
+    ref = oracle.Oracle(spec, tr, [p for p, _ in tps]).mt_forward(ids, mask)
+    got = model.forward(dev(ids), dev(mask)).cpu().numpy()
+    assert np.abs(got - ref).max() <= 2e-2
+    rng = np.random.default_rng(3)
+    route = (rng.random((1024, 3)) < 0.5).astype(np.uint8)
+    out = torch.full((1024, model.n_logits), -7.0, device="cuda")
+    model.forward_routed(dev(ids), dev(mask), route, out)
+    o = out.cpu().numpy()
+    for t in range(3):
+        sl = slice(model.logit_offset(t), model.logit_offset(t) + spec.tasks[t].n_classes)
+        want = route[:, t].astype(bool)
+        assert np.abs(o[want, sl] - ref[want, sl]).max() <= 2e-2
+        assert (o[~want, sl] == -7.0).all()
     model.close()
