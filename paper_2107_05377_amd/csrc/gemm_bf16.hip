@@ -560,7 +560,14 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
     if ((uint64_t)s.M * (uint64_t)s.lda * 2 >= (1ull << 32) || (uint64_t)s.N * (uint64_t)(s.ldw ? s.ldw : s.K) * 2 >= (1ull << 32))
         return hipErrorInvalidValue;
     int sel = g_gemm_bf16_tile_override;
-    if ((sel == 0 && s.M <= 256) || sel == 13 || s.n_sub > 1 || s.d_sub_rows) {                                   // few rows: weight-streaming kernel
+    // workgroups a 64x128 tiling of the launch would have
+    const long wg64 = (long)s.G * s.splits * ((s.M + 63) / 64) * ((s.N + 127) / 128);
+    // Few rows: the weight-streaming kernel, unless the launch still fills a good part of the chip with tiles (several
+    // problems with wide outputs, or 512 rows and more in all): measured at 64..256 rows, 1 and 8 problems, the tiled
+    // kernel is then 1.3x to 3.5x faster.  K-split launches and launches of fewer than 64 rows (half-empty tiles) stay
+    // with the streaming kernel.
+    const bool few_rows = s.M <= 256 && !(s.splits == 1 && s.M >= 64 && (wg64 >= 64 || (long)s.G * s.M >= 512));
+    if ((sel == 0 && few_rows) || sel == 13 || s.n_sub > 1 || s.d_sub_rows) {
         return launch_gemm_skinny_bf16(g, s, stream);
     }
     if (sel == 0) {
@@ -569,12 +576,13 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
         // number of 256x256 tiles the bound implies and errs towards the smaller tile when few.
         //   many tiles: 256x256 with 8 wavefronts (least L2 traffic per flop); the GELU epilogue's vector
         //   work instead prefers 8 wavefronts of 64x64 on a 256x128 tile, two workgroups per CU;
-        //   few tiles (single problem): 128x128 (wide outputs) or 64x128 (narrow outputs), two workgroups per CU,
+        //   few tiles (single problem): 128x128 (wide outputs) or 64x128 (narrow outputs, and wide ones of up to about
+        //   1024 rows, where 128x128 tiles leave most CUs without work), two workgroups per CU,
         //   slice-scope fragment buffers (4 MFMAs per K step cannot hide an LDS read behind one step).
         const long t256 = (long)s.G * s.splits * ((s.M + 255) / 256) * ((s.N + 255) / 256);
         const bool gelu = s.act == ACT_GELU_ERF || s.act == ACT_GELU_TANH;
         if (t256 >= 256) sel = gelu ? MT_GEMM_GELU_TILE : MT_GEMM_BIG_TILE;
-        else if (s.N >= 2048) sel = MT_GEMM_WIDE_TILE;
+        else if (s.N >= 2048 && wg64 > 400) sel = MT_GEMM_WIDE_TILE;
         else sel = MT_GEMM_NARROW_TILE;                      // narrow output: 64-row tiles double the tile count, so K needs less splitting
     }
     switch (sel) {
