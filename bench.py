@@ -188,7 +188,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=64, help="sequences the CPU oracle is timed on")
     ap.add_argument("--latency-calls", type=int, default=2000,
-                    help="config 'latency' only: forwards timed one by one (host clock, stream sync per call) per batch size")
+                    help="configs 'latency' and 'industrial': forwards timed one by one (host clock, stream sync per call) per "
+                         "batch size; 0 skips that sweep")
     ap.add_argument("--qps", default="", help="comma-separated request rates (requests/s): also serve an open-loop Poisson "
                                               "stream of single-sequence requests at each rate and report p50/p99 latency")
     ap.add_argument("--qps-requests", type=int, default=20000, help="requests per rate of --qps")
@@ -380,7 +381,7 @@ def main():
         "e2e_tflops_dense_padded_equivalent": e2e_tflops_dense,
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "weights_load_s": load_s,
     }
-    if spec.name in ("latency", "industrial"):
+    if spec.name in ("latency", "industrial") and args.latency_calls > 0:
         line["latency"] = latency_sweep(mt, ms, spec, model, args.latency_calls)
     if args.qps:
         line["qps_stream"] = qps_stream(ms, spec, model, [float(r) for r in args.qps.split(",")], args.qps_requests)

@@ -43,6 +43,15 @@ extern int g_gemm_bf16_tile_override;
 #ifndef MT_MAX_SPLITS_OUT
 #define MT_MAX_SPLITS_OUT 1
 #endif
+#ifndef MT_FEW_TILES
+#define MT_FEW_TILES 64
+#endif
+#ifndef MT_FEW_SPLITS_OUT
+#define MT_FEW_SPLITS_OUT 2
+#endif
+#ifndef MT_FEW_SPLITS_FFN2
+#define MT_FEW_SPLITS_FFN2 4
+#endif
 #ifndef MT_MAX_SPLITS_FFN2
 #define MT_MAX_SPLITS_FFN2 1
 #endif
@@ -354,17 +363,20 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& 
     const bool fuse_res = bf && MT_RESID_IN_GEMM;
     // A contraction with few output tiles (one problem, narrow output) is cut along K into equal
     // ranges whose float32 partial products the following LayerNorm adds up in a fixed order.
-    auto pick_splits = [&](int K, int N, int max_splits) {
+    auto pick_splits = [&](int K, int N, int max_splits, int max_splits_few) {
         if (!bf || n != 1 || io[0].scr->y_parts < 2) return 1;
         const long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
         if (tiles128 >= 256) return 1;
+        // a launch of at most MT_FEW_TILES 64x128 tiles leaves most CUs idle: there the K ranges pay
+        const long tiles64 = (long)((M + 63) / 64) * ((N + 127) / 128);
+        if (tiles64 <= MT_FEW_TILES) max_splits = max_splits_few;
         int sp = std::min(max_splits, io[0].scr->y_parts);
         while (sp > 1 && K % (64 * sp) != 0) sp >>= 1;
         return sp;
     };
 
     // output projection -> y (fp32 partial products), then LayerNorm(y + bias + residual) -> x1
-    const int sp_o = pick_splits(H, H, MT_MAX_SPLITS_OUT);
+    const int sp_o = pick_splits(H, H, MT_MAX_SPLITS_OUT, MT_FEW_SPLITS_OUT);
     for (int i = 0; i < n; ++i) {
         g.A[i] = ws + io[i].scr->ctx;
         g.W[i] = W + io[i].w->Wo;
@@ -404,7 +416,7 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& 
     L.gemm(MT_K_GEMM_FFN1, g, s, false);
 
     // FFN2 -> y (fp32 partial products), then LayerNorm(y + bias + residual) -> layer output
-    const int sp_f = pick_splits(F, H, MT_MAX_SPLITS_FFN2);
+    const int sp_f = pick_splits(F, H, MT_MAX_SPLITS_FFN2, MT_FEW_SPLITS_FFN2);
     for (int i = 0; i < n; ++i) {
         g.A[i] = ws + io[i].scr->u;
         g.W[i] = W + io[i].w->W2;
