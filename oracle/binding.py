@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import ctypes as C
+import os
 
 import numpy as np
 
@@ -31,7 +32,9 @@ def _ip(a):
 def lib():
     global _lib
     if _lib is None:
-        L = C.CDLL(build())
+        # ORC_LIB: a library built elsewhere from a (deliberately altered) copy of the source; the mutation audit of the
+        # pins uses it, nothing else does
+        L = C.CDLL(os.environ.get("ORC_LIB") or build())
         L.orc_layer_param_count.restype = C.c_int64
         L.orc_layer_param_count.argtypes = [C.c_int64, C.c_int64]
         L.orc_trunk_param_count.restype = C.c_int64
