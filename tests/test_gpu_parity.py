@@ -907,3 +907,35 @@ def test_routing_at_the_largest_batch():
         assert np.abs(o[want, sl] - ref[want, sl]).max() <= 2e-2
         assert (o[~want, sl] == -7.0).all()
     model.close()
+
+
+def test_tasks_are_added_while_serving():
+    """Section 5.1's modular update: a graph declared with room for five tasks serves with two of them loaded (the
+    others masked off), a third is loaded later without touching the first two, and an unloaded task is refused."""
+    spec = SMALL
+    tr, tri, tps = _params(spec, True, 0.05)
+    model = mt.Model(mt.make_config(spec))
+    model.load_params(-1, tr, len(tri))
+    for t in (0, 3):
+        model.load_params(t, tps[t][0], len(tps[t][1]))
+    ids, mask, _ = ms.make_inputs(spec)
+    ref = oracle.Oracle(spec, tr, [p for p, _ in tps]).mt_forward(ids, mask)
+    d_ids, d_mask = dev(ids), dev(mask)
+    with pytest.raises(mt.MTError):
+        model.forward(d_ids, d_mask)                                   # tasks 1, 2, 4 have no weights yet
+    first = torch.full((spec.batch, model.n_logits), 4.0, device="cuda")
+    model.forward(d_ids, d_mask, out=first, task_mask=[1, 0, 0, 1, 0])
+    first = first.cpu().numpy()
+    cols = lambda t: slice(model.logit_offset(t), model.logit_offset(t) + spec.tasks[t].n_classes)
+    for t in (0, 3):
+        assert np.abs(first[:, cols(t)] - ref[:, cols(t)]).max() <= 2e-2
+    for t in (1, 2, 4):
+        assert (first[:, cols(t)] == 4.0).all()
+    model.load_params(4, tps[4][0], len(tps[4][1]))                    # a new task arrives
+    second = torch.full((spec.batch, model.n_logits), 4.0, device="cuda")
+    model.forward(d_ids, d_mask, out=second, task_mask=[1, 0, 0, 1, 1])
+    second = second.cpu().numpy()
+    for t in (0, 3):
+        assert np.array_equal(second[:, cols(t)], first[:, cols(t)])   # bit for bit
+    assert np.abs(second[:, cols(4)] - ref[:, cols(4)]).max() <= 2e-2
+    model.close()
