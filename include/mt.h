@@ -178,6 +178,10 @@ int mt_forward_tokens(mt_model* m, const int32_t* d_input_ids, const int32_t* d_
  * written to d_out_logits[b][mt_logit_offset(t)..]; all other entries are left untouched.  batch <= 1024.
  * d_token_type_ids may be NULL.  Errors as mt_forward, and CONFIG when a wanted task has a token-level head (not
  * routed).  After this call mt_read_hidden serves trunk taps only.
+ * With more than one group the groups run side by side on up to four streams that the model owns (default
+ * priority; the first routed call creates them and their events, mt_destroy releases them): they wait for the
+ * trunk on hip_stream through an event and hip_stream waits for them before the call's work counts as done, so
+ * for the caller everything is still ordered on hip_stream and the call only enqueues.
  */
 int mt_forward_routed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask,
                       int32_t batch, int32_t seq, const uint8_t* h_route, float* d_out_logits, void* hip_stream);

@@ -128,6 +128,11 @@ struct mt_model {
     std::vector<ProfRec> prof;
     std::vector<hipEvent_t> event_pool;
     std::vector<RouteMapOff> route;
+    // per-sequence routing: groups of tasks run side by side on streams of the model's own (default priority),
+    // forked from and joined back into the caller's stream with events; created by the first routed forward
+    std::vector<hipStream_t> aux_streams;
+    std::vector<hipEvent_t> aux_join;
+    hipEvent_t aux_fork = nullptr;
 
     std::string err;
 };
@@ -814,6 +819,9 @@ void mt_destroy(mt_model* m)
         (void)hipEventDestroy(r.t1);
     }
     for (auto e : m->event_pool) (void)hipEventDestroy(e);
+    for (auto st : m->aux_streams) (void)hipStreamDestroy(st);
+    for (auto e : m->aux_join) (void)hipEventDestroy(e);
+    if (m->aux_fork) (void)hipEventDestroy(m->aux_fork);
     delete m;
 }
 
@@ -984,6 +992,36 @@ int mt_load_weights(mt_model* m, int32_t scope, const void* h_blob, size_t nbyte
 
 // The forward pass.  h_route == NULL: every enabled task (h_task_mask) runs on every sequence, branches interleaved
 // with the trunk.  h_route [batch][n_tasks]: per-sequence routing, a task runs on the sequences that ask for it.
+// Streams and events for running routed groups side by side; false (and nothing kept) if the runtime refuses.
+static bool ensure_aux_streams(mt_model* m)
+{
+    constexpr int kAux = 4;
+    if (!m->aux_streams.empty()) return true;
+    std::vector<hipStream_t> st;
+    std::vector<hipEvent_t> ev;
+    hipEvent_t fork = nullptr;
+    bool ok = hipEventCreateWithFlags(&fork, hipEventDisableTiming) == hipSuccess;
+    for (int j = 0; ok && j < kAux; ++j) {
+        hipStream_t s = nullptr;
+        hipEvent_t e = nullptr;
+        ok = hipStreamCreateWithFlags(&s, hipStreamNonBlocking) == hipSuccess;      // default priority
+        if (ok) st.push_back(s);
+        ok = ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
+        if (ok) ev.push_back(e);
+    }
+    if (!ok) {
+        (void)hipGetLastError();
+        for (auto s : st) (void)hipStreamDestroy(s);
+        for (auto e : ev) (void)hipEventDestroy(e);
+        if (fork) (void)hipEventDestroy(fork);
+        return false;
+    }
+    m->aux_streams = st;
+    m->aux_join = ev;
+    m->aux_fork = fork;
+    return true;
+}
+
 static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask,
                         int32_t batch, int32_t seq, const uint8_t* h_task_mask, const uint8_t* h_route, float* d_out_logits,
                         float* d_out_token_logits, void* hip_stream)
@@ -1108,7 +1146,7 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
 
     // ---- poolers and classifiers.  The pooler input stays float32-accurate in both modes: the bf16
     // path feeds the matrix cores with the [hi | lo] split of the first-token rows against [W | W].
-    auto run_heads = [&](const std::vector<int>& all, const RowMap& hrm, int HB, bool gathered, const int32_t* out_row) {
+    auto run_heads = [&](Launcher& L, const std::vector<int>& all, const RowMap& hrm, int HB, bool gathered, const int32_t* out_row) {
     std::vector<int> list;
     for (int t : all)
         if (m->tasks[t].head == MT_HEAD_SEQUENCE) list.push_back(t);
@@ -1185,25 +1223,48 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
     };
 
     if (!h_route) {
-        run_heads(enabled, rm, B, false, nullptr);
+        run_heads(L, enabled, rm, B, false, nullptr);
         run_token_heads(enabled);
     } else {
         // ---- per-sequence routing: tasks wanted by the same set of sequences form a group; the group's sequences are
         // gathered from each task's tap into a padding-free row order of their own, on which the task's layers,
         // pooler and classifier run exactly as on a whole batch; logits land in the rows of the chosen sequences.
+        struct Group {
+            std::vector<int> tasks;
+            int t0;
+        };
+        std::vector<Group> groups;
         std::vector<char> done(T, 0);
         for (int t0 : enabled) {
             if (done[t0]) continue;
-            std::vector<int> grp_tasks;
+            Group grp;
+            grp.t0 = t0;
             for (int t : enabled) {
                 if (done[t]) continue;
                 bool same = true;
                 for (int b = 0; b < B && same; ++b) same = (h_route[(size_t)b * T + t] != 0) == (h_route[(size_t)b * T + t0] != 0);
                 if (same) {
-                    grp_tasks.push_back(t);
+                    grp.tasks.push_back(t);
                     done[t] = 1;
                 }
             }
+            groups.push_back(std::move(grp));
+        }
+        // Groups touch disjoint scratch (per task) and disjoint logits, and only read the trunk's taps and the batch's
+        // row map: with more than one group they are issued round-robin to the model's own streams, which wait for
+        // the trunk through one event and are joined back into the caller's stream at the end.  Per-launch timing
+        // (mt_profile_enable) keeps everything on the caller's stream.
+        const bool side = groups.size() > 1 && !m->profiling && ensure_aux_streams(m);
+        const int n_side = side ? (int)std::min(groups.size(), m->aux_streams.size()) : 0;
+        if (side) {
+            L.check(hipEventRecord(m->aux_fork, L.st));
+            for (int j = 0; j < n_side; ++j) L.check(hipStreamWaitEvent(m->aux_streams[j], m->aux_fork, 0));
+        }
+        for (size_t gi = 0; gi < groups.size(); ++gi) {
+            const std::vector<int>& grp_tasks = groups[gi].tasks;
+            const int t0 = groups[gi].t0;
+            Launcher LS{m, side ? m->aux_streams[gi % n_side] : L.st};
+            Launcher& GL = side ? LS : L;
             RouteIdx idx;
             int nb = 0;
             for (int b = 0; b < B; ++b)
@@ -1211,15 +1272,15 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
             const RouteMapOff& ro = m->route[t0];
             RowMap crm{(int32_t*)(ws + ro.n), (int32_t*)(ws + ro.src), nullptr, (int32_t*)(ws + ro.start), (int32_t*)(ws + ro.len)};
             int32_t* c_seq = (int32_t*)(ws + ro.seq);
-            L.begin(MT_K_EMBED);
-            L.check(launch_route_map(idx, nb, rm.seq_start, rm.seq_len, crm.seq_start, crm.seq_len, crm.src, c_seq, crm.n_rows, L.st));
+            GL.begin(MT_K_EMBED);
+            GL.check(launch_route_map(idx, nb, rm.seq_start, rm.seq_len, crm.seq_start, crm.seq_len, crm.src, c_seq, crm.n_rows, GL.st));
             for (int t : grp_tasks) {
                 const int tap = m->tap_of_layer[m->tasks[t].fork_layer];
-                L.check(launch_route_gather((const float*)(ws + m->tap_f[tap]), bf ? (const void*)(ws + m->tap_b[tap]) : nullptr,
-                                            (float*)(ws + m->task_xf[t]), bf ? (void*)(ws + m->task_xb[t]) : nullptr, crm.src, crm.n_rows,
-                                            nb * S, H, 2, L.st));
+                GL.check(launch_route_gather((const float*)(ws + m->tap_f[tap]), bf ? (const void*)(ws + m->tap_b[tap]) : nullptr,
+                                             (float*)(ws + m->task_xf[t]), bf ? (void*)(ws + m->task_xb[t]) : nullptr, crm.src, crm.n_rows,
+                                             nb * S, H, 2, GL.st));
             }
-            L.end();
+            GL.end();
             int gy = 0;
             for (int t : grp_tasks) gy = std::max(gy, m->tasks[t].n_layers);
             for (int stage = 0; stage < gy; ++stage) {
@@ -1238,14 +1299,21 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
                 }
                 for (size_t lo = 0; lo < full.size(); lo += kMaxGroup) {
                     std::vector<LayerIO> part(full.begin() + lo, full.begin() + std::min(full.size(), lo + (size_t)kMaxGroup));
-                    run_layer_group(L, part, crm, nb, S);
+                    run_layer_group(GL, part, crm, nb, S);
                 }
                 for (size_t lo = 0; lo < last.size(); lo += kMaxGroup) {
                     std::vector<LastIO> part(last.begin() + lo, last.begin() + std::min(last.size(), lo + (size_t)kMaxGroup));
-                    run_last_layer_group(L, part, crm, nb, S);
+                    run_last_layer_group(GL, part, crm, nb, S);
                 }
             }
-            run_heads(grp_tasks, crm, nb, true, c_seq);
+            run_heads(GL, grp_tasks, crm, nb, true, c_seq);
+            if (side) L.check(LS.first_err);
+        }
+        if (side) {
+            for (int j = 0; j < n_side; ++j) {
+                L.check(hipEventRecord(m->aux_join[j], m->aux_streams[j]));
+                L.check(hipStreamWaitEvent(L.st, m->aux_join[j], 0));
+            }
         }
     }
 
