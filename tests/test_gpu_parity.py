@@ -939,3 +939,30 @@ def test_tasks_are_added_while_serving():
         assert np.array_equal(second[:, cols(t)], first[:, cols(t)])   # bit for bit
     assert np.abs(second[:, cols(4)] - ref[:, cols(4)]).max() <= 2e-2
     model.close()
+
+
+@pytest.mark.parametrize("which", ["fp32", "bf16"])
+def test_a_sequence_without_real_tokens_disturbs_nothing(which):
+    """A sequence whose mask is all zero breaks the precondition (its own outputs are unspecified), but it has no rows
+    in the padding-free order and must leave every other sequence's logits as they are; a batch of such sequences
+    only has to come back."""
+    spec = TOKF if which == "fp32" else TOKB
+    tr, tri, tps = _params(spec, True, 0.1 if which == "fp32" else 0.05)
+    model = _load(spec, tr, tri, tps)
+    ids, mask, _ = ms.make_inputs(spec)
+    ref, ref_tok = oracle.Oracle(spec, tr, [p for p, _ in tps]).mt_forward(ids, mask, want_tokens=True)
+    dead = mask.copy()
+    dead[1, :] = 0
+    got, tok = model.forward_tokens(dev(ids), dev(dead))
+    got, tok = got.cpu().numpy(), tok.cpu().numpy()
+    keep = [b for b in range(spec.batch) if b != 1]
+    tol = 1e-4 * max(np.abs(ref).max(), np.abs(ref_tok).max()) if which == "fp32" else 2e-2
+    real = mask[keep].astype(bool)
+    assert np.abs(got[keep] - ref[keep]).max() <= tol
+    assert np.abs(tok[keep][real] - ref_tok[keep][real]).max() <= tol
+    assert (tok[1] == 0).all()                                # no kept row: the token head writes zeros there
+    model.forward_tokens(dev(ids), dev(np.zeros_like(mask)))   # no row at all
+    torch.cuda.synchronize()
+    again, _ = model.forward_tokens(dev(ids), dev(mask))       # and the model still serves
+    assert np.abs(again.cpu().numpy() - ref).max() <= tol
+    model.close()
