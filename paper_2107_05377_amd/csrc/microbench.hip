@@ -1,7 +1,9 @@
 // Matrix-core rate of the chip as it runs here, for judging the contraction kernels against more than the
 // data-sheet figure: every SIMD issues back-to-back, independent v_mfma_f32_32x32x16_bf16 on registers only
 // (no LDS, no memory), two wavefronts per SIMD.  The result moves with the clock the power management
-// grants under full matrix load, which is below the boost clock the data-sheet peak assumes.
+// grants under full matrix load, which is below the boost clock the data-sheet peak assumes, and that clock
+// depends on how many operand bits toggle: the operands are pseudo-random bfloat16 values in +-[0.5, 1), like
+// activations and weights (with small constant integers the same loop runs 25-30 % faster).
 #include "kernels.h"
 #include "device_util.h"
 
@@ -20,14 +22,22 @@ __global__ __launch_bounds__(MB_THREADS) void mfma_rate_kernel(float* __restrict
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
     bf16x8 a[4], b[2];
+    auto value = [](unsigned key) {            // a bfloat16 with random sign and mantissa, exponent of 0.5
+        unsigned h = key * 2654435761u;
+        h ^= h >> 13;
+        h *= 0x5bd1e995u;
+        h ^= h >> 15;
+        const unsigned bits = ((h & 0x807fu) | 0x3f00u) << 16;
+        return (__bf16)__uint_as_float(bits);
+    };
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) a[i][e] = (__bf16)(float)((threadIdx.x + i + e) & 7);
+        for (int e = 0; e < 8; ++e) a[i][e] = value((blockIdx.x * MB_THREADS + threadIdx.x) * 64u + i * 8 + e);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) b[i][e] = (__bf16)(float)((threadIdx.x * 3 + i + e) & 3);
+        for (int e = 0; e < 8; ++e) b[i][e] = value((blockIdx.x * MB_THREADS + threadIdx.x) * 64u + 32 + i * 8 + e);
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int i = 0; i < MB_ACC; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[i & 1], a[i >> 1], acc[i], 0, 0, 0);
