@@ -258,3 +258,43 @@ def test_pack_blob_layout():
     assert blob[:4] == b"MTW1" and len(blob) == 16 + 20
     assert np.frombuffer(blob[4:16], dtype="<i4").tolist() == [3, 7, 0]
     assert np.frombuffer(blob[16:], dtype="<f4").tolist() == [0, 1, 2, 3, 4]
+
+
+def test_random_task_tables_host_bookkeeping():
+    """Random task tables (forks, depths, class counts, head kinds): the library's layer count equals the oracle's
+    overhead formula (Section 4.1), the wavefront step count is max over tasks of fork + own layers, logit offsets
+    follow the order of the tasks inside each kind of row, and a checkpoint blob of the canonical size is what the
+    loader asks for (checked through its size error, no device needed)."""
+    import oracle
+    rng = np.random.default_rng(2107)
+    L = mt.lib()
+    for _ in range(40):
+        depth = int(rng.integers(0, 7))
+        n_tasks = int(rng.integers(1, 9))
+        tasks = [ms.TaskSpec(int(rng.integers(0, depth + 1)), int(rng.integers(0, 4)), int(rng.integers(1, 9)),
+                             token_level=bool(rng.integers(0, 2))) for _ in range(n_tasks)]
+        k = int(rng.integers(0, n_tasks))
+        tasks[k] = ms.TaskSpec(depth, tasks[k].n_layers, tasks[k].n_classes, token_level=tasks[k].token_level)
+        spec = ms.MTSpec("rnd", vocab=64, hidden=64, heads=2, ffn=128, max_pos=16, n_trunk_layers=depth, tasks=tuple(tasks),
+                         precision="fp32", batch=2, seq=8, len_lo=1, len_hi=8)
+        rc, h, _ = _create(spec)
+        assert rc == mt.MT_OK, tasks
+        assert L.mt_layer_count(h) == oracle.overhead([(t.fork_layer, t.n_layers) for t in tasks])
+        assert L.mt_schedule_steps(h, None) == max(t.fork_layer + t.n_layers for t in tasks)
+        mask = (C.c_uint8 * n_tasks)(*[int(rng.integers(0, 2)) for _ in range(n_tasks)])
+        on = [t for t, m in zip(tasks, mask) if m]
+        assert L.mt_schedule_steps(h, mask) == (max(t.fork_layer + t.n_layers for t in on) if on else 0)
+        assert L.mt_n_logits(h) == spec.n_logits and L.mt_n_token_logits(h) == spec.n_token_logits
+        for t, task in enumerate(tasks):
+            good, bad = (L.mt_token_logit_offset, L.mt_logit_offset) if task.token_level else (L.mt_logit_offset, L.mt_token_logit_offset)
+            assert good(h, t) == spec.logit_offset(t) and bad(h, t) == mt.MT_ERR_CONFIG
+        # blob sizes: one float too many is refused, and the message names the canonical size
+        fake = C.c_void_p(0x10000)
+        assert L.mt_bind(h, fake, 1 << 40, fake, 1 << 40) == mt.MT_OK
+        t = int(rng.integers(0, n_tasks))
+        flat, idx = ms.make_task_params(spec, t)
+        blob = mt.pack_blob(t, len(idx), np.concatenate([flat, np.zeros(1, np.float32)]))
+        buf = C.create_string_buffer(blob, len(blob))
+        assert L.mt_load_weights(h, t, C.cast(buf, C.c_void_p), len(blob), None) == mt.MT_ERR_BLOB
+        assert str(16 + 4 * flat.size).encode() in L.mt_last_error(h)
+        L.mt_destroy(h)
