@@ -124,7 +124,9 @@ int mt_share_weights(mt_model* m, const mt_model* owner);
  *   task scope : y_t layers in that order, then Wp[H,H] bp[H] Wc[C,H] bc[C]
  *                (MT_HEAD_TOKEN: y_t layers, then Wc[C,H] bc[C] only)
  * The call converts on the host, copies on `hip_stream` and waits for the copy, so h_blob may be
- * released on return.  Errors: NULL, STATE (not bound), BLOB (magic/scope/size mismatch), HIP.
+ * released on return.  The copy is ordered only against work on `hip_stream`: a forward pass that reads this scope
+ * on another stream (a replica's, say) must have finished, or must have the task masked off, while its weights are
+ * replaced.  Errors: NULL, STATE (not bound), BLOB (magic/scope/size mismatch), HIP.
  */
 int mt_load_weights(mt_model* m, int32_t scope, const void* h_blob, size_t nbytes, void* hip_stream);
 
