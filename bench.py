@@ -63,6 +63,23 @@ def forward(model, batch, out=None, out_tokens=None):
     return model.forward(*batch, out=out)
 
 
+def host_description():
+    """Logical CPUs visible to this process and the processor's model name, for reading the CPU baseline."""
+    model = ""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count()
+    return {"logical_cpus": os.cpu_count(), "usable_cpus": usable, "model": model}
+
+
 def stored_traffic(workload_name):
     """HBM-side bytes per launch of the tiled contraction kernel from the committed counter summary, or None
     when there is none for this workload or the kernel's source has changed since the counters were taken."""
@@ -269,6 +286,15 @@ def main():
     # per-kernel figures below are measured on, so that no other batch's kernels share the chip with them)
     run_steps(min(args.warmup, 3), 1)
     ms_serial = run_steps(args.steps, 1) / args.steps
+    # ... and the same steps once more with an event pair around every single forward: median and minimum
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    torch.cuda.synchronize()
+    marks[0].record(stream)
+    for i in range(args.steps):
+        forward(model, batches[i % n_batches], out, tok_outs[0])
+        marks[i + 1].record(stream)
+    torch.cuda.synchronize()
+    per_step = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)])
 
     # ---- per-kernel durations from HIP events around every launch, same stream, same steps
     model.profile_enable(True)
@@ -354,7 +380,7 @@ def main():
             n_done += n
         cpu = {"value": n_done / dt, "unit": "sequences/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"the first {n_done} sequences of the same workload's batches, one pass, {dt:.1f} s",
-               "max_abs_dlogit_vs_gpu": err}
+               "max_abs_dlogit_vs_gpu": err, "host": host_description()}
         # the same oracle on one thread, on a smaller sample
         n1 = max(1, min(4, n_done))
         all_threads = oracle.num_threads()
@@ -377,6 +403,7 @@ def main():
                    "layers_on_first_token_only": n_first, "real_tokens_per_batch": rows, "padding_skipped": True,
                    "batches_in_flight": n_fly},
         "ms_per_step_one_in_flight": ms_serial, "sequences_per_s_one_in_flight": B / (ms_serial * 1e-3),
+        "ms_per_step_one_in_flight_median": float(np.median(per_step)), "ms_per_step_one_in_flight_min": float(per_step.min()),
         "e2e_tflops_executed": e2e_tflops, "e2e_frac_of_peak": e2e_tflops / peak,
         "e2e_tflops_dense_padded_equivalent": e2e_tflops_dense,
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "weights_load_s": load_s,
