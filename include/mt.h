@@ -114,8 +114,7 @@ int mt_bind(mt_model* m, void* d_weights, size_t weight_bytes, void* d_workspace
 int mt_share_weights(mt_model* m, const mt_model* owner);
 
 /*
- * Load one checkpoint into the graph ("load weights from multiple model checkpoints into one
- * computation graph", Section 3.3).  scope -1 = embeddings + trunk layers, scope t >= 0 = task t's
+ * Merge one checkpoint into the shared graph (Section 3.3, Model Merging).  scope -1 = embeddings + trunk layers, scope t >= 0 = task t's
  * layers, pooler and classifier; loading one task never touches another's memory (the per-task
  * update of Section 5.1).  h_blob is a little-endian HOST buffer:
  *     char magic[4] = "MTW1"; int32 scope; int32 n_tensors; int32 reserved(0);  then float32 data
@@ -217,7 +216,9 @@ const char* mt_error_name(int code);
  *              sequence is computed (the pooler reads nothing else): position 0 holds it, the rest is 0;
  *              for a task without own layers this is its trunk tap (`layer` ignored); for a token-level task
  *              the whole state (padded positions 0)
- * into d_out on `hip_stream`.  For validation.  Errors: NULL, STATE, SHAPE.
+ * into d_out on `hip_stream`.  For validation.  Errors: NULL, SHAPE, STATE (no forward pass has run; the task
+ * was masked off in the last one; the last one stopped the trunk below `layer` because no deeper task was
+ * enabled, or had no task enabled at all).
  */
 int mt_read_hidden(mt_model* m, int32_t task, int32_t layer, float* d_out, size_t out_bytes, void* hip_stream);
 
@@ -287,7 +288,9 @@ int mt_op_layernorm(const float* d_x, const float* d_gamma, const float* d_beta,
                     void* d_out_bf16, int32_t M, int32_t H, void* hip_stream);
 
 /* Tuning aid for benchmarks: force one bf16 GEMM tile configuration for all later launches in this
- * process (0 = choose by shape, the default; 1..12 = a fixed tile configuration, 13 = the few-row kernel).  Returns the previous value. */
+ * process (0 = choose by shape, the default; 1..26 except 13 = a fixed tile configuration, 13 = the few-row kernel;
+ * any other value resets to 0).  One process-wide setting, not thread-safe: for single-threaded tuning sweeps
+ * only, never set while forward passes are being enqueued from other threads.  Returns the previous value. */
 int mt_debug_set_gemm_tile(int32_t sel);
 
 /*

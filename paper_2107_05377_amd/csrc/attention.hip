@@ -493,12 +493,10 @@ hipError_t launch_attention_bf16(const AttnGroup& g, int G, const int32_t* mask,
                       (size_t)(kAttnBf16MaxSeq + 32) * 260 + 512 > 160 * 1024,
                   "kAttnBf16MaxSeq is the largest multiple of 32 whose keys and values fit the LDS");
     if (lds > 160 * 1024) return hipErrorInvalidValue;
-    static bool attr_set = false;
-    if (lds > 64 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)attention_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           160 * 1024);
+    static std::atomic<uint64_t> lds_raised{0};
+    if (lds > 64 * 1024) {
+        hipError_t e = ensure_dynamic_lds((const void*)attention_bf16_kernel, 160 * 1024, lds_raised);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     dim3 grid((S + 127) / 128, A, B * G), block(256);
     const float scale_log2e = (1.0f / sqrtf(64.0f)) * kLog2e;

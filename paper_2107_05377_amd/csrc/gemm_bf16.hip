@@ -109,23 +109,6 @@ __device__ __forceinline__ void wait_slices(int y)
     wait_vmcnt<0>();
 }
 
-// Fast GELU(x) = x * Phi(x) for the bf16 epilogue: erf through the Abramowitz-Stegun 7.1.26 rational
-// (|error| <= 1.5e-7 before rounding), far below the bf16 rounding of the stored result.
-__device__ __forceinline__ float gelu_erf_fast(float x)
-{
-    const float ax = fabsf(x);
-    const float y = ax * 0.70710678118654752f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, y, 1.0f));
-    float p = fmaf(1.061405429f, t, -1.453152027f);
-    p = fmaf(p, t, 1.421413741f);
-    p = fmaf(p, t, -0.284496736f);
-    p = fmaf(p, t, 0.254829592f);
-    p *= t;
-    const float e = __builtin_amdgcn_exp2f(-y * y * 1.4426950408889634f);
-    const float erf_abs = fmaf(-p, e, 1.0f);          // erf(|x|/sqrt2)
-    return 0.5f * fmaf(ax, erf_abs, x);               // 0.5*(x + |x| erf(|x|/sqrt2)) = x*Phi(x)
-}
-
 template <int ACT>
 __device__ __forceinline__ float epi_act(float v)
 {
@@ -517,11 +500,10 @@ hipError_t launch_one(const GemmGroup& g, const GemmShape& s, hipStream_t stream
     const int total = s.G * s.splits * tiles_m * tiles_n;
     if (s.K % (BK * s.splits) != 0) return hipErrorInvalidValue;
     auto kfn = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, STAGES, MINW, OUT_F32, ACT, FS>;
-    static bool attr_set = false;
-    if (Cfg::LDS_BYTES > 64 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+    static std::atomic<uint64_t> lds_raised{0};          // one per instantiation
+    if (Cfg::LDS_BYTES > 64 * 1024) {
+        hipError_t e = ensure_dynamic_lds((const void*)kfn, Cfg::LDS_BYTES, lds_raised);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     hipLaunchKernelGGL(kfn, dim3(total), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, g, s, tiles_n);
     return hipGetLastError();

@@ -20,25 +20,10 @@ constexpr int SK_BM = 32, SK_BN = 32;
 constexpr int SK_UNROLL = 8;          // K steps (of 16) in flight per wavefront
 constexpr int SK_LDP = SK_BN + 4;     // padded row of the float32 partial tile in LDS
 
-__device__ __forceinline__ float skinny_gelu_erf(float x)
-{
-    // erf through the Abramowitz-Stegun 7.1.26 rational, |error| <= 1.5e-7
-    const float ax = fabsf(x);
-    const float y = ax * 0.70710678118654752f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, y, 1.0f));
-    float p = fmaf(1.061405429f, t, -1.453152027f);
-    p = fmaf(p, t, 1.421413741f);
-    p = fmaf(p, t, -0.284496736f);
-    p = fmaf(p, t, 0.254829592f);
-    p *= t;
-    const float e = __builtin_amdgcn_exp2f(-y * y * 1.4426950408889634f);
-    return 0.5f * fmaf(ax, fmaf(-p, e, 1.0f), x);
-}
-
 __device__ __forceinline__ float skinny_act(float v, int act)
 {
     switch (act) {
-        case ACT_GELU_ERF: return skinny_gelu_erf(v);
+        case ACT_GELU_ERF: return gelu_erf_fast(v);
         case ACT_GELU_TANH: return gelu_tanh(v);
         case ACT_TANH: return tanhf(v);
         default: return v;

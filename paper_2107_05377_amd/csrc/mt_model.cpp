@@ -118,10 +118,12 @@ struct mt_model {
 
     unsigned char* d_w = nullptr;
     unsigned char* d_ws = nullptr;
+    unsigned char* ws_act = nullptr;   // workspace of the forward pass being enqueued / enqueued last (d_ws or the static scratch)
     bool trunk_loaded = false;
     std::vector<char> task_loaded;
 
     int last_B = 0, last_S = 0;
+    int last_depth = -1;                 // trunk layers the last forward pass evaluated; -1: it evaluated nothing
     std::vector<char> last_enabled;
 
     bool profiling = false;
@@ -330,7 +332,7 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& 
     const int H = m->cfg.hidden, F = m->cfg.ffn, A = m->cfg.heads, M = B * S;
     const int n = (int)io.size();
     unsigned char* W = m->d_w;
-    unsigned char* ws = m->d_ws;
+    unsigned char* ws = m->ws_act;
     const bool bf = m->bf16;
     const int gelu_act = m->cfg.gelu == MT_GELU_TANH ? ACT_GELU_TANH : ACT_GELU_ERF;
 
@@ -462,7 +464,7 @@ void run_last_layer_group(Launcher& L, const std::vector<LastIO>& io, const RowM
     const int H = m->cfg.hidden, F = m->cfg.ffn, A = m->cfg.heads, M = B * S;
     const int n = (int)io.size();
     unsigned char* W = m->d_w;
-    unsigned char* ws = m->d_ws;
+    unsigned char* ws = m->ws_act;
     const bool bf = m->bf16;
     const size_t esz = m->esz;
     const int gelu_act = m->cfg.gelu == MT_GELU_TANH ? ACT_GELU_TANH : ACT_GELU_ERF;
@@ -1024,7 +1026,7 @@ static bool ensure_aux_streams(mt_model* m)
 
 static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask,
                         int32_t batch, int32_t seq, const uint8_t* h_task_mask, const uint8_t* h_route, float* d_out_logits,
-                        float* d_out_token_logits, void* hip_stream)
+                        float* d_out_token_logits, void* hip_stream, unsigned char* ws_other = nullptr)
 {
     if (!m) return MT_ERR_NULL;
     if (!d_input_ids || !d_attn_mask) return fail(m, MT_ERR_NULL, "mt_forward: null device pointer");
@@ -1060,11 +1062,14 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
     std::fill(m->last_enabled.begin(), m->last_enabled.end(), 0);
     m->last_B = batch;
     m->last_S = seq;
+    m->last_depth = -1;                 // no trunk state of this call exists (yet)
+    m->ws_act = ws_other ? ws_other : m->d_ws;
     if (enabled.empty()) return MT_OK;
+    m->last_depth = depth;
 
     const int B = batch, S = seq, H = m->cfg.hidden;
     unsigned char* W = m->d_w;
-    unsigned char* ws = m->d_ws;
+    unsigned char* ws = m->ws_act;
     const bool bf = m->bf16;
     Launcher L{m, static_cast<hipStream_t>(hip_stream)};
 
@@ -1356,30 +1361,33 @@ int mt_read_hidden(mt_model* m, int32_t task, int32_t layer, float* d_out, size_
 {
     if (!m) return MT_ERR_NULL;
     if (!d_out) return fail(m, MT_ERR_NULL, "mt_read_hidden: null output");
-    if (!m->d_ws || m->last_B == 0) return fail(m, MT_ERR_STATE, "mt_read_hidden: no forward pass has run");
+    if (!m->ws_act || m->last_B == 0) return fail(m, MT_ERR_STATE, "mt_read_hidden: no forward pass has run");
     const size_t bytes = (size_t)m->last_B * m->last_S * m->cfg.hidden * 4;
     if (out_bytes < bytes) return fail(m, MT_ERR_SHAPE, "mt_read_hidden: need %zu bytes", bytes);
     const unsigned char* src;
     if (task < 0) {
         if (layer < 0 || layer > m->cfg.n_trunk_layers || m->tap_of_layer[layer] < 0)
             return fail(m, MT_ERR_SHAPE, "mt_read_hidden: no task forks at trunk layer %d", layer);
-        src = m->d_ws + m->tap_f[m->tap_of_layer[layer]];
+        if (layer > m->last_depth)
+            return fail(m, MT_ERR_STATE, "mt_read_hidden: the last forward pass ran the trunk to layer %d only, not to layer %d",
+                        m->last_depth, layer);
+        src = m->ws_act + m->tap_f[m->tap_of_layer[layer]];
     } else {
         if (task >= (int)m->tasks.size()) return fail(m, MT_ERR_SHAPE, "mt_read_hidden: task %d out of range", task);
         if (!m->last_enabled[task]) return fail(m, MT_ERR_STATE, "mt_read_hidden: task %d was not computed", task);
         const mt_task_desc& d = m->tasks[task];
         if (d.n_layers > 0 && d.head == MT_HEAD_TOKEN) {
-            src = m->d_ws + m->task_xf[task];
+            src = m->ws_act + m->task_xf[task];
         } else if (d.n_layers > 0) {   // only the first-token rows of a branch's final state exist
-            hipError_t e = launch_place_first_rows((const float*)(m->d_ws + m->task_cls[task].out_f), m->last_B, m->last_S,
+            hipError_t e = launch_place_first_rows((const float*)(m->ws_act + m->task_cls[task].out_f), m->last_B, m->last_S,
                                                    m->cfg.hidden, d_out, static_cast<hipStream_t>(hip_stream));
             if (e != hipSuccess) return fail(m, MT_ERR_HIP, "mt_read_hidden: %s", hipGetErrorString(e));
             return MT_OK;
         } else {
-            src = m->d_ws + m->tap_f[m->tap_of_layer[d.fork_layer]];
+            src = m->ws_act + m->tap_f[m->tap_of_layer[d.fork_layer]];
         }
     }
-    hipError_t e = launch_unpack_rows((const float*)src, (const int32_t*)(m->d_ws + m->rm_rowof), m->last_B * m->last_S, m->cfg.hidden,
+    hipError_t e = launch_unpack_rows((const float*)src, (const int32_t*)(m->ws_act + m->rm_rowof), m->last_B * m->last_S, m->cfg.hidden,
                                       d_out, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(m, MT_ERR_HIP, "mt_read_hidden: %s", hipGetErrorString(e));
     return MT_OK;

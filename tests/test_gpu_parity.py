@@ -966,3 +966,33 @@ def test_a_sequence_without_real_tokens_disturbs_nothing(which):
     again, _ = model.forward_tokens(dev(ids), dev(mask))       # and the model still serves
     assert np.abs(again.cpu().numpy() - ref).max() <= tol
     model.close()
+
+
+def test_read_hidden_refuses_states_the_last_forward_did_not_write():
+    """A trunk tap is readable only if the last forward pass ran the trunk that deep: with the deeper tasks masked
+    off the trunk stops at the deepest enabled fork, and with no task enabled nothing runs at all."""
+    spec = MINI                                         # forks at layers 1, 3, 2, 0
+    tr, tri, tps = _params(spec, True, 0.1)
+    model = _load(spec, tr, tri, tps)
+    ids, mask, _ = ms.make_inputs(spec)
+    _, hidden = oracle.Oracle(spec, tr, [p for p, _ in tps]).mt_forward(ids, mask, want_hidden=True)
+    real = mask.astype(bool)
+    model.forward(dev(ids), dev(mask))
+    for layer in (0, 1, 2, 3):
+        h = model.read_hidden(-1, layer, *ids.shape).cpu().numpy()
+        assert np.abs(h[real] - hidden[layer][real]).max() <= 2e-5
+    model.forward(dev(ids), dev(mask), task_mask=[1, 0, 0, 1])       # deepest enabled fork: layer 1
+    h = model.read_hidden(-1, 1, *ids.shape).cpu().numpy()
+    assert np.abs(h[real] - hidden[1][real]).max() <= 2e-5
+    for layer in (2, 3):
+        with pytest.raises(mt.MTError) as ei:
+            model.read_hidden(-1, layer, *ids.shape)
+        assert ei.value.code == mt.MT_ERR_STATE
+    with pytest.raises(mt.MTError) as ei:
+        model.read_hidden(1, 0, *ids.shape)                           # task 1 was masked off
+    assert ei.value.code == mt.MT_ERR_STATE
+    model.forward(dev(ids), dev(mask), task_mask=[0, 0, 0, 0])       # nothing enabled: nothing was computed
+    with pytest.raises(mt.MTError) as ei:
+        model.read_hidden(-1, 0, *ids.shape)
+    assert ei.value.code == mt.MT_ERR_STATE
+    model.close()
