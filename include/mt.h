@@ -148,6 +148,28 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
                const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream);
 
 /*
+ * mt_forward for callers that cannot allocate device memory or let a library do so on their behalf: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-identical logits, but the workspace is NOT the arena given to mt_bind: it is a fixed array of
+ * MT_STATIC_SCRATCH_BYTES of device memory inside the library's code object (every GPU the library is loaded on
+ * holds one copy until the process ends; its address is looked up once per device).  The call makes no
+ * hipMalloc / hipFree or other allocating call; mt_bind must still have attached the weight arena (its workspace
+ * argument is not touched by this call).
+ *   - Limit: mt_workspace_bytes(m) <= MT_STATIC_SCRATCH_BYTES, i.e. create the model with max_batch x max_seq
+ *     small enough (at BERT-base width with 8 two-layer tasks on 6 shared layers: 2 x 64 tokens); larger models get
+ *     MT_ERR_SHAPE with a message that names both sizes, and nothing is enqueued.
+ *   - All calls on one GPU, from every model and every stream, share that GPU's array: calls that overlap on one
+ *     GPU race.  Issue them on one stream, or order them yourself.  Nothing in the array needs to start at
+ *     zero: each call rewrites what it reads, so contents left by an earlier (larger or smaller) call are harmless.
+ *   - mt_read_hidden afterwards reads this call's states from the array.  Per-launch timing must be off
+ *     (MT_ERR_STATE otherwise: it creates events).  Sequence-level heads only, no segment ids.
+ * Errors: as mt_forward, plus the above.
+ */
+#define MT_STATIC_SCRATCH_BYTES (32u * 1024u * 1024u)
+int mt_forward_static(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_mask, int32_t batch, int32_t seq,
+                      const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream);
+
+/*
  * mt_forward with segment (token type) ids for sentence-pair inputs, as in the BERT input representation
  * the student models are built on (Section 3): the embedding of a token adds row d_token_type_ids[b][s]
  * of the type table instead of row 0.  d_token_type_ids: [batch][seq] int32 device array, values clamped

@@ -21,6 +21,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <thread>
 #include <vector>
@@ -1347,6 +1348,54 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
                const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream)
 {
     return forward_impl(m, d_input_ids, nullptr, d_attn_mask, batch, seq, h_task_mask, nullptr, d_out_logits, nullptr, hip_stream);
+}
+
+// ---- the forward pass for callers that must not allocate: its workspace is a fixed array in device memory that is
+// part of the loaded code object (every GPU the library runs on holds its own copy until the process ends).
+// MT_STATIC_SCRATCH_BYTES is declared in mt.h.  Host code never uses the array's name as an address: the name is a
+// host-side stand-in, and the per-device address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char mt_static_scratch[MT_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the current device's copy of the array, or nullptr with *err set.
+unsigned char* static_scratch_of_current_device(hipError_t* err)
+{
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(mt_static_scratch));
+        if (*err != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+int mt_forward_static(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_mask, int32_t batch, int32_t seq,
+                      const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream)
+{
+    if (!m) return MT_ERR_NULL;
+    if (m->workspace_bytes > (size_t)MT_STATIC_SCRATCH_BYTES)
+        return fail(m, MT_ERR_SHAPE,
+                    "mt_forward_static: this model's workspace (max_batch %d x max_seq %d: %zu bytes) exceeds the static scratch of %zu "
+                    "bytes; create the model with smaller bounds or use mt_forward",
+                    m->cfg.max_batch, m->cfg.max_seq, m->workspace_bytes, (size_t)MT_STATIC_SCRATCH_BYTES);
+    if (m->profiling) return fail(m, MT_ERR_STATE, "mt_forward_static: per-launch timing creates events; switch mt_profile_enable off");
+    hipError_t e = hipSuccess;
+    unsigned char* scratch = static_scratch_of_current_device(&e);
+    if (!scratch) return fail(m, MT_ERR_HIP, "mt_forward_static: static scratch address: %s", hipGetErrorString(e));
+    return forward_impl(m, d_input_ids, nullptr, d_attn_mask, batch, seq, h_task_mask, nullptr, d_out_logits, nullptr, hip_stream, scratch);
 }
 
 int mt_forward_routed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask, int32_t batch,
