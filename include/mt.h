@@ -148,6 +148,23 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
                const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream);
 
 /*
+ * Several request batches in ONE forward pass (dynamic batching across requests: Appendix E's deployment serves a
+ * stream of requests, and the merged model is the same function of every sequence whoever sent it).  Request r
+ * brings its own device arrays h_d_input_ids[r], h_d_attn_mask[r] ([batch][seq] int32 each) and receives its logits
+ * in h_d_out_logits[r] ([batch][C_tot] float32); the three tables are HOST arrays of n_requests device pointers,
+ * read before the call returns.  The library copies the ids and masks behind one another into its workspace, runs
+ * the trunk and all branches once over the n_requests * batch sequences (every contraction then has n_requests
+ * times the rows, which is what fills a 256-CU chip at serving batch sizes), and copies each request's logits rows
+ * back, the columns of enabled tasks only (others are left untouched, as in mt_forward).  Same shapes for every
+ * request; sequences of different requests never interact.  Results equal mt_forward per request up to the
+ * rounding differences between launch shapes (the contraction kernel is chosen by row count).
+ * Needs 1 <= n_requests <= 16, n_requests * batch <= max_batch, sequence-level heads only, C_tot <= 1024.
+ * Enqueues on hip_stream only.  Errors: NULL, SHAPE, CONFIG (token-level task enabled), STATE, HIP.
+ */
+int mt_forward_multi(mt_model* m, int32_t n_requests, const int32_t* const* h_d_input_ids, const int32_t* const* h_d_attn_mask,
+                     int32_t batch, int32_t seq, const uint8_t* h_task_mask, float* const* h_d_out_logits, void* hip_stream);
+
+/*
  * mt_forward for callers that cannot allocate device memory or let a library do so on their behalf: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
  * bit-identical logits, but the workspace is NOT the arena given to mt_bind: it is a fixed array of

@@ -27,7 +27,7 @@ EXPORTS = ["mt_create", "mt_destroy", "mt_weight_bytes", "mt_workspace_bytes", "
            "mt_forward", "mt_logit_offset", "mt_n_logits", "mt_layer_count", "mt_last_error", "mt_error_name",
            "mt_read_hidden", "mt_profile_enable", "mt_profile_read", "mt_op_linear", "mt_op_attention",
            "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed", "mt_op_linear_sub", "mt_op_first_token_pool", "mt_schedule_steps", "mt_forward_routed",
-           "mt_forward_tokens", "mt_token_logit_offset", "mt_n_token_logits", "mt_forward_static"]
+           "mt_forward_tokens", "mt_token_logit_offset", "mt_n_token_logits", "mt_forward_static", "mt_forward_multi"]
 MT_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 
 
@@ -66,6 +66,7 @@ def lib():
         L.mt_load_weights.argtypes = [vp, i32, vp, sz, vp]
         L.mt_forward.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_static.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
+        L.mt_forward_multi.argtypes = [vp, i32, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_typed.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_routed.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_tokens.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
@@ -219,6 +220,23 @@ class Model:
             assert type_ids.shape == ids.shape
             self._check(lib().mt_forward_typed(self.h, _ptr(ids), _ptr(type_ids), _ptr(mask), b, s, tm, _ptr(out), _stream()))
         return out
+
+    def forward_multi(self, requests, outs=None, task_mask=None):
+        """mt_forward_multi: `requests` is a list of (ids, mask) int32 CUDA tensor pairs of one shape [B,S]; returns the list
+        of float32 CUDA tensors [B, C_tot], one per request (enqueued, not synced)."""
+        import torch
+        n = len(requests)
+        b, s = requests[0][0].shape
+        if outs is None:
+            outs = [torch.zeros((b, self.n_logits), dtype=torch.float32, device=requests[0][0].device) for _ in range(n)]
+        tm = None
+        if task_mask is not None:
+            tm = (C.c_uint8 * len(task_mask))(*[1 if v else 0 for v in task_mask])
+        p_ids = (C.c_void_p * n)(*[r[0].data_ptr() for r in requests])
+        p_mask = (C.c_void_p * n)(*[r[1].data_ptr() for r in requests])
+        p_out = (C.c_void_p * n)(*[o.data_ptr() for o in outs])
+        self._check(lib().mt_forward_multi(self.h, n, p_ids, p_mask, b, s, tm, p_out, _stream()))
+        return outs
 
     def forward_static(self, ids, mask, out, task_mask=None):
         """mt_forward_static: the forward pass on the library's fixed scratch array; `out` is the caller's float32

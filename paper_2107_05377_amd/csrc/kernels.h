@@ -48,6 +48,10 @@ struct GemmShape {
 
 // bf16 x bf16 -> fp32 accumulate on the matrix cores.  Needs K % 64 == 0, lda % 8 == 0, 16-byte aligned A/W rows.
 hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t stream);
+// Persistent variant for launches of many 256x256 tiles (one workgroup per compute unit walks a tile list with
+// its load ring never draining); launch_gemm_bf16 routes to it by itself.  gemm_bf16_persist_takes: shape supported.
+bool gemm_bf16_persist_takes(const GemmShape& s);
+hipError_t launch_gemm_bf16_persist(const GemmGroup& g, const GemmShape& s, hipStream_t stream);
 // Few-row variant (M <= 256), memory-parallel instead of tiled; launch_gemm_bf16 routes to it by itself.
 hipError_t launch_gemm_skinny_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t stream);
 // Register-only matrix-core rate measurement: n_cu workgroups of 8 wavefronts, `iters` x 8 MFMAs each; d_out needs
@@ -176,6 +180,20 @@ struct TokGroup {
 };
 hipError_t launch_token_classifier(const TokGroup& g, int G, int n_pos, int H, int w_bf16, int64_t ldo, const int32_t* row_of,
                                    const int32_t* n_rows, hipStream_t stream);
+
+// Several request batches served by one forward pass: request r's ids and mask ([batch][seq] each) are copied behind
+// one another into contiguous staging arrays, and afterwards the logits rows of the combined batch go back to each
+// request's own [batch][ldo] array, only the columns whose bit is set in col_on (bit c of word c/32).
+constexpr int kMaxRequests = 16;
+constexpr int kMaxLogitCols = 1024;
+struct RequestPtrs {
+    const int32_t* ids[kMaxRequests];
+    const int32_t* mask[kMaxRequests];
+    float* out[kMaxRequests];
+    uint32_t col_on[kMaxLogitCols / 32];
+};
+hipError_t launch_gather_requests(const RequestPtrs& rq, int n_req, int n_per_req, int32_t* ids_all, int32_t* mask_all, hipStream_t stream);
+hipError_t launch_scatter_logits(const RequestPtrs& rq, int n_req, int batch, int n_cols, const float* logits_all, hipStream_t stream);
 
 // Per-sequence task routing: a sub-batch of the sequences, as a padding-free row order of its own.
 // idx lists the chosen sequences (ascending batch indices), passed by value with the launch.

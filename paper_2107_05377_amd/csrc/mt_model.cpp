@@ -115,6 +115,7 @@ struct mt_model {
     std::vector<ClsScratch> task_cls;
     size_t pooled = 0, cls_split = 0;
     size_t rm_n = 0, rm_src = 0, rm_rowof = 0, rm_start = 0, rm_len = 0;   // padding-free row map of the current batch
+    size_t mr_ids = 0, mr_mask = 0, mr_logits = 0;                          // mt_forward_multi: the combined batch's ids, mask, logits
     size_t workspace_bytes = 0;
 
     unsigned char* d_w = nullptr;
@@ -807,6 +808,9 @@ int mt_create(const mt_config* cfg, mt_model** out)
     m->rm_len = sb.take((size_t)cfg->max_batch * 4);
     m->pooled = sb.take(T * (size_t)cfg->max_batch * H * 4);
     m->cls_split = sb.take(T * (size_t)cfg->max_batch * H * 4);   // [hi | lo] bf16 halves, or float32 rows in the validation mode
+    m->mr_ids = sb.take(M * 4);
+    m->mr_mask = sb.take(M * 4);
+    m->mr_logits = sb.take((size_t)cfg->max_batch * std::max(m->C_tot, 1) * 4);
     m->workspace_bytes = sb.off;
     m->task_loaded.assign(T, 0);
     m->last_enabled.assign(T, 0);
@@ -1350,6 +1354,46 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
     return forward_impl(m, d_input_ids, nullptr, d_attn_mask, batch, seq, h_task_mask, nullptr, d_out_logits, nullptr, hip_stream);
 }
 
+int mt_forward_multi(mt_model* m, int32_t n_requests, const int32_t* const* h_d_input_ids, const int32_t* const* h_d_attn_mask,
+                     int32_t batch, int32_t seq, const uint8_t* h_task_mask, float* const* h_d_out_logits, void* hip_stream)
+{
+    if (!m) return MT_ERR_NULL;
+    if (!h_d_input_ids || !h_d_attn_mask || !h_d_out_logits) return fail(m, MT_ERR_NULL, "mt_forward_multi: null pointer table");
+    if (n_requests < 1 || n_requests > kMaxRequests)
+        return fail(m, MT_ERR_SHAPE, "mt_forward_multi: %d requests, at most %d per call", n_requests, kMaxRequests);
+    if (batch < 1 || seq < 1 || (int64_t)n_requests * batch > m->cfg.max_batch || seq > m->cfg.max_seq)
+        return fail(m, MT_ERR_SHAPE, "mt_forward_multi: %d requests x batch %d x seq %d outside max_batch %d x max_seq %d", n_requests, batch,
+                    seq, m->cfg.max_batch, m->cfg.max_seq);
+    if (m->C_tot > kMaxLogitCols) return fail(m, MT_ERR_CONFIG, "mt_forward_multi: more than %d logit columns", kMaxLogitCols);
+    if (!m->d_w || !m->d_ws) return fail(m, MT_ERR_STATE, "mt_forward_multi: call mt_bind first");
+    RequestPtrs rq;
+    memset(&rq, 0, sizeof rq);
+    for (int r = 0; r < n_requests; ++r) {
+        if (!h_d_input_ids[r] || !h_d_attn_mask[r] || !h_d_out_logits[r])
+            return fail(m, MT_ERR_NULL, "mt_forward_multi: request %d has a null device pointer", r);
+        rq.ids[r] = h_d_input_ids[r];
+        rq.mask[r] = h_d_attn_mask[r];
+        rq.out[r] = h_d_out_logits[r];
+    }
+    for (size_t t = 0; t < m->tasks.size(); ++t) {
+        if (h_task_mask && !h_task_mask[t]) continue;
+        if (m->tasks[t].head == MT_HEAD_TOKEN)
+            return fail(m, MT_ERR_CONFIG, "mt_forward_multi: task %zu has a token-level head (use mt_forward_tokens per request)", t);
+        for (int c = m->logit_off[t]; c < m->logit_off[t] + m->tasks[t].n_classes; ++c) rq.col_on[c >> 5] |= 1u << (c & 31);
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    int32_t* ids_all = (int32_t*)(m->d_ws + m->mr_ids);
+    int32_t* mask_all = (int32_t*)(m->d_ws + m->mr_mask);
+    float* logits_all = (float*)(m->d_ws + m->mr_logits);
+    hipError_t e = launch_gather_requests(rq, n_requests, batch * seq, ids_all, mask_all, st);
+    if (e != hipSuccess) return fail(m, MT_ERR_HIP, "mt_forward_multi: %s", hipGetErrorString(e));
+    const int rc = forward_impl(m, ids_all, nullptr, mask_all, n_requests * batch, seq, h_task_mask, nullptr, logits_all, nullptr, hip_stream);
+    if (rc != MT_OK) return rc;
+    e = launch_scatter_logits(rq, n_requests, batch, m->C_tot, logits_all, st);
+    if (e != hipSuccess) return fail(m, MT_ERR_HIP, "mt_forward_multi: %s", hipGetErrorString(e));
+    return MT_OK;
+}
+
 // ---- the forward pass for callers that must not allocate: its workspace is a fixed array in device memory that is
 // part of the loaded code object (every GPU the library runs on holds its own copy until the process ends).
 // MT_STATIC_SCRATCH_BYTES is declared in mt.h.  Host code never uses the array's name as an address: the name is a
@@ -1490,7 +1534,7 @@ int mt_debug_mfma_peak(int32_t iters, void* d_scratch, size_t scratch_bytes, flo
 int mt_debug_set_gemm_tile(int32_t sel)
 {
     const int prev = mt::g_gemm_bf16_tile_override;
-    mt::g_gemm_bf16_tile_override = (sel >= 0 && sel <= 26) ? sel : 0;
+    mt::g_gemm_bf16_tile_override = (sel >= 0 && sel <= 27) ? sel : 0;
     return prev;
 }
 

@@ -968,6 +968,52 @@ def test_a_sequence_without_real_tokens_disturbs_nothing(which):
     model.close()
 
 
+@pytest.mark.parametrize("which", ["fp32", "bf16"])
+def test_several_requests_in_one_forward_match_oracle(which):
+    """mt_forward_multi: request batches arriving in separate device arrays run as one combined batch; every request
+    gets the oracle's logits for its own sequences, columns of masked-off tasks stay untouched, and pointer tables
+    are read before the call returns (they are rebuilt for every call here)."""
+    spec = MINI if which == "fp32" else SMALL
+    tr, tri, tps = _params(spec, True, 0.1 if which == "fp32" else 0.05)
+    orc = oracle.Oracle(spec, tr, [p for p, _ in tps])
+    n_req = 5
+    model = _load(spec, tr, tri, tps, max_batch=n_req * spec.batch)
+    one = _load(spec, tr, tri, tps)
+    reqs, refs = [], []
+    for r in range(n_req):
+        ids, mask, _ = ms.make_inputs(spec, batch_index=20 + r)
+        reqs.append((dev(ids), dev(mask)))
+        refs.append(orc.mt_forward(ids, mask))
+    outs = model.forward_multi(reqs)
+    for r in range(n_req):
+        got = outs[r].cpu().numpy()
+        if which == "fp32":
+            assert max(rel_err_per_task(spec, got, refs[r])) <= 1e-4
+        else:
+            assert np.abs(got - refs[r]).max() <= 2e-2
+        alone = one.forward(*reqs[r]).cpu().numpy()
+        assert np.abs(got - alone).max() <= (1e-5 if which == "fp32" else 5e-3)
+    # fewer requests than the model was created for, and a task mask
+    tm = [1] + [0] * (spec.n_tasks - 2) + [1]
+    outs2 = [torch.full((spec.batch, model.n_logits), 7.0, device="cuda") for _ in range(2)]
+    model.forward_multi(reqs[3:5], outs=outs2, task_mask=tm)
+    for k, r in enumerate((3, 4)):
+        o = outs2[k].cpu().numpy()
+        want = outs[r].cpu().numpy()
+        for t in range(spec.n_tasks):
+            lo = spec.logit_offset(t)
+            sl = slice(lo, lo + spec.tasks[t].n_classes)
+            if tm[t]:
+                assert np.abs(o[:, sl] - want[:, sl]).max() <= (1e-5 if which == "fp32" else 5e-3)
+            else:
+                assert (o[:, sl] == 7.0).all()
+    with pytest.raises(mt.MTError) as ei:                       # more sequences than the model was created for
+        one.forward_multi(reqs[:2])
+    assert ei.value.code == mt.MT_ERR_SHAPE
+    model.close()
+    one.close()
+
+
 def test_read_hidden_refuses_states_the_last_forward_did_not_write():
     """A trunk tap is readable only if the last forward pass ran the trunk that deep: with the deeper tasks masked
     off the trunk stops at the deepest enabled fork, and with no task enabled nothing runs at all."""
