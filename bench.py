@@ -1,11 +1,14 @@
 #!/usr/bin/env python3
 """Throughput of the merged multi-task serving forward pass on one MI355X.
 
-One step = one mt_forward over one synthetic batch (embeddings, shared trunk once, all task branches,
-poolers and heads), inputs and weights already resident in HBM.  Prints ONE JSON line:
-sequences/s (whole job), the roofline position of the dominant kernel (the bf16 MFMA GEMM) from
-per-launch HIP events recorded inside the library on the forward's stream, and the CPU oracle timed
-on a bounded sample of the same workload on this host.
+One step = the forward pass over one synthetic request batch (embeddings, shared trunk once, all task
+branches, poolers and heads), inputs and weights already resident in HBM.  Request batches keep the
+workload's batch size (32 sequences for `base`); the server hands several of them to the library in one
+call (mt_forward_multi, --requests-per-call), which runs them as one combined batch so that every
+contraction has enough rows to fill the chip.  Prints ONE JSON line: sequences/s (whole job), the
+roofline position of the dominant kernel (the bf16 MFMA contraction) from per-launch HIP events recorded
+inside the library on the forward's stream, the CPU oracle timed on a bounded sample of the same workload
+on this host, and short runs of the other workloads (`workloads`).
 """
 import argparse
 import json
@@ -192,6 +195,143 @@ def qps_stream(ms, spec, model, rates, n_requests, seed=7):
     return res
 
 
+class Served:
+    """A loaded model plus the replicas, streams and request batches one measurement needs."""
+
+    def __init__(self, mt, ms, spec, B, R, n_fly, n_batches=8):
+        import numpy as np
+        import torch
+        self.mt, self.spec, self.B, self.R, self.S = mt, spec, B, max(1, R), spec.seq
+        self.multi = self.R > 1
+        t0 = time.time()
+        self.model, _ = mt.load_synthetic(spec, max_batch=B * self.R, max_seq=spec.seq)
+        self.load_s = time.time() - t0
+        self.n_batches = n_batches
+        self.batches, self.real_tokens, self.sq_lengths = [], [], []
+        for i in range(n_batches):
+            ids, mask, lengths = ms.make_inputs(spec, batch=B, batch_index=i)
+            self.batches.append((torch.from_numpy(ids).cuda(), torch.from_numpy(mask).cuda()))
+            self.real_tokens.append(int(mask.sum()))
+            self.sq_lengths.append(float((lengths.astype(np.float64) ** 2).sum()))
+        self.stream = torch.cuda.current_stream()
+        self.n_fly = max(1, n_fly)
+        self.models = [self.model] + [self.model.replica() for _ in range(self.n_fly - 1)]
+        self.streams = [torch.cuda.Stream() for _ in range(self.n_fly)]          # default priority
+        m = self.model
+        self.outs = [[torch.zeros((B, m.n_logits), dtype=torch.float32, device="cuda") for _ in range(self.R)] for _ in range(self.n_fly)]
+        self.tok_outs = [torch.zeros((B, self.S, m.n_token_logits), dtype=torch.float32, device="cuda") if m.n_token_logits else None
+                         for _ in range(self.n_fly)]
+
+    def call(self, j, first, n):
+        """One library call on replica j: request batches first .. first+n-1 (indices into the cycled batches)."""
+        reqs = [self.batches[(first + r) % self.n_batches] for r in range(n)]
+        if self.multi:
+            self.models[j].forward_multi(reqs, outs=self.outs[j][:n])
+        else:
+            forward(self.models[j], reqs[0], self.outs[j][0], self.tok_outs[j])
+
+    def run_steps(self, k, fly):
+        """k request batches, R per call, calls round-robin over the replicas' streams; elapsed milliseconds."""
+        import torch
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(self.stream)
+        for st in self.streams[:fly]:
+            st.wait_event(e0)
+        done, c = 0, 0
+        while done < k:
+            n = min(self.R, k - done)
+            with torch.cuda.stream(self.streams[c % fly]):
+                self.call(c % fly, done, n)
+            done += n
+            c += 1
+        for st in self.streams[:fly]:
+            self.stream.wait_stream(st)
+        e1.record(self.stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    def rows_per_step(self, steps):
+        import numpy as np
+        rows = float(np.mean([self.real_tokens[i % self.n_batches] for i in range(steps)]))
+        sumsq = float(np.mean([self.sq_lengths[i % self.n_batches] for i in range(steps)]))
+        return rows, sumsq
+
+    def profile(self, steps):
+        """Per-kernel-class durations (ms per request batch, event overhead taken off) with one call in flight."""
+        import torch
+        ms_serial = self.run_steps(steps, 1) / steps
+        self.model.profile_enable(True)
+        done = 0
+        while done < steps:
+            n = min(self.R, steps - done)
+            self.call(0, done, n)
+            done += n
+        torch.cuda.synchronize()
+        prof = self.model.profile_read()
+        self.model.profile_enable(False)
+        # An event record costs the command processor a few microseconds, so the event-bracketed durations sum to
+        # more than the same launches take back to back without events (ms_serial; kernels of one forward run
+        # gap-free on one stream).  The excess, spread evenly over the launches, is taken off every duration.
+        launches_total = sum(n for _, n in prof.values()) / steps
+        raw_sum_ms = sum(ms_tot for ms_tot, _ in prof.values()) / steps
+        event_overhead_ms = max(0.0, (raw_sum_ms - ms_serial) / launches_total)
+        dur, kernels = {}, {}
+        for k, (ms_tot, n) in prof.items():
+            if n == 0:
+                continue
+            dur[k] = max(1e-6, ms_tot / steps - event_overhead_ms * n / steps)
+            kernels[k] = {"launches_per_step": n / steps, "ms_per_step": dur[k], "avg_us": 1e3 * dur[k] / (n / steps),
+                          "ms_per_step_raw_events": ms_tot / steps}
+        return ms_serial, prof, dur, kernels, event_overhead_ms
+
+    def close(self):
+        for m in self.models[1:]:
+            m.close()
+        self.model.close()
+
+
+def gemm_summary(spec, B, rows, prof, dur, kernels, steps, peak):
+    """Adds TFLOP/s and the fraction of the matrix-core peak to the contraction classes; returns the totals over the
+    tiled contractions (the dominant kernel)."""
+    flops = gemm_flops_per_forward(spec, rows, B)
+    for k in flops:
+        if k in kernels:
+            kernels[k]["tflops"] = flops[k] / (dur[k] * 1e-3) / 1e12
+            kernels[k]["frac"] = kernels[k]["tflops"] / peak
+    main = [k for k in flops if k != "gemm_first" and k in dur]
+    main_flops = sum(flops[k] for k in main)
+    gemm_ms = sum(dur[k] for k in main)
+    gemm_ms_raw = sum(prof[k][0] for k in main) / steps
+    gemm_launches = sum(prof[k][1] for k in main) / steps
+    return flops, main_flops, gemm_ms, gemm_ms_raw, gemm_launches
+
+
+def side_workload(mt, ms, name, R, fly, steps, warmup, latency_calls=0):
+    """A short run of another workload: sequences/s and the tiled contraction's TFLOP/s; for the small-batch serving
+    workloads also the per-call latency sweep."""
+    import torch
+    spec = ms.get_config(name)
+    sv = Served(mt, ms, spec, spec.batch, R, fly)
+    sv.run_steps(warmup, sv.n_fly)
+    ms_step = sv.run_steps(steps, sv.n_fly) / steps
+    ms_serial, prof, dur, kernels, _ = sv.profile(steps)
+    rows, _ = sv.rows_per_step(steps)
+    _, main_flops, gemm_ms, _, gemm_launches = gemm_summary(spec, spec.batch, rows, prof, dur, kernels, steps, PEAK_BF16_MFMA_TFLOPS)
+    ent = {"workload": f"{spec.name}: H={spec.hidden} trunk={spec.n_trunk_layers} tasks={spec.n_tasks} layers={sv.model.layer_count()} "
+                       f"B={spec.batch} S={spec.seq}",
+           "requests_per_call": sv.R, "calls_in_flight": sv.n_fly, "steps": steps,
+           "sequences_per_s": spec.batch / (ms_step * 1e-3), "ms_per_step": ms_step, "ms_per_step_one_call_in_flight": ms_serial,
+           "gemm_tflops": main_flops / (gemm_ms * 1e-3) / 1e12, "gemm_frac": main_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+           "gemm_launches_per_step": gemm_launches}
+    if latency_calls > 0:
+        ent["latency"] = latency_sweep(mt, ms, spec, sv.model, latency_calls)
+    sv.close()
+    del sv
+    torch.cuda.empty_cache()
+    return ent
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -199,13 +339,17 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="base", help="tiny | base | hetero | latency | large | industrial | wo_kd | mixed | assistant")
     ap.add_argument("--batch", type=int, default=None)
-    ap.add_argument("--in-flight", type=int, default=3,
-                    help="batches in flight: forwards are issued round-robin to this many model replicas (shared "
-                         "weights, own workspace) on as many streams; 1 = strictly one forward after another")
+    ap.add_argument("--requests-per-call", type=int, default=None,
+                    help="request batches handed to the library per call (mt_forward_multi); 1 = plain mt_forward.  Default: 8 "
+                         "for sequence-level workloads of up to 64 sequences per batch, else 1")
+    ap.add_argument("--in-flight", type=int, default=2,
+                    help="calls in flight: calls are issued round-robin to this many model replicas (shared "
+                         "weights, own workspace) on as many streams; 1 = strictly one call after another")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-workloads", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--cpu-sample", type=int, default=64, help="sequences the CPU oracle is timed on")
     ap.add_argument("--latency-calls", type=int, default=2000,
-                    help="configs 'latency' and 'industrial': forwards timed one by one (host clock, stream sync per call) per "
+                    help="small-batch serving workloads: forwards timed one by one (host clock, stream sync per call) per "
                          "batch size; 0 skips that sweep")
     ap.add_argument("--qps", default="", help="comma-separated request rates (requests/s): also serve an open-loop Poisson "
                                               "stream of single-sequence requests at each rate and report p50/p99 latency")
@@ -233,41 +377,12 @@ def main():
     spec = ms.get_config(args.config)
     B = args.batch or spec.batch
     S = spec.seq
-    t0 = time.time()
-    model, _ = mt.load_synthetic(spec, max_batch=B, max_seq=S)
-    load_s = time.time() - t0
-    n_batches = 8
-    batches, real_tokens, sq_lengths = [], [], []
-    for i in range(n_batches):
-        ids, mask, lengths = ms.make_inputs(spec, batch=B, batch_index=i)
-        batches.append((torch.from_numpy(ids).cuda(), torch.from_numpy(mask).cuda()))
-        real_tokens.append(int(mask.sum()))
-        sq_lengths.append(float((lengths.astype(np.float64) ** 2).sum()))
-    out = torch.zeros((B, model.n_logits), dtype=torch.float32, device="cuda")
-    stream = torch.cuda.current_stream()
-    n_fly = max(1, args.in_flight)
-    models = [model] + [model.replica() for _ in range(n_fly - 1)]
-    streams = [torch.cuda.Stream() for _ in range(n_fly)]          # default priority
-    outs = [torch.zeros_like(out) for _ in range(n_fly)]
-    tok_outs = [torch.zeros((B, S, model.n_token_logits), dtype=torch.float32, device="cuda") if model.n_token_logits else None
-                for _ in range(n_fly)]
-
-    def run_steps(k, fly):
-        """k forwards, round-robin over the replicas' streams; returns elapsed milliseconds."""
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for st in streams[:fly]:
-            st.wait_event(e0)
-        for i in range(k):
-            j = i % fly
-            with torch.cuda.stream(streams[j]):
-                forward(models[j], batches[i % n_batches], outs[j], tok_outs[j])
-        for st in streams[:fly]:
-            stream.wait_stream(st)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1)
+    has_tokens = any(getattr(t, "token_level", False) for t in spec.tasks)
+    R = args.requests_per_call if args.requests_per_call else (8 if (B <= 64 and not has_tokens) else 1)
+    if has_tokens:
+        R = 1
+    sv = Served(mt, ms, spec, B, R, args.in_flight)
+    model, n_fly = sv.model, sv.n_fly
 
     if args.copy_calibration:
         src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")       # 256 MiB read + 256 MiB written
@@ -277,77 +392,51 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    run_steps(args.warmup, n_fly)
-    ms_per_step = run_steps(args.steps, n_fly) / args.steps
+    sv.run_steps(args.warmup, n_fly)
+    ms_per_step = sv.run_steps(args.steps, n_fly) / args.steps
     seq_per_s = B / (ms_per_step * 1e-3)
-    for o in outs[:min(n_fly, args.steps)]:
+    for o in sv.outs[0][:min(sv.R, args.steps)]:
         assert torch.isfinite(o).all()
-    # the same K steps strictly one after another on one stream (latency of one batch; also what the
-    # per-kernel figures below are measured on, so that no other batch's kernels share the chip with them)
-    run_steps(min(args.warmup, 3), 1)
-    ms_serial = run_steps(args.steps, 1) / args.steps
-    # ... and the same steps once more with an event pair around every single forward: median and minimum
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    # the same steps with one call in flight (what the per-kernel figures are measured on, so that no other call's
+    # kernels share the chip with a timed launch), then with HIP events around every launch
+    sv.run_steps(min(args.warmup, 3 * sv.R), 1)
+    ms_serial, prof, dur, kernels, event_overhead_ms = sv.profile(args.steps)
+    # ... and call by call with an event pair around every call: median and minimum per request batch
+    n_calls = (args.steps + sv.R - 1) // sv.R
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_calls + 1)]
     torch.cuda.synchronize()
-    marks[0].record(stream)
-    for i in range(args.steps):
-        forward(model, batches[i % n_batches], out, tok_outs[0])
-        marks[i + 1].record(stream)
+    marks[0].record(sv.stream)
+    done, sizes = 0, []
+    for i in range(n_calls):
+        n = min(sv.R, args.steps - done)
+        sv.call(0, done, n)
+        marks[i + 1].record(sv.stream)
+        done += n
+        sizes.append(n)
     torch.cuda.synchronize()
-    per_step = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)])
-
-    # ---- per-kernel durations from HIP events around every launch, same stream, same steps
-    model.profile_enable(True)
-    for i in range(args.steps):
-        forward(model, batches[i % n_batches], out, tok_outs[0])
-    torch.cuda.synchronize()
-    prof = model.profile_read()
-    model.profile_enable(False)
+    per_step = np.array([marks[i].elapsed_time(marks[i + 1]) / sizes[i] for i in range(n_calls)])
 
     n_layers = model.layer_count()
-    # the timed steps cycle through the batches: average real-token count over the steps actually run
-    rows = float(np.mean([real_tokens[i % n_batches] for i in range(args.steps)]))
-    sumsq = float(np.mean([sq_lengths[i % n_batches] for i in range(args.steps)]))
-    flops = gemm_flops_per_forward(spec, rows, B)
+    rows, sumsq = sv.rows_per_step(args.steps)
     n_full, n_first = layer_kinds(spec)
     assert n_full + n_first == n_layers
-    # An event record costs the command processor a few microseconds, so the event-bracketed durations sum to
-    # more than the same launches take back to back without events (ms_serial; kernels of one forward run
-    # gap-free on one stream).  The excess, spread evenly over the launches, is taken off every duration.
-    launches_total = sum(n for _, n in prof.values()) / args.steps
-    raw_sum_ms = sum(ms_tot for ms_tot, _ in prof.values()) / args.steps
-    event_overhead_ms = max(0.0, (raw_sum_ms - ms_serial) / launches_total)
-    kernels = {}
-    dur = {}
-    for k, (ms_tot, n) in prof.items():
-        if n == 0:
-            continue
-        dur[k] = max(1e-6, ms_tot / args.steps - event_overhead_ms * n / args.steps)      # ms per step, corrected
-        ent = {"launches_per_step": n / args.steps, "ms_per_step": dur[k], "avg_us": 1e3 * dur[k] / (n / args.steps),
-               "ms_per_step_raw_events": ms_tot / args.steps}
-        if k in flops:
-            ent["tflops"] = flops[k] / (dur[k] * 1e-3) / 1e12
-        kernels[k] = ent
-    # the dominant kernel: the tiled matrix-core contraction over all token rows (the one-row-per-sequence
-    # contractions of the branches' last layers run in the few-row kernel and are listed on their own)
-    main = [k for k in flops if k != "gemm_first"]
-    main_flops = sum(flops[k] for k in main)
-    gemm_ms = sum(dur[k] for k in main)
-    gemm_ms_raw = sum(prof[k][0] for k in main) / args.steps
-    gemm_launches = sum(prof[k][1] for k in main) / args.steps
-    gemm_tflops = main_flops / (gemm_ms * 1e-3) / 1e12
     bf16 = spec.precision == "bf16"
     peak = PEAK_BF16_MFMA_TFLOPS if bf16 else PEAK_FP32_VALU_TFLOPS
-    kname = ("gemm_bf16_kernel" if rows > 256 else "gemm_skinny_bf16_kernel") if bf16 else "gemm_f32_kernel"
-    traffic = stored_traffic(spec.name) if (bf16 and B == spec.batch and kname == "gemm_bf16_kernel") else None
+    flops, main_flops, gemm_ms, gemm_ms_raw, gemm_launches = gemm_summary(spec, B, rows, prof, dur, kernels, args.steps, peak)
+    gemm_tflops = main_flops / (gemm_ms * 1e-3) / 1e12
+    kname = ("gemm_bf16_kernel + gemm_bf16_persist_kernel" if rows * sv.R > 256 else "gemm_skinny_bf16_kernel") if bf16 else "gemm_f32_kernel"
+    traffic = stored_traffic(spec.name) if (bf16 and B == spec.batch and rows * sv.R > 256) else None
     measured_peak = mt.mfma_peak() if bf16 else None
+    # per LAUNCH: a launch serves the rows of all request batches of its call
     roofline = {"kernel": kname, "bound": "mfma" if bf16 else "alu",
                 "achieved": gemm_tflops, "peak": peak, "unit": "TFLOP/s", "frac": gemm_tflops / peak, "traffic": traffic,
+                "traffic_source": "stored rocprofv3 counter summary under profiles/ (null: none for this kernel source)",
                 "peak_measured_mfma_only": measured_peak,
                 "frac_of_measured_peak": (gemm_tflops / measured_peak) if measured_peak else None,
                 "flops_per_launch": main_flops / gemm_launches, "avg_launch_us": 1e3 * gemm_ms / gemm_launches,
                 "flops_counted": "executed: real (unpadded) token rows only",
                 "launches_per_step": gemm_launches, "gemm_ms_per_step": gemm_ms,
+                "rows_per_launch": rows * min(sv.R, args.steps),
                 "avg_launch_us_raw_events": 1e3 * gemm_ms_raw / gemm_launches, "event_overhead_us_per_launch": 1e3 * event_overhead_ms}
 
     h = spec.hidden
@@ -366,7 +455,7 @@ def main():
         tasks = [ms.make_task_params(spec, t)[0] for t in range(spec.n_tasks)]
         orc = oracle.Oracle(spec, trunk, tasks)
         left, dt, n_done, err = max(1, args.cpu_sample), 0.0, 0, 0.0
-        for bi in range(n_batches):
+        for bi in range(sv.n_batches):
             if left <= 0:
                 break
             n = min(left, B)
@@ -374,7 +463,8 @@ def main():
             t0 = time.time()
             ref = orc.mt_forward(ids[:n], mask[:n])
             dt += time.time() - t0
-            got = forward(model, batches[bi]).cpu().numpy()[:n]
+            sv.call(0, bi, 1)
+            got = sv.outs[0][0].cpu().numpy()[:n]
             err = max(err, float(np.abs(got - ref).max()))
             left -= n
             n_done += n
@@ -401,17 +491,29 @@ def main():
                                f"tasks={spec.n_tasks} layers={n_layers} B={B} S={S} len~U[{spec.len_lo},{spec.len_hi}]",
                    "batch": B, "seq_len": S, "layer_evals": n_layers, "layers_on_all_rows": n_full,
                    "layers_on_first_token_only": n_first, "real_tokens_per_batch": rows, "padding_skipped": True,
-                   "batches_in_flight": n_fly},
-        "ms_per_step_one_in_flight": ms_serial, "sequences_per_s_one_in_flight": B / (ms_serial * 1e-3),
-        "ms_per_step_one_in_flight_median": float(np.median(per_step)), "ms_per_step_one_in_flight_min": float(per_step.min()),
+                   "step": "one request batch of `batch` sequences", "requests_per_call": sv.R, "calls_in_flight": n_fly},
+        "ms_per_step_one_call_in_flight": ms_serial, "sequences_per_s_one_call_in_flight": B / (ms_serial * 1e-3),
+        "ms_per_step_one_call_in_flight_median": float(np.median(per_step)), "ms_per_step_one_call_in_flight_min": float(per_step.min()),
         "e2e_tflops_executed": e2e_tflops, "e2e_frac_of_peak": e2e_tflops / peak,
         "e2e_tflops_dense_padded_equivalent": e2e_tflops_dense,
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "weights_load_s": load_s,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "weights_load_s": sv.load_s,
     }
     if spec.name in ("latency", "industrial") and args.latency_calls > 0:
         line["latency"] = latency_sweep(mt, ms, spec, model, args.latency_calls)
     if args.qps:
         line["qps_stream"] = qps_stream(ms, spec, model, [float(r) for r in args.qps.split(",")], args.qps_requests)
+    if spec.name == "base" and not args.no_workloads:
+        # the other workloads, driver-timed: short runs (a few seconds each), same measurement as above
+        sv.close()
+        del sv, model
+        torch.cuda.empty_cache()
+        side = {}
+        side["base_one_request_per_call"] = side_workload(mt, ms, "base", 1, 3, 48, 8)
+        side["hetero"] = side_workload(mt, ms, "hetero", 4, 2, 16, 4)
+        side["large"] = side_workload(mt, ms, "large", 1, 2, 8, 2)
+        side["industrial"] = side_workload(mt, ms, "industrial", 8, 2, 64, 8)
+        side["latency"] = side_workload(mt, ms, "latency", 1, 1, 32, 8, latency_calls=args.latency_calls)
+        line["workloads"] = side
     print(json.dumps(line))
 
 

@@ -51,22 +51,34 @@ __device__ __forceinline__ float p_act(float v)
     else return v;
 }
 
-// One K step's instruction mix for the scheduler: NM MFMAs with NF fragment reads and NL global->LDS loads
-// slotted between them.
-template <int NM, int NF, int NL>
+// One K step's instruction mix for the scheduler: NM MFMAs; the NF fragment reads go behind the first MFMAs,
+// PER at a time, so that the rest of the step's MFMAs cover their latency before the next step needs them; the NL
+// global->LDS loads follow, one per MFMA.
+template <int NM, int NF, int NL, int PER>
 __device__ __forceinline__ void p_interleave()
 {
-#pragma unroll
-    for (int i = 0; i < NM; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (i < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        else if (i - NF < NL) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    if constexpr (NM > 0) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                   // one MFMA ...
+        if constexpr (NF > 0) {
+            __builtin_amdgcn_sched_group_barrier(0x100, NF < PER ? NF : PER, 0);              // ... then fragment reads
+            p_interleave<NM - 1, (NF > PER ? NF - PER : 0), NL, PER>();
+        } else if constexpr (NL > 0) {
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                               // ... or one load
+            p_interleave<NM - 1, 0, NL - 1, PER>();
+        } else {
+            p_interleave<NM - 1, 0, 0, PER>();
+        }
     }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+#ifndef MT_P_DSPER
+#define MT_P_DSPER 2
+#endif
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK_, int STAGES, int PARK_COLS_>
 struct PCfg {
-    static constexpr int BK = 32, ROW_BYTES = 64, CH = 4, KK = 2, RPI = 16, KEY_SHIFT = 2;
+    static constexpr int BK = BK_, ROW_BYTES = BK * 2, CH = BK / 8, KK = BK / 16, RPI = 1024 / ROW_BYTES;
+    static constexpr int KEY_SHIFT = (BK == 64) ? 1 : 2;     // rows per 256 bytes of LDS = 2 or 4
     static constexpr int NW = WAVES_M * WAVES_N, NT = NW * 64;
     static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     static constexpr int TMI = WM / 32, TNI = WN / 32;
@@ -74,14 +86,16 @@ struct PCfg {
     static constexpr int LPP = LPS / KK;
     static constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
     static constexpr int RING_BYTES = STAGES * STAGE_BYTES;
-    static constexpr int PARK_ROWB = WN * 4;                 // bytes per parked float32 row
-    static constexpr int PARK_BYTES = 32 * PARK_ROWB;        // one 32-row block of the wavefront's sub-tile
+    static constexpr int PARK_COLS = PARK_COLS_;             // columns of the wavefront's sub-tile parked at a time (WN or 32)
+    static constexpr int PARK_ROWB = PARK_COLS * 4;          // bytes per parked float32 row
+    static constexpr int PARK_BYTES = 32 * PARK_ROWB;        // one 32-row block
     static constexpr int LDS_BYTES = RING_BYTES + NW * PARK_BYTES;
+    static_assert(BK == 32 || BK == 64, "BK");
     static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "rows must split evenly over wavefront loads");
     static_assert(LPS % KK == 0, "loads of a slice must split evenly over its K steps");
-    static_assert(STAGES >= 3 && LPS * (STAGES - 2) <= 63, "ring depth");
+    static_assert(STAGES >= 2 && LPS * (STAGES - 2) <= 63, "ring depth");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
-    static_assert(PARK_ROWB % 256 == 0 || 256 % PARK_ROWB == 0, "park row");
+    static_assert(PARK_COLS == WN || PARK_COLS == 32, "park block");
 };
 
 // What a workgroup needs to know of one tile to fetch it.
@@ -93,10 +107,11 @@ struct TileRef {
     int grp, m0, n0;
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool OUT_F32, int ACT>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int PARK_COLS, bool OUT_F32, int ACT>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void gemm_bf16_persist_kernel(GemmGroup g, GemmShape s, int tiles_n)
 {
-    using Cfg = PCfg<BM, BN, WAVES_M, WAVES_N, STAGES>;
+    using Cfg = PCfg<BM, BN, WAVES_M, WAVES_N, BK, STAGES, PARK_COLS>;
+    constexpr int KK = Cfg::KK;
     constexpr int TMI = Cfg::TMI, TNI = Cfg::TNI, ROW_BYTES = Cfg::ROW_BYTES, LPS = Cfg::LPS, LPP = Cfg::LPP;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
@@ -112,7 +127,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void gemm_bf16_persist_ke
     if (wi >= cnt) return;                                                   // uniform over the workgroup
     const int n_mine = (cnt - wi + wg_x - 1) / wg_x;
 
-    const int KT = s.K / Cfg::BK;
+    const int KT = s.K / BK;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -177,12 +192,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void gemm_bf16_persist_ke
                                                  (lptr_t)(sbase + BM * ROW_BYTES + (wave + (i_ - Cfg::A_LOADS) * Cfg::NW) * 1024), 16, 0, 0); \
         }                                                                                                           \
     } while (0)
-    // slice index r of the current tile's K range, or of the next tile's when r runs past it
-#define MT_P_ISSUE_AT(r_, stage_, part_)                                                                            \
-    do {                                                                                                            \
-        if ((r_) < KT) MT_P_ISSUE(cur, (r_), stage_, part_);                                                        \
-        else MT_P_ISSUE(nxt, (r_)-KT, stage_, part_);                                                               \
-    } while (0)
 #define MT_P_FRAGS(buf_, stage_, kk_)                                                                               \
     do {                                                                                                            \
         const unsigned char* sb = lds + (stage_) * Cfg::STAGE_BYTES;                                                \
@@ -205,8 +214,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void gemm_bf16_persist_ke
     //      slice starts in: slice 0 landed for everyone, part 0 of slice STAGES-1 issued, first fragments in registers
 #pragma unroll
     for (int p = 0; p < STAGES - 1; ++p) {
-        MT_P_ISSUE(cur, p, p, 0);
-        MT_P_ISSUE(cur, p, p, 1);
+#pragma unroll
+        for (int part = 0; part < KK; ++part) MT_P_ISSUE(cur, p, p, part);
     }
     p_wait_vmcnt<LPS*(STAGES - 2)>();
     __builtin_amdgcn_s_barrier();
@@ -214,12 +223,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void gemm_bf16_persist_ke
     MT_P_FRAGS(0, 0, 0);
     int cs = 0;                                         // ring stage of the slice being multiplied
 
-    // epilogue geometry: a parked row is WN float32; on the way out NCH lanes cover a row with 4 columns each
+    // epilogue geometry: a parked row is PARK_COLS float32; on the way out NCH lanes cover a row with 4 columns each
     constexpr int ROWB = Cfg::PARK_ROWB;
     constexpr int NCH = ROWB / 16;
     constexpr int RPW = ROWB >= 256 ? 1 : 256 / ROWB;
     constexpr int ROWS_PER_INST = 64 / NCH;
     constexpr int NIT = 32 / ROWS_PER_INST;
+    constexpr int JPB = Cfg::PARK_COLS / 32;                  // 32-column MFMA blocks per parked block
+    constexpr int NCB = Cfg::WN / Cfg::PARK_COLS;             // parked blocks across the wavefront's sub-tile
     static_assert(NCH <= 64 && 64 % NCH == 0, "row must split evenly over lanes");
     unsigned char* park = lds + Cfg::RING_BYTES + wave * Cfg::PARK_BYTES;
     const int c = lane % NCH;
@@ -234,70 +245,88 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void gemm_bf16_persist_ke
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][jj][e] = 0.f;
 
-        for (int kt = 0; kt < KT; ++kt) {
-            const int ns = cs + 1 == STAGES ? 0 : cs + 1;          // stage of slice kt+1
-            const int ps = cs == 0 ? STAGES - 1 : cs - 1;          // stage of slice kt+STAGES-1
-            // K step 0: fragments of step 1, second half of the loads of slice kt+STAGES-1
-            MT_P_FRAGS(1, cs, 1);
-            MT_P_ISSUE_AT(kt + STAGES - 1, ps, 1);
-            MT_P_MFMAS(0);
-            p_interleave<TMI * TNI, TMI + TNI, LPP>();
-            __builtin_amdgcn_sched_barrier(0);
-            // sync point: this wavefront's reads of slice kt are in registers, slice kt+1 must have landed
-            p_wait_lgkmcnt0();
-            p_wait_vmcnt<LPS*(STAGES - 2)>();
-            __builtin_amdgcn_s_barrier();
-            MT_P_ISSUE_AT(kt + STAGES, cs, 0);                       // stage cs was just vacated by everyone
-            MT_P_FRAGS(0, ns, 0);
-            MT_P_MFMAS(1);
-            p_interleave<TMI * TNI, TMI + TNI, LPP>();
-            __builtin_amdgcn_sched_barrier(0);
-            cs = ns;
-        }
+        // One K slice: K steps 0 .. KK-2 read the fragments of the next step and issue the next part of the loads of
+        // slice kt+STAGES-1 (tile T1_, slice R1_); the last step follows the sync point (this wavefront's reads of
+        // slice kt are in registers, slice kt+1 must have landed for everyone), refills the stage just vacated with
+        // part 0 of slice kt+STAGES (tile T0_, slice R0_) and reads the first fragments of slice kt+1.
+        // No branch inside: a branch would cut the block the scheduler and the wait-count pass see, and the
+        // multiplications of one step would then wait for the fragment reads of the next.
+#define MT_P_SLICE(T1_, R1_, T0_, R0_)                                                                              \
+        do {                                                                                                        \
+            const int ns = cs + 1 == STAGES ? 0 : cs + 1;                                                           \
+            const int ps = cs == 0 ? STAGES - 1 : cs - 1;                                                           \
+            _Pragma("unroll") for (int kk = 0; kk < KK - 1; ++kk) {                                                 \
+                MT_P_FRAGS((kk + 1) & 1, cs, kk + 1);                                                               \
+                MT_P_ISSUE(T1_, R1_, ps, kk + 1);                                                                   \
+                MT_P_MFMAS(kk & 1);                                                                                 \
+                p_interleave<TMI * TNI, TMI + TNI, LPP, MT_P_DSPER>();                                                          \
+                __builtin_amdgcn_sched_barrier(0);                                                                  \
+            }                                                                                                       \
+            p_wait_lgkmcnt0();                                                                                      \
+            p_wait_vmcnt<LPS*(STAGES - 2)>();                                                                       \
+            __builtin_amdgcn_s_barrier();                                                                           \
+            MT_P_ISSUE(T0_, R0_, cs, 0);                                                                            \
+            MT_P_FRAGS(0, ns, 0);                                                                                   \
+            MT_P_MFMAS((KK - 1) & 1);                                                                               \
+            p_interleave<TMI * TNI, TMI + TNI, LPP, MT_P_DSPER>();                                                              \
+            __builtin_amdgcn_sched_barrier(0);                                                                      \
+            cs = ns;                                                                                                \
+        } while (0)
+        // slices whose refills still belong to this tile; the one whose second refill is the next tile's slice 0;
+        // the last STAGES-1 slices, which fetch the next tile's first slices
+        int kt = 0;
+        for (; kt < KT - STAGES; ++kt) MT_P_SLICE(cur, kt + STAGES - 1, cur, kt + STAGES);
+        MT_P_SLICE(cur, KT - 1, nxt, 0);
+        for (kt = 1; kt < STAGES; ++kt) MT_P_SLICE(nxt, kt - 1, nxt, kt);
+#undef MT_P_SLICE
 
-        // ---- epilogue of tile `cur`, wavefront-private: park one 32-row block of raw accumulators, read it back
-        //      row-contiguously (4 consecutive columns per lane), bias / activation / residual, store row segments
-        const int n = cur.n0 + wn0 + c * 4;
-        const bool n_ok = n < s.N;                               // N % 4 == 0
-        float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (g.bias[cur.grp] && n_ok) bv = *reinterpret_cast<const float4*>(g.bias[cur.grp] + n);
+        // ---- epilogue of tile `cur`, wavefront-private: park a 32-row x PARK_COLS block of raw accumulators, read it
+        //      back row-contiguously (4 consecutive columns per lane), bias / activation / residual, store row segments
         const float* __restrict__ res = g.residual[cur.grp];
+        const float* __restrict__ bias = g.bias[cur.grp];
         unsigned char* __restrict__ Cout = static_cast<unsigned char*>(g.C[cur.grp]);
         const size_t ldc_b = (size_t)s.ldc * (OUT_F32 ? 4 : 2), ldr_b = (size_t)s.ldr * 4;
 #pragma unroll
-        for (int p = 0; p < TMI; ++p) {
-            const int key_w = (l32 / RPW) & (NCH - 1);
+        for (int cb = 0; cb < NCB; ++cb) {
+            const int n = cur.n0 + wn0 + cb * Cfg::PARK_COLS + c * 4;
+            const bool n_ok = n < s.N;                               // N % 4 == 0
+            float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (bias && n_ok) bv = *reinterpret_cast<const float4*>(bias + n);
 #pragma unroll
-            for (int jj = 0; jj < TNI; ++jj)
+            for (int p = 0; p < TMI; ++p) {
+                const int key_w = (l32 / RPW) & (NCH - 1);
 #pragma unroll
-                for (int qq = 0; qq < 4; ++qq) {
-                    const int chunk = (jj * 32 + qq * 8 + half * 4) >> 2;
-                    const f32x16& a = acc[p][jj];
-                    *reinterpret_cast<float4*>(park + l32 * ROWB + ((chunk ^ key_w) << 4)) =
-                        make_float4(a[qq * 4 + 0], a[qq * 4 + 1], a[qq * 4 + 2], a[qq * 4 + 3]);
-                }
-            // the same wavefront reads back what it wrote: LDS operations of one wavefront execute in order
+                for (int jj = 0; jj < JPB; ++jj)
 #pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                const int ml = it * ROWS_PER_INST + lane / NCH;
-                const int key = (ml / RPW) & (NCH - 1);
-                const float4 v = *reinterpret_cast<const float4*>(park + ml * ROWB + ((c ^ key) << 4));
-                const int mm = cur.m0 + wm0 + p * 32 + ml;
-                const bool ok = n_ok && mm < M;
-                float4 o;
-                o.x = p_act<ACT>(v.x + bv.x);
-                o.y = p_act<ACT>(v.y + bv.y);
-                o.z = p_act<ACT>(v.z + bv.z);
-                o.w = p_act<ACT>(v.w + bv.w);
-                if constexpr (OUT_F32) {
-                    if (res && ok) {
-                        const float4 rv = *reinterpret_cast<const float4*>(reinterpret_cast<const unsigned char*>(res) + mm * ldr_b + (size_t)n * 4);
-                        o.x += rv.x; o.y += rv.y; o.z += rv.z; o.w += rv.w;
+                    for (int qq = 0; qq < 4; ++qq) {
+                        const int chunk = (jj * 32 + qq * 8 + half * 4) >> 2;
+                        const f32x16& a = acc[p][cb * JPB + jj];
+                        *reinterpret_cast<float4*>(park + l32 * ROWB + ((chunk ^ key_w) << 4)) =
+                            make_float4(a[qq * 4 + 0], a[qq * 4 + 1], a[qq * 4 + 2], a[qq * 4 + 3]);
                     }
-                    if (ok) *reinterpret_cast<float4*>(Cout + mm * ldc_b + (size_t)n * 4) = o;
-                } else {
-                    bf16x4 ob = {(__bf16)o.x, (__bf16)o.y, (__bf16)o.z, (__bf16)o.w};
-                    if (ok) *reinterpret_cast<bf16x4*>(Cout + mm * ldc_b + (size_t)n * 2) = ob;
+                // the same wavefront reads back what it wrote: LDS operations of one wavefront execute in order
+#pragma unroll
+                for (int it = 0; it < NIT; ++it) {
+                    const int ml = it * ROWS_PER_INST + lane / NCH;
+                    const int key = (ml / RPW) & (NCH - 1);
+                    const float4 v = *reinterpret_cast<const float4*>(park + ml * ROWB + ((c ^ key) << 4));
+                    const int mm = cur.m0 + wm0 + p * 32 + ml;
+                    const bool ok = n_ok && mm < M;
+                    float4 o;
+                    o.x = p_act<ACT>(v.x + bv.x);
+                    o.y = p_act<ACT>(v.y + bv.y);
+                    o.z = p_act<ACT>(v.z + bv.z);
+                    o.w = p_act<ACT>(v.w + bv.w);
+                    if constexpr (OUT_F32) {
+                        if (res && ok) {
+                            const float4 rv = *reinterpret_cast<const float4*>(reinterpret_cast<const unsigned char*>(res) + mm * ldr_b + (size_t)n * 4);
+                            o.x += rv.x; o.y += rv.y; o.z += rv.z; o.w += rv.w;
+                        }
+                        if (ok) *reinterpret_cast<float4*>(Cout + mm * ldc_b + (size_t)n * 4) = o;
+                    } else {
+                        bf16x4 ob = {(__bf16)o.x, (__bf16)o.y, (__bf16)o.z, (__bf16)o.w};
+                        if (ok) *reinterpret_cast<bf16x4*>(Cout + mm * ldc_b + (size_t)n * 2) = ob;
+                    }
                 }
             }
         }
@@ -306,17 +335,16 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void gemm_bf16_persist_ke
     // the ring still receives the repeat loads issued past the last tile: they must land before the LDS is released
     p_wait_vmcnt<0>();
 #undef MT_P_ISSUE
-#undef MT_P_ISSUE_AT
 #undef MT_P_FRAGS
 #undef MT_P_MFMAS
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool OUT_F32, int ACT>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int PARK_COLS, bool OUT_F32, int ACT>
 hipError_t p_launch_one(const GemmGroup& g, const GemmShape& s, int n_wg, hipStream_t stream)
 {
-    using Cfg = PCfg<BM, BN, WAVES_M, WAVES_N, STAGES>;
+    using Cfg = PCfg<BM, BN, WAVES_M, WAVES_N, BK, STAGES, PARK_COLS>;
     const int tiles_n = (s.N + BN - 1) / BN;
-    auto kfn = gemm_bf16_persist_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, OUT_F32, ACT>;
+    auto kfn = gemm_bf16_persist_kernel<BM, BN, WAVES_M, WAVES_N, BK, STAGES, PARK_COLS, OUT_F32, ACT>;
     static std::atomic<uint64_t> lds_raised{0};
     hipError_t e = ensure_dynamic_lds((const void*)kfn, Cfg::LDS_BYTES, lds_raised);
     if (e != hipSuccess) return e;
@@ -324,17 +352,17 @@ hipError_t p_launch_one(const GemmGroup& g, const GemmShape& s, int n_wg, hipStr
     return hipGetLastError();
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int PARK_COLS>
 hipError_t p_launch_cfg(const GemmGroup& g, const GemmShape& s, int n_wg, hipStream_t stream)
 {
     if (s.out_f32) {
         if (s.act != ACT_NONE) return hipErrorInvalidValue;
-        return p_launch_one<BM, BN, WAVES_M, WAVES_N, STAGES, true, ACT_NONE>(g, s, n_wg, stream);
+        return p_launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, PARK_COLS, true, ACT_NONE>(g, s, n_wg, stream);
     }
     switch (s.act) {
-        case ACT_NONE: return p_launch_one<BM, BN, WAVES_M, WAVES_N, STAGES, false, ACT_NONE>(g, s, n_wg, stream);
-        case ACT_GELU_ERF: return p_launch_one<BM, BN, WAVES_M, WAVES_N, STAGES, false, ACT_GELU_ERF>(g, s, n_wg, stream);
-        case ACT_GELU_TANH: return p_launch_one<BM, BN, WAVES_M, WAVES_N, STAGES, false, ACT_GELU_TANH>(g, s, n_wg, stream);
+        case ACT_NONE: return p_launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, PARK_COLS, false, ACT_NONE>(g, s, n_wg, stream);
+        case ACT_GELU_ERF: return p_launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, PARK_COLS, false, ACT_GELU_ERF>(g, s, n_wg, stream);
+        case ACT_GELU_TANH: return p_launch_one<BM, BN, WAVES_M, WAVES_N, BK, STAGES, PARK_COLS, false, ACT_GELU_TANH>(g, s, n_wg, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -358,17 +386,32 @@ bool gemm_bf16_persist_takes(const GemmShape& s)
 {
     // K slices must outnumber the ring stages (a tile's refills reach at most into the NEXT tile), no K split,
     // no sub-problems; 32-bit byte offsets as in the tiled kernel
-    return s.splits == 1 && s.n_sub <= 1 && !s.d_sub_rows && s.K % 32 == 0 && s.K / 32 >= 4 && s.N % 4 == 0 &&
+    return s.splits == 1 && s.n_sub <= 1 && !s.d_sub_rows && s.K % 64 == 0 && s.K / 64 >= 4 && s.N % 4 == 0 &&
            (s.act == ACT_NONE || (!s.out_f32 && (s.act == ACT_GELU_ERF || s.act == ACT_GELU_TANH)));
 }
 
-hipError_t launch_gemm_bf16_persist(const GemmGroup& g, const GemmShape& s, hipStream_t stream)
+// Rule from measurements at BERT-base and BERT-large widths (1 and 8 problems, 7 k to 20 k rows): with at least one
+// 256x256 tile per compute unit the persistent form wins by 5-35 % (most where the output is float32 or K is
+// long).  The GELU epilogue is pure vector work that nothing overlaps when one workgroup owns the compute unit, so
+// such launches come here only when a part-filled last round of tiles costs little (8 rounds and more by the row
+// bound).  The row bound over-counts (padding is dropped on the device), so this errs towards the tiled kernel.
+bool gemm_bf16_persist_wants(const GemmShape& s)
+{
+    if (!gemm_bf16_persist_takes(s)) return false;
+    const long tiles = (long)s.G * ((s.M + 255) / 256) * ((s.N + 255) / 256);
+    const bool gelu = s.act == ACT_GELU_ERF || s.act == ACT_GELU_TANH;
+    return tiles >= (long)(gelu ? 8 : 1) * cu_count();
+}
+
+hipError_t launch_gemm_bf16_persist(const GemmGroup& g, const GemmShape& s, int form, hipStream_t stream)
 {
     if (!gemm_bf16_persist_takes(s)) return hipErrorInvalidValue;
     const long tiles = (long)s.G * ((s.M + 255) / 256) * ((s.N + 255) / 256);
     const int n_wg = (int)std::min<long>(tiles, cu_count());
     if (n_wg < kPXcds) return hipErrorInvalidValue;          // every XCD's tile range needs a workgroup
-    return p_launch_cfg<256, 256, 2, 4, 3>(g, s, n_wg, stream);
+    if (form == 1) return p_launch_cfg<256, 256, 2, 4, 64, 2, 32>(g, s, n_wg, stream);      // 128 KB ring of two 64-wide slices
+    if (form == 2) return p_launch_cfg<256, 256, 2, 4, 32, 4, 32>(g, s, n_wg, stream);      // 128 KB ring of four 32-wide slices
+    return p_launch_cfg<256, 256, 2, 4, 32, 3, 64>(g, s, n_wg, stream);                       // 96 KB ring, 64 KB park
 }
 
 }  // namespace mt
