@@ -327,7 +327,8 @@ int mt_op_layernorm(const float* d_x, const float* d_gamma, const float* d_beta,
                     void* d_out_bf16, int32_t M, int32_t H, void* hip_stream);
 
 /* Tuning aid for benchmarks: force one bf16 GEMM tile configuration for all later launches in this
- * process (0 = choose by shape, the default; 1..26 except 13 = a fixed tile configuration, 13 = the few-row kernel;
+ * process (0 = choose by shape, the default; 1..26 except 13 = a fixed tile configuration, 13 = the few-row kernel, 27..29 = the persistent
+ * kernel's three ring shapes;
  * any other value resets to 0).  One process-wide setting, not thread-safe: for single-threaded tuning sweeps
  * only, never set while forward passes are being enqueued from other threads.  Returns the previous value. */
 int mt_debug_set_gemm_tile(int32_t sel);

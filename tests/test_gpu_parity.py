@@ -84,6 +84,46 @@ def test_gemm_bf16_vs_oracle(tile):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("tile", [27, 28, 29])
+def test_gemm_bf16_persistent_vs_oracle(tile):
+    """The persistent contraction (one workgroup per compute unit walking a tile list) in its three ring shapes:
+    8 problems of ragged M and N (more 256x256 tiles than compute units, so that workgroups really walk from tile to tile and
+    from problem to problem), every epilogue the model uses."""
+    say(f"gemm_bf16 persistent, selector {tile}")
+    rng = np.random.default_rng(40 + tile)
+    G, M, N, K = 8, 1560, 1300, 320          # 8 x 7 x 6 = 336 tiles for 256 workgroups
+    A = bf16_grid(rng.standard_normal((G, M, K)))
+    W = bf16_grid(rng.standard_normal((G, N, K)) * 0.1)
+    bias = rng.standard_normal((G, N)).astype(np.float32)
+    res = rng.standard_normal((G, M, N)).astype(np.float32)
+    ref = np.stack([oracle.linear(A[g], W[g], bias[g]) for g in range(G)])
+    scale = max(1.0, float(np.abs(ref).max()))
+    prev = mt.set_gemm_tile(tile)
+    try:
+        dA, dW, db, dr = dev(A, torch.bfloat16), dev(W, torch.bfloat16), dev(bias), dev(res)
+        out = mt.op_linear_batched(mt.MT_BF16, dA, dW, db, None, 0, True).cpu().numpy()
+        assert np.abs(out - ref).max() <= 2e-4 * scale
+        out = mt.op_linear_batched(mt.MT_BF16, dA, dW, db, dr, 0, True).cpu().numpy()
+        assert np.abs(out - (ref.astype(np.float64) + res)).max() <= 2e-4 * scale
+        out = mt.op_linear_batched(mt.MT_BF16, dA, dW, db, None, 1, False).float().cpu().numpy()
+        g = np.stack([oracle.gelu(ref[i]) for i in range(G)])
+        assert np.abs(out - g).max() <= 2 ** -8 * np.abs(g).max() + 1e-3
+        out = mt.op_linear_batched(mt.MT_BF16, dA[0], dW, None, None, 0, False).float().cpu().numpy()      # shared A
+        ref0 = np.stack([oracle.linear(A[0], W[i], None) for i in range(G)])
+        assert np.abs(out - ref0).max() <= 2 ** -8 * np.abs(ref0).max() + 1e-3
+        # untouched beyond the ragged edges: a canary row and column around a [M][N] window of a larger buffer
+        big = torch.full((G, M + 1, N + 8), 7.0, dtype=torch.float32, device="cuda")
+        rc = mt.lib().mt_op_linear_batched(mt.MT_BF16, G, dA.data_ptr(), M * K, K, dW.data_ptr(), N * K, db.data_ptr(), N, None, 0,
+                                           big.data_ptr(), (M + 1) * (N + 8), N + 8, M, N, K, 0, 1, None)
+        assert rc == mt.MT_OK
+        o = big.cpu().numpy()
+        assert np.abs(o[:, :M, :N] - ref).max() <= 2e-4 * scale
+        assert (o[:, M, :] == 7.0).all() and (o[:, :, N:] == 7.0).all()
+    finally:
+        mt.set_gemm_tile(prev)
+    torch.cuda.synchronize()
+
+
 def test_gemm_bf16_bert_shapes_sampled():
     """BERT-base shapes in the default (shape-chosen) tile configuration, checked on sampled rows."""
     rng = np.random.default_rng(3)
