@@ -216,8 +216,8 @@ int mt_forward_tokens(mt_model* m, const int32_t* d_input_ids, const int32_t* d_
  * fork; tasks wanted by the same set of sequences form a group whose sequences are gathered into a row order of
  * their own, on which the group's branch layers, poolers and classifiers run.  Logits of wanted (b, t) pairs are
  * written to d_out_logits[b][mt_logit_offset(t)..]; all other entries are left untouched.  batch <= 1024.
- * d_token_type_ids may be NULL.  Errors as mt_forward, and CONFIG when a wanted task has a token-level head (not
- * routed).  After this call mt_read_hidden serves trunk taps only.
+ * d_token_type_ids may be NULL.  Errors as mt_forward; NULL when a wanted task has a token-level head (that needs
+ * mt_forward_routed_tokens).  After this call mt_read_hidden serves trunk taps only.
  * With more than one group the groups run side by side on up to four streams that the model owns (default
  * priority; the first routed call creates them and their events, mt_destroy releases them): they wait for the
  * trunk on hip_stream through an event and hip_stream waits for them before the call's work counts as done, so
@@ -225,6 +225,18 @@ int mt_forward_tokens(mt_model* m, const int32_t* d_input_ids, const int32_t* d_
  */
 int mt_forward_routed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask,
                       int32_t batch, int32_t seq, const uint8_t* h_route, float* d_out_logits, void* hip_stream);
+
+/*
+ * mt_forward_routed for models with token-level tasks (Section 5.2 x Appendix E's tagging tasks): as above, plus
+ *   d_out_token_logits [batch][seq][C_tok] float32: for every wanted pair (b, t) of a MT_HEAD_TOKEN task, task t's
+ *               columns of sequence b are written at every position (logits where d_attn_mask is 1, zeros where it
+ *               is 0); columns of unwanted pairs are left untouched.  A routed token-level task evaluates all its
+ *               layers on every token of its sequences.
+ * d_out_logits may be NULL when no wanted task has a sequence head, d_out_token_logits when none has a token head.
+ */
+int mt_forward_routed_tokens(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask,
+                             int32_t batch, int32_t seq, const uint8_t* h_route, float* d_out_logits, float* d_out_token_logits,
+                             void* hip_stream);
 
 /* Column of task t's first logit inside the row of its kind (the per-sequence row for MT_HEAD_SEQUENCE, the
  * per-token row for MT_HEAD_TOKEN), or MT_ERR_SHAPE (task out of range) / MT_ERR_CONFIG (task is of the other

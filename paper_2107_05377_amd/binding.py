@@ -27,7 +27,7 @@ EXPORTS = ["mt_create", "mt_destroy", "mt_weight_bytes", "mt_workspace_bytes", "
            "mt_forward", "mt_logit_offset", "mt_n_logits", "mt_layer_count", "mt_last_error", "mt_error_name",
            "mt_read_hidden", "mt_profile_enable", "mt_profile_read", "mt_op_linear", "mt_op_attention",
            "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed", "mt_op_linear_sub", "mt_op_first_token_pool", "mt_schedule_steps", "mt_forward_routed",
-           "mt_forward_tokens", "mt_token_logit_offset", "mt_n_token_logits", "mt_forward_static", "mt_forward_multi"]
+           "mt_forward_tokens", "mt_token_logit_offset", "mt_n_token_logits", "mt_forward_static", "mt_forward_multi", "mt_forward_routed_tokens"]
 MT_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 
 
@@ -70,6 +70,7 @@ def lib():
         L.mt_forward_typed.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_routed.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_tokens.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+        L.mt_forward_routed_tokens.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
         L.mt_logit_offset.argtypes = [vp, i32]
         L.mt_token_logit_offset.argtypes = [vp, i32]
         L.mt_n_token_logits.argtypes = [vp]
@@ -273,6 +274,16 @@ class Model:
         self._check(lib().mt_forward_routed(self.h, _ptr(ids), _ptr(type_ids) if type_ids is not None else None, _ptr(mask), b, s,
                                             r.ctypes.data_as(C.c_void_p), _ptr(out), _stream()))
         return out
+
+    def forward_routed_tokens(self, ids, mask, route, out, out_tokens, type_ids=None):
+        """mt_forward_routed_tokens: as forward_routed, token-level tasks' logits of wanted pairs go into `out_tokens`."""
+        b, s = ids.shape
+        r = np.ascontiguousarray(np.asarray(route) != 0, dtype=np.uint8)
+        assert r.shape == (b, self.cfg.n_tasks)
+        self._check(lib().mt_forward_routed_tokens(self.h, _ptr(ids), _ptr(type_ids) if type_ids is not None else None, _ptr(mask), b, s,
+                                                   r.ctypes.data_as(C.c_void_p), _ptr(out) if out is not None and out.numel() else None,
+                                                   _ptr(out_tokens) if out_tokens is not None and out_tokens.numel() else None, _stream()))
+        return out, out_tokens
 
     def read_hidden(self, task: int, layer: int, batch: int, seq: int):
         import torch

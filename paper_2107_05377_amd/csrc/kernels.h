@@ -172,7 +172,8 @@ hipError_t launch_classifier(const ClsGroup& g, int G, int B, int H, int maxC, i
                              hipStream_t stream);
 
 // Token-level heads: out[g][p*ldo + c] = Wc[g][c] . x[g][row_of[p]] + bc[g][c] for every position p = b*S+s that is a
-// kept row (row_of[p] in [0, *n_rows)), zeros for the positions that are not.  x is float32 in the padding-free order.
+// kept row (row_of[p] in [0, *n_rows)), zeros for the positions that are not; positions with row_of[p] == -2 are
+// left untouched.  x is float32 in the padding-free order.
 struct TokGroup {
     const float* x[kMaxGroup];        // [rows][H]
     const void* Wc[kMaxGroup];        // [C][H]
@@ -207,6 +208,11 @@ struct RouteIdx {
 // c_src[r] = row of the batch order that compact row r copies, c_seq[i] = idx.seq[i] (as int32, for the logits rows).
 hipError_t launch_route_map(const RouteIdx& idx, int n_sel, const int32_t* g_start, const int32_t* g_len, int32_t* c_start,
                             int32_t* c_len, int32_t* c_src, int32_t* c_seq, int32_t* c_n, hipStream_t stream);
+// c_rowof[b*S+s] for all B*S positions of the batch: the sub-batch's compact row of a real token of a chosen sequence,
+// -1 for its padded positions, -2 for positions of sequences outside the sub-batch (launch_token_classifier leaves
+// those untouched).  row_of / g_start: the batch's row map; c_start: the sub-batch's sequence starts.
+hipError_t launch_route_rowof(const RouteIdx& idx, int n_sel, int B, int S, const int32_t* row_of, const int32_t* g_start,
+                              const int32_t* c_start, int32_t* c_rowof, hipStream_t stream);
 // out_f[r] = in_f[c_src[r]] (float32 rows) and out_a[r] = in_a[c_src[r]] (act_bytes per element; both optional), r < *c_n <= max_rows.
 hipError_t launch_route_gather(const float* in_f, const void* in_a, float* out_f, void* out_a, const int32_t* c_src, const int32_t* c_n,
                                int max_rows, int H, int act_bytes, hipStream_t stream);

@@ -81,6 +81,7 @@ struct ClsScratch {   // per task with own layers: compact [max_batch] x ... buf
 };
 struct RouteMapOff {   // byte offsets of a sub-batch row map (per-sequence routing), one per task
     size_t n, src, start, len, seq;
+    size_t rowof;      // position -> compact row, for token-level heads
 };
 struct ProfRec {
     int klass;
@@ -799,6 +800,7 @@ int mt_create(const mt_config* cfg, mt_model** out)
         r.start = sb.take(MB * 4);
         r.len = sb.take(MB * 4);
         r.seq = sb.take(MB * 4);
+        r.rowof = sb.take(M * 4);
         m->route.push_back(r);
     }
     m->rm_n = sb.take(4);
@@ -1053,7 +1055,6 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
         if (h_task_mask && !h_task_mask[t]) continue;
         if (!m->task_loaded[t]) return fail(m, MT_ERR_STATE, "mt_forward: task %d has no weights loaded", t);
         if (m->tasks[t].head == MT_HEAD_TOKEN) {
-            if (h_route) return fail(m, MT_ERR_CONFIG, "mt_forward_routed: task %d has a token-level head, which is not routed", t);
             if (!d_out_token_logits)
                 return fail(m, MT_ERR_NULL, "mt_forward: task %d has a token-level head: pass a token logits buffer (mt_forward_tokens)", t);
         } else if (!d_out_logits) {
@@ -1208,7 +1209,7 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
     };
 
     // ---- token-level heads: one linear layer on every kept row of the task's final state, scattered to [B][S][C_tok]
-    auto run_token_heads = [&](const std::vector<int>& all) {
+    auto run_token_heads = [&](Launcher& L, const std::vector<int>& all, bool gathered, const int32_t* pos_row, const int32_t* n_rows) {
         std::vector<int> list;
         for (int t : all)
             if (m->tasks[t].head == MT_HEAD_TOKEN) list.push_back(t);
@@ -1219,22 +1220,22 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
             for (int i = 0; i < n; ++i) {
                 const int t = list[lo + i];
                 const mt_task_desc& d = m->tasks[t];
-                tg.x[i] = d.n_layers > 0 ? (const float*)(ws + m->task_xf[t])
-                                         : (const float*)(ws + m->tap_f[m->tap_of_layer[d.fork_layer]]);
+                tg.x[i] = (d.n_layers > 0 || gathered) ? (const float*)(ws + m->task_xf[t])
+                                                       : (const float*)(ws + m->tap_f[m->tap_of_layer[d.fork_layer]]);
                 tg.Wc[i] = W + m->taskw[t].Wc;
                 tg.bc[i] = (const float*)(W + m->taskw[t].bc);
                 tg.out[i] = d_out_token_logits + m->logit_off[t];
                 tg.C[i] = d.n_classes;
             }
             L.begin(MT_K_POOL);
-            L.check(launch_token_classifier(tg, n, B * S, H, bf ? 1 : 0, m->C_tok, rm.row_of, rm.n_rows, L.st));
+            L.check(launch_token_classifier(tg, n, B * S, H, bf ? 1 : 0, m->C_tok, pos_row, n_rows, L.st));
             L.end();
         }
     };
 
     if (!h_route) {
         run_heads(L, enabled, rm, B, false, nullptr);
-        run_token_heads(enabled);
+        run_token_heads(L, enabled, false, rm.row_of, rm.n_rows);
     } else {
         // ---- per-sequence routing: tasks wanted by the same set of sequences form a group; the group's sequences are
         // gathered from each task's tap into a padding-free row order of their own, on which the task's layers,
@@ -1301,7 +1302,7 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
                     if (stage >= d.n_layers) continue;
                     const float* in_f = (const float*)(ws + m->task_xf[t]);
                     const void* in_b = bf ? (const void*)(ws + m->task_xb[t]) : nullptr;
-                    if (stage == d.n_layers - 1)
+                    if (stage == d.n_layers - 1 && d.head == MT_HEAD_SEQUENCE)
                         last.push_back(LastIO{in_f, bf ? in_b : (const void*)in_f, &m->taskw[t].layers[stage], &m->task_scr[t], &m->task_cls[t]});
                     else
                         full.push_back(LayerIO{in_f, in_b, &m->taskw[t].layers[stage], &m->task_scr[t], (float*)(ws + m->task_xf[t]),
@@ -1317,6 +1318,17 @@ static int forward_impl(mt_model* m, const int32_t* d_input_ids, const int32_t* 
                 }
             }
             run_heads(GL, grp_tasks, crm, nb, true, c_seq);
+            bool any_token = false;
+            for (int t : grp_tasks) any_token = any_token || m->tasks[t].head == MT_HEAD_TOKEN;
+            if (any_token) {
+                // token-level heads: logits of the group's real tokens go to their own positions of [B][S][C_tok], zeros to
+                // the padded positions of its sequences, nothing to the other sequences
+                int32_t* c_rowof = (int32_t*)(ws + ro.rowof);
+                GL.begin(MT_K_POOL);
+                GL.check(launch_route_rowof(idx, nb, B, S, rm.row_of, rm.seq_start, crm.seq_start, c_rowof, GL.st));
+                GL.end();
+                run_token_heads(GL, grp_tasks, true, c_rowof, crm.n_rows);
+            }
             if (side) L.check(LS.first_err);
         }
         if (side) {
@@ -1448,6 +1460,16 @@ int mt_forward_routed(mt_model* m, const int32_t* d_input_ids, const int32_t* d_
     if (!m) return MT_ERR_NULL;
     if (!h_route) return fail(m, MT_ERR_NULL, "mt_forward_routed: null routing table");
     return forward_impl(m, d_input_ids, d_token_type_ids, d_attn_mask, batch, seq, nullptr, h_route, d_out_logits, nullptr, hip_stream);
+}
+
+int mt_forward_routed_tokens(mt_model* m, const int32_t* d_input_ids, const int32_t* d_token_type_ids, const int32_t* d_attn_mask,
+                             int32_t batch, int32_t seq, const uint8_t* h_route, float* d_out_logits, float* d_out_token_logits,
+                             void* hip_stream)
+{
+    if (!m) return MT_ERR_NULL;
+    if (!h_route) return fail(m, MT_ERR_NULL, "mt_forward_routed_tokens: null routing table");
+    return forward_impl(m, d_input_ids, d_token_type_ids, d_attn_mask, batch, seq, nullptr, h_route, d_out_logits, d_out_token_logits,
+                        hip_stream);
 }
 
 int mt_read_hidden(mt_model* m, int32_t task, int32_t layer, float* d_out, size_t out_bytes, void* hip_stream)

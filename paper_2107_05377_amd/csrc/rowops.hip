@@ -356,6 +356,7 @@ __global__ __launch_bounds__(256) void classifier_kernel(ClsGroup g, int B, int 
 // Token-level head.  A workgroup owns 16 consecutive positions, each of its 4 wavefronts 4 of them, so that a row
 // of Wc is fetched once per 4 positions; lanes stride over the hidden dimension, float32 accumulation.
 constexpr int kTokPosPerWave = 4;
+constexpr int kRowSkip = -2;          // row_of value: the position belongs to no sequence of this launch (see launch_route_rowof)
 template <typename TW>
 __global__ __launch_bounds__(256) void token_classifier_kernel(TokGroup g, int n_pos, int H, int64_t ldo,
                                                                const int32_t* __restrict__ row_of,
@@ -368,12 +369,13 @@ __global__ __launch_bounds__(256) void token_classifier_kernel(TokGroup g, int n
     const int kept = *n_rows;
     const int C = g.C[grp];
     const float* xr[kTokPosPerWave];
-    bool live[kTokPosPerWave];
+    bool live[kTokPosPerWave], skip[kTokPosPerWave];
 #pragma unroll
     for (int j = 0; j < kTokPosPerWave; ++j) {
         const int p = p0 + j;
-        const int r = p < n_pos ? row_of[p] : -1;
+        const int r = p < n_pos ? row_of[p] : kRowSkip;
         live[j] = r >= 0 && r < kept;
+        skip[j] = r == kRowSkip;
         xr[j] = g.x[grp] + (size_t)(live[j] ? r : 0) * H;
     }
     const bool any = live[0] || live[1] || live[2] || live[3];
@@ -391,7 +393,7 @@ __global__ __launch_bounds__(256) void token_classifier_kernel(TokGroup g, int n
 #pragma unroll
         for (int j = 0; j < kTokPosPerWave; ++j) {
             const float v = wave_sum(acc[j]);
-            if (lane == 0 && p0 + j < n_pos) g.out[grp][(size_t)(p0 + j) * ldo + c] = live[j] ? v + bias : 0.f;
+            if (lane == 0 && !skip[j]) g.out[grp][(size_t)(p0 + j) * ldo + c] = live[j] ? v + bias : 0.f;
         }
     }
 }
@@ -411,6 +413,7 @@ __global__ __launch_bounds__(256) void token_classifier_rows_kernel(TokGroup g, 
     const int C = g.C[grp];
     float* out = g.out[grp] + (size_t)p * ldo;
     const int r = row_of[p];
+    if (r == kRowSkip) return;                        // not this launch's position: left untouched
     if (r < 0 || r >= *n_rows) {
         for (int c = lane; c < C; c += 64) out[c] = 0.f;
         return;
@@ -489,6 +492,36 @@ __global__ __launch_bounds__(256) void route_map_kernel(RouteIdx idx, int n_sel,
     for (int i = 0; i < n_sel; ++i) {
         const int src0 = g_start[idx.seq[i]], dst0 = start_s[i];
         for (int j = tid; j < len_s[i]; j += 256) c_src[dst0 + j] = src0 + j;
+    }
+}
+
+// Position -> compact row of a sub-batch, for the token-level heads of routed tasks: one workgroup per sequence of
+// the BATCH.  Positions of a sequence outside the sub-batch get kRowSkip (the classifier leaves them untouched),
+// padded positions of a chosen sequence -1 (it writes zeros), real tokens their compact row.
+__global__ __launch_bounds__(256) void route_rowof_kernel(RouteIdx idx, int n_sel, int S, const int32_t* __restrict__ row_of,
+                                                          const int32_t* __restrict__ g_start, const int32_t* __restrict__ c_start,
+                                                          int32_t* __restrict__ c_rowof)
+{
+    __shared__ int which;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    if (tid == 0) {
+        int lo = 0, hi = n_sel - 1, found = -1;       // idx.seq is ascending
+        while (lo <= hi) {
+            const int mid = (lo + hi) >> 1;
+            const int v = idx.seq[mid];
+            if (v == b) { found = mid; break; }
+            if (v < b) lo = mid + 1;
+            else hi = mid - 1;
+        }
+        which = found;
+    }
+    __syncthreads();
+    const int i = which;
+    const int shift = i >= 0 ? c_start[i] - g_start[b] : 0;
+    for (int s = tid; s < S; s += 256) {
+        const size_t p = (size_t)b * S + s;
+        const int r = row_of[p];
+        c_rowof[p] = i < 0 ? kRowSkip : (r < 0 ? -1 : r + shift);
     }
 }
 
@@ -644,6 +677,15 @@ hipError_t launch_route_map(const RouteIdx& idx, int n_sel, const int32_t* g_sta
     if (n_sel <= 0) return hipSuccess;
     if (n_sel > kMaxRouted || !g_start || !g_len || !c_start || !c_len || !c_src || !c_seq || !c_n) return hipErrorInvalidValue;
     hipLaunchKernelGGL(route_map_kernel, dim3(1), dim3(256), 0, stream, idx, n_sel, g_start, g_len, c_start, c_len, c_src, c_seq, c_n);
+    return hipGetLastError();
+}
+
+hipError_t launch_route_rowof(const RouteIdx& idx, int n_sel, int B, int S, const int32_t* row_of, const int32_t* g_start,
+                              const int32_t* c_start, int32_t* c_rowof, hipStream_t stream)
+{
+    if (B <= 0 || S <= 0) return hipSuccess;
+    if (n_sel < 0 || n_sel > kMaxRouted || !row_of || !g_start || !c_start || !c_rowof) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(route_rowof_kernel, dim3(B), dim3(256), 0, stream, idx, n_sel, S, row_of, g_start, c_start, c_rowof);
     return hipGetLastError();
 }
 

@@ -170,7 +170,7 @@ def test_token_level_heads_layout_and_checks():
     diff = L.mt_weight_bytes(h2) - L.mt_weight_bytes(h)
     assert 2 * 9 * 768 * 768 <= diff <= 2 * 9 * 768 * 768 + 3 * 768 * 4 + 4096
     L.mt_destroy(h2)
-    # a token-level task needs the token buffer, and is not routed
+    # a token-level task needs the token buffer
     fake = C.c_void_p(0x10000)     # never dereferenced: the calls below fail their host-side checks first
     assert L.mt_bind(h, fake, 1 << 40, fake, 1 << 40) == mt.MT_OK
     cfg = mt.make_config(spec)

@@ -1054,6 +1054,51 @@ def test_several_requests_in_one_forward_match_oracle(which):
     one.close()
 
 
+@pytest.mark.parametrize("which", ["fp32", "bf16"])
+def test_token_heads_under_per_sequence_routing(which):
+    """Routing with tagging tasks: a wanted (sequence, task) pair gets the oracle's token logits on its real tokens and
+    zeros on its padding; unwanted pairs and other tasks' columns are left untouched; sequence-level tasks of the
+    same call behave as in mt_forward_routed."""
+    spec = TOKF if which == "fp32" else TOKB
+    tr, tri, tps = _params(spec, True, 0.1 if which == "fp32" else 0.05)
+    model = _load(spec, tr, tri, tps)
+    ids, mask, _ = ms.make_inputs(spec, batch_index=1)
+    ref, ref_tok = oracle.Oracle(spec, tr, [p for p, _ in tps]).mt_forward(ids, mask, want_tokens=True)
+    B, S, T = ids.shape[0], ids.shape[1], spec.n_tasks
+    rng = np.random.default_rng(5)
+    route = (rng.random((B, T)) < 0.6).astype(np.uint8)
+    route[0, :] = 1
+    route[1, :] = 0
+    tok_tasks = [t for t in range(T) if spec.tasks[t].token_level]
+    route[:, tok_tasks[1]] = route[:, tok_tasks[0]]                 # two tagging tasks share a group
+    out = torch.full((B, model.n_logits), 9.0, device="cuda")
+    tok = torch.full((B, S, model.n_token_logits), 9.0, device="cuda")
+    model.forward_routed_tokens(dev(ids), dev(mask), route, out, tok)
+    got, got_tok = out.cpu().numpy(), tok.cpu().numpy()
+    tol_seq = 1e-4 * max(np.abs(ref).max(), 1e-3) if which == "fp32" else 2e-2
+    tol_tok = 1e-4 * max(np.abs(ref_tok).max(), 1e-3) if which == "fp32" else 2e-2
+    for t, task in enumerate(spec.tasks):
+        lo = spec.logit_offset(t)
+        sl = slice(lo, lo + task.n_classes)
+        for b in range(B):
+            real = mask[b].astype(bool)
+            if task.token_level:
+                if route[b, t]:
+                    assert np.abs(got_tok[b, real, sl] - ref_tok[b, real, sl]).max() <= tol_tok, (b, t)
+                    assert (got_tok[b, ~real, sl] == 0.0).all(), (b, t)
+                else:
+                    assert (got_tok[b, :, sl] == 9.0).all(), (b, t)
+            elif route[b, t]:
+                assert np.abs(got[b, sl] - ref[b, sl]).max() <= tol_seq, (b, t)
+            else:
+                assert (got[b, sl] == 9.0).all(), (b, t)
+    # the plain routed entry point has nowhere to put token logits
+    with pytest.raises(mt.MTError) as ei:
+        model.forward_routed(dev(ids), dev(mask), route, out)
+    assert ei.value.code == mt.MT_ERR_NULL
+    model.close()
+
+
 def test_read_hidden_refuses_states_the_last_forward_did_not_write():
     """A trunk tap is readable only if the last forward pass ran the trunk that deep: with the deeper tasks masked
     off the trunk stops at the deepest enabled fork, and with no task enabled nothing runs at all."""
