@@ -40,7 +40,7 @@ enum {
     MT_ERR_HIP = -6      /* a HIP runtime call failed */
 };
 
-enum { MT_BF16 = 0, MT_FP32_CHECK = 1 };     /* mt_config.precision */
+enum { MT_BF16 = 0, MT_FP32_CHECK = 1, MT_FP8_FFN = 2 };     /* mt_config.precision */
 enum { MT_GELU_ERF = 0, MT_GELU_TANH = 1 };  /* mt_config.gelu */
 enum { MT_HEAD_SEQUENCE = 0, MT_HEAD_TOKEN = 1 };  /* mt_task_desc.head */
 
@@ -73,6 +73,13 @@ typedef struct {
  * hidden/heads == 64, hidden % 64 == 0, ffn % 64 == 0 and max_seq <= 608 (the attention kernel keeps one
  * sequence's keys and values of a head in the 160 KB LDS).  MT_FP32_CHECK: everything float32 on
  * the vector ALUs, any shape, max_seq <= 4096, meant for validation.
+ * MT_FP8_FFN: MT_BF16 with the two feed-forward contractions of every layer that is evaluated on all token rows run
+ * in OCP FP8 E4M3 on the FP8 matrix cores (float32 accumulation); a reduced-precision serving variant in the spirit of
+ * the deployment note of Appendix E (half precision there).  Every feed-forward matrix W is additionally stored as
+ * E4M3(s W) with s the largest power of two that keeps s max|W| <= 448, undone exactly in the epilogue; the
+ * LayerNorm output that feeds the first contraction and the GELU output that feeds the second are rounded to E4M3
+ * (unit scale, saturating at +-448) instead of bfloat16.  Everything else, including the first-token-only last
+ * layer of every branch, is as in MT_BF16.  Needs hidden >= 192 and ffn >= 192 on top of MT_BF16's conditions.
  * max_batch*max_seq bounds the workspace; max_seq <= max_pos.
  */
 typedef struct {
@@ -337,6 +344,18 @@ int mt_op_attention(int32_t precision, const void* d_qkv, const int32_t* d_mask,
  * and bfloat16 d_out_bf16 (may be NULL). */
 int mt_op_layernorm(const float* d_x, const float* d_gamma, const float* d_beta, float eps, float* d_out_f32,
                     void* d_out_bf16, int32_t M, int32_t H, void* hip_stream);
+
+/* The FP8 contraction alone, as MT_FP8_FFN uses it: d_A [M][lda] and d_W [N][K] are E4M3 bytes (lda in elements, a
+ * multiple of 16), C = act(scale * A W^T + bias) (+ residual); out_kind 0 bfloat16, 1 float32 (d_residual allowed, no
+ * activation), 2 E4M3 (the value times out_scale, saturating).  act_kind 0 none, 1 GELU(erf), 2 GELU(tanh).
+ * Needs K % 64 == 0, K >= 192, N % 4 == 0.  Errors: NULL, SHAPE, HIP. */
+int mt_op_linear_fp8(const void* d_A, int64_t lda, const void* d_W, float scale, const float* d_bias, const float* d_residual,
+                     void* d_C, int64_t ldc, int32_t M, int32_t N, int32_t K, int32_t act_kind, int32_t out_kind, float out_scale,
+                     void* hip_stream);
+/* Host only: the conversion mt_load_weights applies to a feed-forward matrix in MT_FP8_FFN mode.  Returns the storage
+ * scale s (largest power of two with s max|w| <= 448; 1 for an all-zero matrix) and, if h_out is not NULL, writes
+ * E4M3(s w[i]) (round to nearest even, saturating) to h_out[i]. */
+float mt_debug_e4m3_quantize(const float* h_w, size_t n, uint8_t* h_out);
 
 /* Tuning aid for benchmarks: force one bf16 GEMM tile configuration for all later launches in this
  * process (0 = choose by shape, the default; 1..26 except 13 = a fixed tile configuration, 13 = the few-row kernel, 27..29 = the persistent

@@ -8,7 +8,8 @@ Weight recipe: every matrix and embedding table ~ N(0, std 0.02); biases 0, Laye
 beta 0.  `stress=True` instead draws biases and beta ~ N(0, 0.02) and gamma ~ 1 + N(0, 0.02) so that
 bias/gamma/beta code paths carry signal.  `bf16_grid=True` snaps matrices and embedding tables to
 values representable in bfloat16 (round to nearest even), so a consumer that stores them as
-bfloat16 and one that keeps float32 see identical numbers.
+bfloat16 and one that keeps float32 see identical numbers.  A spec of precision "fp8" additionally snaps the
+two feed-forward matrices of every layer to the FP8 E4M3 grid under their power-of-two storage scale.
 
 Input recipe: sequence lengths uniform on the inclusive range [len_lo, len_hi]; the attention mask
 is a prefix of ones; token ids are uniform in [0, vocab) at every position, padded ones included.
@@ -77,7 +78,56 @@ def round_to_bf16_grid(x: np.ndarray) -> np.ndarray:
     return x
 
 
-def _fill(flat: np.ndarray, tensors, seed: int, scope_id: int, std: float, stress: bool, bf16_grid: bool):
+def e4m3_scale(x: np.ndarray) -> float:
+    """Storage scale of an FP8 (OCP E4M3, largest finite value 448) matrix: the largest power of two s with
+    s * max|x| <= 448; 1 for an all-zero matrix."""
+    mx = float(np.abs(x).max()) if x.size else 0.0
+    if not (mx > 0.0) or not np.isfinite(mx):
+        return 1.0
+    s = 2.0 ** np.floor(np.log2(448.0 / mx))
+    while s * mx > 448.0:
+        s *= 0.5
+    while 2.0 * s * mx <= 448.0:
+        s *= 2.0
+    return float(s)
+
+
+def _snap_e4m3(x: np.ndarray, s: float) -> np.ndarray:
+    """The values an OCP FP8 E4M3 store of s * x holds, divided by s again (a new array)."""
+    s = np.float32(s)
+    y = (x * s).astype(np.float32)
+    a = np.abs(y)
+    small = a < np.float32(2.0 ** -6)
+    u = a.view(np.uint32).copy()
+    u += np.uint32(0x7FFFF) + ((u >> np.uint32(20)) & np.uint32(1))
+    u &= np.uint32(0xFFF00000)
+    big = np.minimum(u.view(np.float32), np.float32(448.0))
+    sub = (np.rint(a.astype(np.float64) * 512.0) / 512.0).astype(np.float32)
+    q = np.where(small, sub, big).astype(np.float32)
+    return (np.copysign(q, y) / s).astype(np.float32)
+
+
+def round_to_e4m3_grid(x: np.ndarray, scale: float | None = None) -> np.ndarray:
+    """Snap float32 values, in place, to the values an OCP FP8 E4M3 store of scale * x holds (3 mantissa bits, round to
+    nearest even; multiples of 2^-9 below 2^-6; saturating at 448), divided by the scale again.
+    scale None: the storage scale e4m3_scale, chosen so that the RESULT has that same storage scale (a largest entry that
+    rounds down onto 224 / scale would otherwise admit twice the scale: then the snap is redone with the doubled one)."""
+    if scale is not None:
+        x[...] = _snap_e4m3(x, scale)
+        return x
+    s = e4m3_scale(x)
+    for _ in range(4):
+        y = _snap_e4m3(x, s)
+        s2 = e4m3_scale(y)
+        if s2 == s:
+            break
+        s = s2
+    assert e4m3_scale(y) == s
+    x[...] = y
+    return x
+
+
+def _fill(flat: np.ndarray, tensors, seed: int, scope_id: int, std: float, stress: bool, bf16_grid: bool, fp8_ffn: bool = False):
     off = 0
     index = []
     for ti, (name, shape) in enumerate(tensors):
@@ -88,7 +138,9 @@ def _fill(flat: np.ndarray, tensors, seed: int, scope_id: int, std: float, stres
         if len(shape) == 2:                       # matrices and embedding tables
             normal(key, n, out=view)
             view *= np.float32(std)
-            if bf16_grid:
+            if fp8_ffn and base in ("W1", "W2"):
+                round_to_e4m3_grid(view)          # E4M3 values (times a power of two) are bfloat16 values too
+            elif bf16_grid:
                 round_to_bf16_grid(view)
         elif base.endswith("_g"):                 # LayerNorm gamma
             view[:] = 1.0
@@ -111,20 +163,20 @@ def _count(tensors) -> int:
 def make_trunk_params(spec: MTSpec, *, stress: bool = False, bf16_grid: bool | None = None,
                       seed: int | None = None, std: float = 0.02):
     """Flat float32 parameter vector of the trunk scope (canonical order) and its (name, shape, offset) index."""
-    bf16_grid = (spec.precision == "bf16") if bf16_grid is None else bf16_grid
+    bf16_grid = (spec.precision in ("bf16", "fp8")) if bf16_grid is None else bf16_grid
     tensors = trunk_tensors(spec)
     flat = np.empty(_count(tensors), dtype=np.float32)
-    index = _fill(flat, tensors, spec.weights_seed if seed is None else seed, 0, std, stress, bf16_grid)
+    index = _fill(flat, tensors, spec.weights_seed if seed is None else seed, 0, std, stress, bf16_grid, spec.precision == "fp8")
     return flat, index
 
 
 def make_task_params(spec: MTSpec, t: int, *, stress: bool = False, bf16_grid: bool | None = None,
                      seed: int | None = None, std: float = 0.02):
     """Flat float32 parameter vector of task t's scope (canonical order) and its index."""
-    bf16_grid = (spec.precision == "bf16") if bf16_grid is None else bf16_grid
+    bf16_grid = (spec.precision in ("bf16", "fp8")) if bf16_grid is None else bf16_grid
     tensors = task_tensors(spec, t)
     flat = np.empty(_count(tensors), dtype=np.float32)
-    index = _fill(flat, tensors, spec.weights_seed if seed is None else seed, 1 + t, std, stress, bf16_grid)
+    index = _fill(flat, tensors, spec.weights_seed if seed is None else seed, 1 + t, std, stress, bf16_grid, spec.precision == "fp8")
     return flat, index
 
 

@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmt_hip.so")
 
 MT_OK, MT_ERR_NULL, MT_ERR_CONFIG, MT_ERR_SHAPE, MT_ERR_STATE, MT_ERR_BLOB, MT_ERR_HIP = 0, -1, -2, -3, -4, -5, -6
-MT_BF16, MT_FP32_CHECK = 0, 1
+MT_BF16, MT_FP32_CHECK, MT_FP8_FFN = 0, 1, 2
 MT_GELU_ERF, MT_GELU_TANH = 0, 1
 MT_ABI_VERSION = 2
 MT_HEAD_SEQUENCE, MT_HEAD_TOKEN = 0, 1
@@ -27,7 +27,7 @@ EXPORTS = ["mt_create", "mt_destroy", "mt_weight_bytes", "mt_workspace_bytes", "
            "mt_forward", "mt_logit_offset", "mt_n_logits", "mt_layer_count", "mt_last_error", "mt_error_name",
            "mt_read_hidden", "mt_profile_enable", "mt_profile_read", "mt_op_linear", "mt_op_attention",
            "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed", "mt_op_linear_sub", "mt_op_first_token_pool", "mt_schedule_steps", "mt_forward_routed",
-           "mt_forward_tokens", "mt_token_logit_offset", "mt_n_token_logits", "mt_forward_static", "mt_forward_multi", "mt_forward_routed_tokens"]
+           "mt_forward_tokens", "mt_token_logit_offset", "mt_n_token_logits", "mt_forward_static", "mt_forward_multi", "mt_forward_routed_tokens", "mt_op_linear_fp8", "mt_debug_e4m3_quantize"]
 MT_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 
 
@@ -71,6 +71,9 @@ def lib():
         L.mt_forward_routed.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_tokens.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
         L.mt_forward_routed_tokens.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+        L.mt_op_linear_fp8.argtypes = [vp, i64, vp, C.c_float, vp, vp, vp, i64, i32, i32, i32, i32, i32, C.c_float, vp]
+        L.mt_debug_e4m3_quantize.argtypes = [vp, sz, vp]
+        L.mt_debug_e4m3_quantize.restype = C.c_float
         L.mt_logit_offset.argtypes = [vp, i32]
         L.mt_token_logit_offset.argtypes = [vp, i32]
         L.mt_n_token_logits.argtypes = [vp]
@@ -110,7 +113,7 @@ def make_config(spec, *, max_batch=None, max_seq=None, precision=None):
     tasks = (mt_task_desc * len(spec.tasks))(*[mt_task_desc(t.fork_layer, t.n_layers, t.n_classes,
                                                             MT_HEAD_TOKEN if getattr(t, "token_level", False) else MT_HEAD_SEQUENCE)
                                                for t in spec.tasks])
-    prec = precision if precision is not None else (MT_BF16 if spec.precision == "bf16" else MT_FP32_CHECK)
+    prec = precision if precision is not None else {"bf16": MT_BF16, "fp8": MT_FP8_FFN}.get(spec.precision, MT_FP32_CHECK)
     cfg = mt_config(C.sizeof(mt_config), MT_ABI_VERSION, spec.vocab, spec.hidden, spec.heads, spec.ffn, spec.max_pos,
                     spec.type_vocab, spec.n_trunk_layers, len(spec.tasks), tasks, prec,
                     MT_GELU_TANH if spec.gelu == "tanh" else MT_GELU_ERF, spec.ln_eps,
@@ -361,6 +364,28 @@ def op_linear_batched(precision, A, W, bias=None, residual=None, act=0, out_f32=
                                     _ptr(residual), m * n, _ptr(out), m * n, n, m, n, k, act, 1 if out_f32 else 0, _stream())
     if rc != MT_OK:
         raise MTError(rc, "mt_op_linear_batched")
+    return out
+
+
+def e4m3_quantize(w):
+    """(scale, uint8 codes) of a float32 array under the loader's FP8 storage rule (mt_debug_e4m3_quantize, host only)."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    out = np.empty(w.size, dtype=np.uint8)
+    s = lib().mt_debug_e4m3_quantize(w.ctypes.data_as(C.c_void_p), w.size, out.ctypes.data_as(C.c_void_p))
+    return float(s), out.reshape(w.shape)
+
+
+def op_linear_fp8(A, W, scale, bias=None, residual=None, act=0, out_kind=1, out_scale=1.0):
+    """mt_op_linear_fp8 on device tensors: A [M,K], W [N,K] uint8 (E4M3 codes); returns C [M,N] (bf16 / float32 / uint8)."""
+    import torch
+    m, k = A.shape
+    n = W.shape[0]
+    dt = {0: torch.bfloat16, 1: torch.float32, 2: torch.uint8}[out_kind]
+    out = torch.empty((m, n), dtype=dt, device=A.device)
+    rc = lib().mt_op_linear_fp8(_ptr(A), k, _ptr(W), scale, _ptr(bias), _ptr(residual), _ptr(out), n, m, n, k, act, out_kind,
+                                out_scale, _stream())
+    if rc != MT_OK:
+        raise MTError(rc, "mt_op_linear_fp8")
     return out
 
 

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmt_hip.so")
-SOURCES = ["mt_model.cpp", "gemm_bf16.hip", "gemm_bf16_persist.hip", "gemm_skinny.hip", "gemm_f32.hip", "attention.hip", "rowops.hip", "microbench.hip"]
+SOURCES = ["mt_model.cpp", "gemm_bf16.hip", "gemm_bf16_persist.hip", "gemm_fp8.hip", "gemm_skinny.hip", "gemm_f32.hip", "attention.hip", "rowops.hip", "microbench.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",
          # packed-FP32 instruction selection is switched off for every device function

@@ -73,6 +73,18 @@ __device__ inline float gelu_tanh(float x)
     return 0.5f * x * (1.0f + tanhf(u));
 }
 
+// four float32 -> four OCP FP8 E4M3 bytes in one dword (round to nearest even, saturating at +-448)
+__device__ __forceinline__ uint32_t pack_e4m3(float a, float b, float c, float d)
+{
+    a = __builtin_amdgcn_fmed3f(a, -448.f, 448.f);
+    b = __builtin_amdgcn_fmed3f(b, -448.f, 448.f);
+    c = __builtin_amdgcn_fmed3f(c, -448.f, 448.f);
+    d = __builtin_amdgcn_fmed3f(d, -448.f, 448.f);
+    int v = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
+    v = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, v, true);
+    return (uint32_t)v;
+}
+
 __device__ inline float apply_act(float v, int act)
 {
     switch (act) {

@@ -23,13 +23,14 @@ struct GemmGroup {
     const float* bias[kMaxGroup];       // may be null
     const float* residual[kMaxGroup];   // fp32 [M][ldr], may be null
     int32_t N[kMaxGroup];               // per-problem N (fp32 path only; the MFMA path needs uniform N)
+    float scale[kMaxGroup];             // FP8 path only: the accumulator is multiplied by this before the bias is added
 };
 
 struct GemmShape {
     int32_t G, M, N, K;     // N = max over the group; M = row bound (grid size), see d_M
     int64_t lda, ldc, ldr;  // row strides in elements
     int32_t act;            // ActKind
-    int32_t out_f32;        // 1: C is float32, 0: C has the activation element type
+    int32_t out_f32;        // 1: C is float32, 0: C has the activation element type (bf16); FP8 path also 2: C is E4M3 bytes
     const int32_t* d_M;     // optional device scalar: rows actually present (<= M); tiles beyond it exit at once
     int32_t splits;         // bf16 path, >= 1: K is cut into `splits` equal ranges, range p of problem g writing its
                             // partial product (float32, no epilogue) to C_g + p * split_stride elements
@@ -44,10 +45,15 @@ struct GemmShape {
     int64_t sub_a, sub_w, sub_c, sub_bias;
     const int32_t* d_sub_row0;
     const int32_t* d_sub_rows;
+    float out_scale;        // FP8 path, out_f32 == 2: the value is multiplied by this before it is rounded to E4M3
 };
 
 // bf16 x bf16 -> fp32 accumulate on the matrix cores.  Needs K % 64 == 0, lda % 8 == 0, 16-byte aligned A/W rows.
 hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t stream);
+// FP8 (OCP E4M3) x FP8 -> float32 accumulate, both operands one byte per element, K contiguous (lda / ldw in elements =
+// bytes, multiples of 16); needs K % 64 == 0 and K >= 192.  C_g = epi(g.scale[g] * A_g W_g^T + bias): out_f32 0 / 1 / 2
+// = bf16 / float32 (+ residual) / E4M3 (times out_scale).  Activations: none, GELU(erf), GELU(tanh).
+hipError_t launch_gemm_fp8(const GemmGroup& g, const GemmShape& s, hipStream_t stream);
 // Persistent variant for launches of many 256x256 tiles (one workgroup per compute unit walks a tile list with
 // its load ring never draining); launch_gemm_bf16 routes to it by itself.  gemm_bf16_persist_takes: shape supported.
 bool gemm_bf16_persist_takes(const GemmShape& s);
@@ -100,8 +106,9 @@ struct LnGroup {
     bf16_t* out_bf16[kMaxGroup];    // may be null
 };
 // d_M (optional device scalar) = rows actually present (<= M); n_parts partial sums part_stride elements apart
+// low_fmt: element type written through out_bf16: 0 bfloat16, 1 OCP FP8 E4M3 (one byte per element, saturating)
 hipError_t launch_layernorm(const LnGroup& g, int G, int M, const int32_t* d_M, int H, float eps, int n_parts, int64_t part_stride,
-                            hipStream_t stream);
+                            hipStream_t stream, int low_fmt = 0);
 
 // X0[r] = LN(word[ids[p]] + pos[p % S] + type[0]) with p = src[r] for the kept rows r < *d_M (p = r and all
 // B*S rows when src is null); tables are bf16 (emb_bf16 != 0) or fp32.

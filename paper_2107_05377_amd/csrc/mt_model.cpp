@@ -18,6 +18,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -65,6 +66,10 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct LayerW {   // byte offsets into the weight arena
     size_t Wqkv, bqkv, Wo, bo, ln1g, ln1b, W1, b1, W2, b2, ln2g, ln2b;
     size_t WkT = 0;   // bf16 mode, a task's last layer only: Wk transposed, [H][H] (first-token attention), else 0
+    // FP8 variant: E4M3 copies of the two feed-forward matrices, stored as W * s with s the largest power of two that
+    // keeps s * max|W| <= 448; inv_s (set when the checkpoint is loaded) undoes it in the contraction's epilogue
+    size_t W1q = 0, W2q = 0;
+    float inv_s1 = 1.f, inv_s2 = 1.f;
 };
 struct TaskW {
     std::vector<LayerW> layers;
@@ -95,6 +100,7 @@ struct mt_model {
     mt_config cfg;
     std::vector<mt_task_desc> tasks;
     bool bf16 = true;
+    bool fp8 = false;   // MT_FP8_FFN: bf16 everywhere, the two feed-forward contractions of every all-rows layer in E4M3
     size_t esz = 2;   // bytes per matrix / activation element
     int C_tot = 0, C_tok = 0;            // widths of the per-sequence and of the per-token logit row
     std::vector<int> logit_off;          // task -> first column inside the row of its kind
@@ -167,7 +173,7 @@ struct Bump {
     }
 };
 
-LayerW layout_layer(Bump& b, size_t H, size_t F, size_t esz)
+LayerW layout_layer(Bump& b, size_t H, size_t F, size_t esz, bool fp8 = false)
 {
     LayerW L;
     L.Wqkv = b.take(3 * H * H * esz);
@@ -182,6 +188,10 @@ LayerW layout_layer(Bump& b, size_t H, size_t F, size_t esz)
     L.b2 = b.take(H * 4);
     L.ln2g = b.take(H * 4);
     L.ln2b = b.take(H * 4);
+    if (fp8) {
+        L.W1q = b.take(F * H);
+        L.W2q = b.take(H * F);
+    }
     return L;
 }
 
@@ -205,6 +215,46 @@ inline uint16_t f32_to_bf16_rne(float f)
     if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
+}
+
+// float32 -> OCP FP8 E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; largest finite value 448, no
+// infinities, 0x7F = NaN), round to nearest even, saturating: what a conversion instruction with clamping gives.
+inline uint8_t f32_to_e4m3_rne(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    const uint8_t sign = (uint8_t)((u >> 24) & 0x80u);
+    const uint32_t a = u & 0x7FFFFFFFu;
+    if (a > 0x7F800000u) return (uint8_t)(sign | 0x7Fu);                       // NaN
+    float af;
+    memcpy(&af, &a, 4);
+    if (af >= 448.0f) return (uint8_t)(sign | 0x7Eu);                          // saturate (also +-inf)
+    if (af < 0.015625f) {                                                      // below 2^-6: multiples of 2^-9
+        const float q = nearbyintf(af * 512.0f);                               // default rounding mode: to nearest even
+        return (uint8_t)(sign | (uint8_t)q);                                   // q == 8 is the smallest normal, 0x08
+    }
+    uint32_t r = a + 0x7FFFFu + ((a >> 20) & 1u);                              // keep 3 mantissa bits
+    const int e = (int)(r >> 23) - 127 + 7;                                    // 1 .. 15 here
+    const uint32_t mant = (r >> 20) & 7u;
+    const uint32_t code = ((uint32_t)e << 3) | mant;
+    return (uint8_t)(sign | (code > 0x7Eu ? 0x7Eu : code));
+}
+
+// The storage scale of an FP8 weight matrix: the largest power of two s with s * max|W| <= 448 (1 for a zero matrix).
+inline float e4m3_scale_for(const float* w, size_t n)
+{
+    float mx = 0.f;
+    for (size_t i = 0; i < n; ++i) {
+        const float a = fabsf(w[i]);
+        if (a > mx) mx = a;                        // NaNs never compare greater
+    }
+    if (!(mx > 0.f) || !std::isfinite(mx)) return 1.f;
+    int e = (int)floorf(log2f(448.0f / mx));
+    e = std::max(-100, std::min(100, e));
+    float s = ldexpf(1.0f, e);
+    while (s * mx > 448.0f) s *= 0.5f;             // log2f rounding at exact powers of two
+    while (s * 2.0f * mx <= 448.0f) s *= 2.0f;
+    return s;
 }
 
 // Copy n float32 values into the staging image as matrix elements (bf16 or fp32).
@@ -231,7 +281,7 @@ void put_matrix(unsigned char* dst, const float* src, size_t n, bool bf16)
 }
 
 // Convert one encoder layer from the blob order into the arena image; returns floats consumed.
-size_t stage_layer(const mt_model* m, const LayerW& L, const float* p, unsigned char* img, size_t img_base)
+size_t stage_layer(const mt_model* m, LayerW& L, const float* p, unsigned char* img, size_t img_base)
 {
     const size_t H = m->cfg.hidden, F = m->cfg.ffn;
     const float* p0 = p;
@@ -254,9 +304,19 @@ size_t stage_layer(const mt_model* m, const LayerW& L, const float* p, unsigned 
     memcpy(at(L.bo), p, H * 4); p += H;
     memcpy(at(L.ln1g), p, H * 4); p += H;
     memcpy(at(L.ln1b), p, H * 4); p += H;
-    put_matrix(at(L.W1), p, F * H, m->bf16); p += F * H;
+    auto put_e4m3 = [&](size_t off, const float* w, size_t n) {
+        const float sc = e4m3_scale_for(w, n);
+        uint8_t* q = at(off);
+        for (size_t i = 0; i < n; ++i) q[i] = f32_to_e4m3_rne(w[i] * sc);
+        return 1.0f / sc;
+    };
+    put_matrix(at(L.W1), p, F * H, m->bf16);
+    if (L.W1q) L.inv_s1 = put_e4m3(L.W1q, p, F * H);
+    p += F * H;
     memcpy(at(L.b1), p, F * 4); p += F;
-    put_matrix(at(L.W2), p, H * F, m->bf16); p += H * F;
+    put_matrix(at(L.W2), p, H * F, m->bf16);
+    if (L.W2q) L.inv_s2 = put_e4m3(L.W2q, p, H * F);
+    p += H * F;
     memcpy(at(L.b2), p, H * 4); p += H;
     memcpy(at(L.ln2g), p, H * 4); p += H;
     memcpy(at(L.ln2b), p, H * 4); p += H;
@@ -373,8 +433,10 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& 
     const bool fuse_res = bf && MT_RESID_IN_GEMM;
     // A contraction with few output tiles (one problem, narrow output) is cut along K into equal
     // ranges whose float32 partial products the following LayerNorm adds up in a fixed order.
+    const bool f8 = m->fp8;
     auto pick_splits = [&](int K, int N, int max_splits, int max_splits_few) {
         if (!bf || n != 1 || io[0].scr->y_parts < 2) return 1;
+        if (f8 && K == F) return 1;                                  // the FP8 contraction has no K split
         const long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
         if (tiles128 >= 256) return 1;
         // a launch of at most MT_FEW_TILES 64x128 tiles leaves most CUs idle: there the K ranges pay
@@ -410,33 +472,50 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& 
         lg.out_bf16[i] = bf ? (bf16_t*)(ws + io[i].scr->x1b) : nullptr;
     }
     L.begin(MT_K_LN);
-    L.check(launch_layernorm(lg, n, M, rm.n_rows, H, m->cfg.ln_eps, sp_o, (int64_t)m->Mmax * H, L.st));
+    // (FP8 variant: the operand copy of x1 is E4M3 instead of bf16, in the same buffer)
+    L.check(launch_layernorm(lg, n, M, rm.n_rows, H, m->cfg.ln_eps, sp_o, (int64_t)m->Mmax * H, L.st, f8 ? 1 : 0));
     L.end();
 
     // FFN1 + bias + GELU -> u
     for (int i = 0; i < n; ++i) {
         g.A[i] = bf ? (const void*)(ws + io[i].scr->x1b) : (const void*)(ws + io[i].scr->x1f);
-        g.W[i] = W + io[i].w->W1;
+        g.W[i] = W + (f8 ? io[i].w->W1q : io[i].w->W1);
         g.bias[i] = (const float*)(W + io[i].w->b1);
         g.residual[i] = nullptr;
         g.C[i] = ws + io[i].scr->u;
         g.N[i] = F;
+        g.scale[i] = io[i].w->inv_s1;
     }
     s = GemmShape{n, M, F, H, H, F, 0, gelu_act, bf ? 0 : 1, rm.n_rows, 1, 0};
-    L.gemm(MT_K_GEMM_FFN1, g, s, false);
+    if (f8) {                                                        // E4M3 in, E4M3 out (FFN2's operand), unit activation scale
+        s.out_f32 = 2;
+        s.out_scale = 1.0f;
+        L.begin(MT_K_GEMM_FFN1);
+        L.check(launch_gemm_fp8(g, s, L.st));
+        L.end();
+    } else {
+        L.gemm(MT_K_GEMM_FFN1, g, s, false);
+    }
 
     // FFN2 -> y (fp32 partial products), then LayerNorm(y + bias + residual) -> layer output
     const int sp_f = pick_splits(F, H, MT_MAX_SPLITS_FFN2, MT_FEW_SPLITS_FFN2);
     for (int i = 0; i < n; ++i) {
         g.A[i] = ws + io[i].scr->u;
-        g.W[i] = W + io[i].w->W2;
+        g.W[i] = W + (f8 ? io[i].w->W2q : io[i].w->W2);
         g.bias[i] = (fuse_res && sp_f == 1) ? (const float*)(W + io[i].w->b2) : nullptr;
         g.residual[i] = (fuse_res && sp_f == 1) ? (const float*)(ws + io[i].scr->x1f) : nullptr;
         g.C[i] = ws + io[i].scr->y;
         g.N[i] = H;
+        g.scale[i] = io[i].w->inv_s2;
     }
     s = GemmShape{n, M, H, F, F, H, H, ACT_NONE, 1, rm.n_rows, sp_f, (int64_t)m->Mmax * H};
-    L.gemm(MT_K_GEMM_FFN2, g, s, false);
+    if (f8) {
+        L.begin(MT_K_GEMM_FFN2);
+        L.check(launch_gemm_fp8(g, s, L.st));
+        L.end();
+    } else {
+        L.gemm(MT_K_GEMM_FFN2, g, s, false);
+    }
 
     for (int i = 0; i < n; ++i) {
         lg.x[i] = (const float*)(ws + io[i].scr->y);
@@ -687,10 +766,12 @@ int mt_create(const mt_config* cfg, mt_model** out)
         cfg->n_trunk_layers < 0 || cfg->max_batch < 1 || cfg->max_seq < 1)
         return MT_ERR_CONFIG;
     if (cfg->hidden % cfg->heads != 0 || cfg->max_seq > cfg->max_pos) return MT_ERR_CONFIG;
-    if (cfg->precision != MT_BF16 && cfg->precision != MT_FP32_CHECK) return MT_ERR_CONFIG;
+    if (cfg->precision != MT_BF16 && cfg->precision != MT_FP32_CHECK && cfg->precision != MT_FP8_FFN) return MT_ERR_CONFIG;
     if (cfg->gelu != MT_GELU_ERF && cfg->gelu != MT_GELU_TANH) return MT_ERR_CONFIG;
     if (!(cfg->ln_eps >= 0.0f)) return MT_ERR_CONFIG;
-    if (cfg->precision == MT_BF16 &&
+    // (the FP8 contraction walks K in slices of 64 through a 3-stage ring: K >= 192 for both feed-forward matrices)
+    if (cfg->precision == MT_FP8_FFN && (cfg->hidden < 192 || cfg->ffn < 192)) return MT_ERR_CONFIG;
+    if (cfg->precision != MT_FP32_CHECK &&
         (cfg->hidden != cfg->heads * 64 || cfg->hidden % 64 != 0 || cfg->ffn % 64 != 0 || cfg->max_seq > kAttnBf16MaxSeq))
         return MT_ERR_CONFIG;
     if (cfg->precision == MT_FP32_CHECK && cfg->max_seq > 4096) return MT_ERR_CONFIG;
@@ -708,7 +789,8 @@ int mt_create(const mt_config* cfg, mt_model** out)
     m->cfg = *cfg;
     m->tasks.assign(cfg->tasks, cfg->tasks + cfg->n_tasks);
     m->cfg.tasks = m->tasks.data();
-    m->bf16 = cfg->precision == MT_BF16;
+    m->bf16 = cfg->precision != MT_FP32_CHECK;
+    m->fp8 = cfg->precision == MT_FP8_FFN;
     m->esz = m->bf16 ? 2 : 4;
     const size_t H = cfg->hidden, F = cfg->ffn, T = cfg->n_tasks, D = cfg->n_trunk_layers;
     for (const auto& d : m->tasks) {
@@ -724,13 +806,13 @@ int mt_create(const mt_config* cfg, mt_model** out)
     m->w_type = wb.take((size_t)cfg->type_vocab * H * m->esz);
     m->w_embg = wb.take(H * 4);
     m->w_embb = wb.take(H * 4);
-    for (size_t l = 0; l < D; ++l) m->trunk.push_back(layout_layer(wb, H, F, m->esz));
+    for (size_t l = 0; l < D; ++l) m->trunk.push_back(layout_layer(wb, H, F, m->esz, m->fp8));
     m->w_trunk_end = wb.off;
     m->taskw.resize(T);
     for (size_t t = 0; t < T; ++t) {
         TaskW& tw = m->taskw[t];
         tw.begin = wb.off;
-        for (int l = 0; l < m->tasks[t].n_layers; ++l) tw.layers.push_back(layout_layer(wb, H, F, m->esz));
+        for (int l = 0; l < m->tasks[t].n_layers; ++l) tw.layers.push_back(layout_layer(wb, H, F, m->esz, m->fp8));
         const bool seq_head = m->tasks[t].head == MT_HEAD_SEQUENCE;
         if (m->bf16 && seq_head && !tw.layers.empty()) tw.layers.back().WkT = wb.take(H * H * 2);
         tw.Wp = seq_head ? wb.take(H * H * m->esz * (m->bf16 ? 2 : 1)) : 0;
@@ -907,6 +989,15 @@ int mt_share_weights(mt_model* m, const mt_model* owner)
     if (!any) return fail(m, MT_ERR_STATE, "mt_share_weights: owner has no weights loaded");
     m->trunk_loaded = owner->trunk_loaded;
     m->task_loaded = owner->task_loaded;
+    for (size_t l = 0; l < m->trunk.size(); ++l) {                 // the storage scales live beside the layout
+        m->trunk[l].inv_s1 = owner->trunk[l].inv_s1;
+        m->trunk[l].inv_s2 = owner->trunk[l].inv_s2;
+    }
+    for (size_t t = 0; t < m->taskw.size(); ++t)
+        for (size_t l = 0; l < m->taskw[t].layers.size(); ++l) {
+            m->taskw[t].layers[l].inv_s1 = owner->taskw[t].layers[l].inv_s1;
+            m->taskw[t].layers[l].inv_s2 = owner->taskw[t].layers[l].inv_s2;
+        }
     return MT_OK;
 }
 
@@ -964,11 +1055,11 @@ int mt_load_weights(mt_model* m, int32_t scope, const void* h_blob, size_t nbyte
         put_matrix(at(m->w_type), p, (size_t)m->cfg.type_vocab * H, m->bf16); p += (size_t)m->cfg.type_vocab * H;
         memcpy(at(m->w_embg), p, H * 4); p += H;
         memcpy(at(m->w_embb), p, H * 4); p += H;
-        for (const LayerW& L : m->trunk) p += stage_layer(m, L, p, img, begin);
+        for (LayerW& L : m->trunk) p += stage_layer(m, L, p, img, begin);
     } else {
-        const TaskW& tw = m->taskw[scope];
+        TaskW& tw = m->taskw[scope];
         const size_t C = m->tasks[scope].n_classes;
-        for (const LayerW& L : tw.layers) p += stage_layer(m, L, p, img, begin);
+        for (LayerW& L : tw.layers) p += stage_layer(m, L, p, img, begin);
         const bool seq_head = m->tasks[scope].head == MT_HEAD_SEQUENCE;
         if (!seq_head) {
             // a token-level scope carries no pooler
@@ -1579,6 +1670,37 @@ int mt_op_linear(int32_t precision, const void* d_A, int64_t lda, const void* d_
                                         : launch_gemm_f32(g, s, 0, static_cast<hipStream_t>(hip_stream));
     if (e == hipErrorInvalidValue) return MT_ERR_SHAPE;
     return e == hipSuccess ? MT_OK : MT_ERR_HIP;
+}
+
+int mt_op_linear_fp8(const void* d_A, int64_t lda, const void* d_W, float scale, const float* d_bias, const float* d_residual,
+                     void* d_C, int64_t ldc, int32_t M, int32_t N, int32_t K, int32_t act_kind, int32_t out_kind, float out_scale,
+                     void* hip_stream)
+{
+    if (!d_A || !d_W || !d_C) return MT_ERR_NULL;
+    if (M < 1 || N < 1 || K < 1 || act_kind < 0 || act_kind > 2 || out_kind < 0 || out_kind > 2) return MT_ERR_SHAPE;
+    GemmGroup g;
+    memset(&g, 0, sizeof g);
+    g.A[0] = d_A;
+    g.W[0] = d_W;
+    g.C[0] = d_C;
+    g.bias[0] = d_bias;
+    g.residual[0] = d_residual;
+    g.N[0] = N;
+    g.scale[0] = scale;
+    GemmShape s{1, M, N, K, lda, ldc, ldc, act_kind, out_kind, nullptr, 1, 0};
+    s.out_scale = out_scale;
+    hipError_t e = launch_gemm_fp8(g, s, static_cast<hipStream_t>(hip_stream));
+    if (e == hipErrorInvalidValue) return MT_ERR_SHAPE;
+    return e == hipSuccess ? MT_OK : MT_ERR_HIP;
+}
+
+float mt_debug_e4m3_quantize(const float* h_w, size_t n, uint8_t* h_out)
+{
+    if (!h_w) return 0.f;
+    const float sc = e4m3_scale_for(h_w, n);
+    if (h_out)
+        for (size_t i = 0; i < n; ++i) h_out[i] = f32_to_e4m3_rne(h_w[i] * sc);
+    return sc;
 }
 
 int mt_op_linear_sub(const void* d_A, int64_t lda, const void* d_W, int64_t ldw, const float* d_bias, void* d_C, int64_t ldc,

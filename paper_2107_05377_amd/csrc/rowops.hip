@@ -28,7 +28,7 @@ __device__ inline float4 load4<__bf16>(const __bf16* p)
 // Normalise NV float4 per lane held in registers and store.
 template <int NV>
 __device__ inline void ln_finish_store(float4 (&v)[NV], int lane, int H, const float* gamma, const float* beta,
-                                       float eps, float* out_f32, __bf16* out_bf16)
+                                       float eps, float* out_f32, __bf16* out_bf16, int low_fmt = 0)
 {
     float s = 0.f;
 #pragma unroll
@@ -52,7 +52,9 @@ __device__ inline void ln_finish_store(float4 (&v)[NV], int lane, int H, const f
         o.z = g.z * ((v[i].z - mean) * inv) + b.z;
         o.w = g.w * ((v[i].w - mean) * inv) + b.w;
         if (out_f32) *reinterpret_cast<float4*>(out_f32 + col) = o;
-        if (out_bf16) {
+        if (out_bf16 && low_fmt == 1) {                   // E4M3, one byte per element
+            *reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(out_bf16) + col) = pack_e4m3(o.x, o.y, o.z, o.w);
+        } else if (out_bf16) {
             bf16x4 p = {(__bf16)o.x, (__bf16)o.y, (__bf16)o.z, (__bf16)o.w};
             *reinterpret_cast<bf16x4*>(out_bf16 + col) = p;
         }
@@ -62,7 +64,7 @@ __device__ inline void ln_finish_store(float4 (&v)[NV], int lane, int H, const f
 // H == NV*256: the whole row lives in registers.
 template <int NV>
 __global__ __launch_bounds__(256) void layernorm_fast(LnGroup g, int M, const int32_t* __restrict__ d_M, int H, float eps,
-                                                      int n_parts, int64_t part_stride)
+                                                      int n_parts, int64_t part_stride, int low_fmt)
 {
     const int grp = blockIdx.y;
     const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
@@ -91,13 +93,15 @@ __global__ __launch_bounds__(256) void layernorm_fast(LnGroup g, int M, const in
         }
     }
     float* of = g.out_f32[grp] ? g.out_f32[grp] + (size_t)row * H : nullptr;
-    __bf16* ob = g.out_bf16[grp] ? reinterpret_cast<__bf16*>(g.out_bf16[grp]) + (size_t)row * H : nullptr;
-    ln_finish_store<NV>(v, lane, H, g.gamma[grp], g.beta[grp], eps, of, ob);
+    // the low-precision copy's row is H elements of 2 bytes (bf16) or 1 byte (E4M3)
+    __bf16* ob = g.out_bf16[grp] ? reinterpret_cast<__bf16*>(reinterpret_cast<unsigned char*>(g.out_bf16[grp]) + (size_t)row * H * (low_fmt == 1 ? 1 : 2))
+                                 : nullptr;
+    ln_finish_store<NV>(v, lane, H, g.gamma[grp], g.beta[grp], eps, of, ob, low_fmt);
 }
 
 // Any H: three strided passes over the row (it stays in cache between passes).
 __global__ __launch_bounds__(256) void layernorm_any(LnGroup g, int M, const int32_t* __restrict__ d_M, int H, float eps,
-                                                     int n_parts, int64_t part_stride)
+                                                     int n_parts, int64_t part_stride, int low_fmt)
 {
     const int grp = blockIdx.y;
     const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
@@ -124,10 +128,12 @@ __global__ __launch_bounds__(256) void layernorm_any(LnGroup g, int M, const int
     const float* beta = g.beta[grp];
     float* of = g.out_f32[grp] ? g.out_f32[grp] + (size_t)row * H : nullptr;
     __bf16* ob = g.out_bf16[grp] ? reinterpret_cast<__bf16*>(g.out_bf16[grp]) + (size_t)row * H : nullptr;
+    unsigned char* o8 = g.out_bf16[grp] ? reinterpret_cast<unsigned char*>(g.out_bf16[grp]) + (size_t)row * H : nullptr;
     for (int i = lane; i < H; i += 64) {
         float o = gamma[i] * ((value(i) - mean) * inv) + beta[i];
         if (of) of[i] = o;
-        if (ob) ob[i] = (__bf16)o;
+        if (ob && low_fmt == 1) o8[i] = (unsigned char)(pack_e4m3(o, 0.f, 0.f, 0.f) & 0xFFu);
+        else if (ob) ob[i] = (__bf16)o;
     }
 }
 
@@ -700,15 +706,16 @@ hipError_t launch_route_gather(const float* in_f, const void* in_a, float* out_f
 }
 
 hipError_t launch_layernorm(const LnGroup& g, int G, int M, const int32_t* d_M, int H, float eps, int n_parts, int64_t part_stride,
-                            hipStream_t stream)
+                            hipStream_t stream, int low_fmt)
 {
     if (G <= 0 || M <= 0) return hipSuccess;
+    if (low_fmt != 0 && low_fmt != 1) return hipErrorInvalidValue;
     dim3 grid((M + kRowsPerBlock - 1) / kRowsPerBlock, G), block(256);
-    if (H == 768) hipLaunchKernelGGL((layernorm_fast<3>), grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride);
-    else if (H == 1024) hipLaunchKernelGGL((layernorm_fast<4>), grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride);
-    else if (H == 512) hipLaunchKernelGGL((layernorm_fast<2>), grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride);
-    else if (H == 256) hipLaunchKernelGGL((layernorm_fast<1>), grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride);
-    else hipLaunchKernelGGL(layernorm_any, grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride);
+    if (H == 768) hipLaunchKernelGGL((layernorm_fast<3>), grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride, low_fmt);
+    else if (H == 1024) hipLaunchKernelGGL((layernorm_fast<4>), grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride, low_fmt);
+    else if (H == 512) hipLaunchKernelGGL((layernorm_fast<2>), grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride, low_fmt);
+    else if (H == 256) hipLaunchKernelGGL((layernorm_fast<1>), grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride, low_fmt);
+    else hipLaunchKernelGGL(layernorm_any, grid, block, 0, stream, g, M, d_M, H, eps, n_parts, part_stride, low_fmt);
     return hipGetLastError();
 }
 

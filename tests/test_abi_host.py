@@ -1,6 +1,7 @@
 """Host-side checks of the C-ABI library that need no GPU: it loads, exports what include/mt.h
 declares, validates configurations, counts layers like the paper, and reports call-order errors."""
 import ctypes as C
+import dataclasses
 import os
 import re
 
@@ -298,3 +299,55 @@ def test_random_task_tables_host_bookkeeping():
         assert L.mt_load_weights(h, t, C.cast(buf, C.c_void_p), len(blob), None) == mt.MT_ERR_BLOB
         assert str(16 + 4 * flat.size).encode() in L.mt_last_error(h)
         L.mt_destroy(h)
+
+
+def test_fp8_weight_storage_rule_host_side():
+    """The FP8 variant's weight conversion (host side of mt_load_weights) against two independent writings: torch's
+    float8_e4m3fn cast of the scaled values, and the generator's snap-to-grid (which must be a fixed point of it)."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(1)
+    w = (rng.standard_normal(50000) * 0.02).astype(np.float32)
+    w[:8] = [0.0, -0.0, 1e-9, -3e-5, 0.09, -0.11, 2.0 ** -12, 0.0123]
+    s, codes = mt.e4m3_quantize(w)
+    assert s == ms.e4m3_scale(w) and s == 2.0 ** np.floor(np.log2(448.0 / np.abs(w).max()))
+    assert s * np.abs(w).max() <= 448.0 < 2 * s * np.abs(w).max()
+    ref = torch.from_numpy(w * np.float32(s)).to(torch.float8_e4m3fn)
+    assert np.array_equal(codes & 0x7F, ref.view(torch.uint8).numpy() & 0x7F)          # magnitudes (the sign of a zero aside)
+    nz = ref.float().numpy() != 0
+    assert np.array_equal(codes[nz], ref.view(torch.uint8).numpy()[nz])
+    # saturation, ties to even, the sub-normal range, on hand-picked values at unit scale
+    # (the largest entry, 256, gives scale 1)
+    s1, c1 = mt.e4m3_quantize(np.array([17.0, 19.0, 2.0 ** -6, 2.0 ** -9, 2.0 ** -10, 3 * 2.0 ** -10, 0.0, 256.0], dtype=np.float32))
+    got = torch.from_numpy(c1).view(torch.float8_e4m3fn).float().numpy()
+    assert s1 == 1.0
+    assert np.array_equal(got, np.array([16.0, 20.0, 2.0 ** -6, 2.0 ** -9, 0.0, 2.0 ** -8, 0.0, 256.0], dtype=np.float32))
+    # values already on the grid come back unchanged, with the same scale: what lets the oracle use the same numbers
+    # (here the largest entry, 0.11, rounds down onto 224 / 2048, which admits the scale 4096: the generator then snaps
+    #  with 4096, and the result is a fixed point of the library's rule)
+    g = ms.round_to_e4m3_grid(w.copy())
+    s2, codes2 = mt.e4m3_quantize(g)
+    assert s2 == ms.e4m3_scale(g) == 4096.0
+    back = torch.from_numpy(codes2).view(torch.float8_e4m3fn).float().numpy() / np.float32(s2)
+    assert np.array_equal(back, g)
+    assert np.abs(g - w).max() <= 2.0 ** -4 * np.abs(w).max()
+    for seed in range(20):                              # and for matrices like the generator's
+        w2 = (np.random.default_rng(100 + seed).standard_normal(4096) * 0.02).astype(np.float32)
+        g2 = ms.round_to_e4m3_grid(w2.copy())
+        s3, c3 = mt.e4m3_quantize(g2)
+        assert np.array_equal(torch.from_numpy(c3).view(torch.float8_e4m3fn).float().numpy() / np.float32(s3), g2)
+
+
+def test_fp8_variant_configuration_rules():
+    spec = dataclasses.replace(ms.get_config("base"), precision="fp8")
+    rc, h, _ = _create(spec)
+    assert rc == mt.MT_OK
+    L = mt.lib()
+    rc2, h2, _ = _create(ms.get_config("base"))
+    # two E4M3 copies (F*H bytes each) per layer on top of the bf16 arena
+    n_layers = spec.n_trunk_layers + sum(t.n_layers for t in spec.tasks)
+    diff = L.mt_weight_bytes(h) - L.mt_weight_bytes(h2)
+    assert 2 * n_layers * 768 * 3072 <= diff <= 2 * n_layers * (768 * 3072 + 256)
+    L.mt_destroy(h)
+    L.mt_destroy(h2)
+    small = dataclasses.replace(spec, hidden=128, heads=2, ffn=256)          # K of the first contraction below the 3-slice ring
+    assert _create(small)[0] == mt.MT_ERR_CONFIG
