@@ -21,6 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
+PEAK_FP8_MFMA_TFLOPS = 5000.0      # ... and dense FP8
 PEAK_FP32_VALU_TFLOPS = 157.3
 
 
@@ -307,11 +308,15 @@ def gemm_summary(spec, B, rows, prof, dur, kernels, steps, peak):
     return flops, main_flops, gemm_ms, gemm_ms_raw, gemm_launches
 
 
-def side_workload(mt, ms, name, R, fly, steps, warmup, latency_calls=0):
+def side_workload(mt, ms, name, R, fly, steps, warmup, latency_calls=0, precision=None):
     """A short run of another workload: sequences/s and the tiled contraction's TFLOP/s; for the small-batch serving
-    workloads also the per-call latency sweep."""
+    workloads also the per-call latency sweep.  precision "fp8": the same shapes in the FP8 variant (E4M3 feed-forward
+    contractions, whose two classes are then also given against the FP8 matrix-core peak)."""
+    import dataclasses
     import torch
     spec = ms.get_config(name)
+    if precision:
+        spec = dataclasses.replace(spec, precision=precision)
     sv = Served(mt, ms, spec, spec.batch, R, fly)
     sv.run_steps(warmup, sv.n_fly)
     ms_step = sv.run_steps(steps, sv.n_fly) / steps
@@ -324,6 +329,11 @@ def side_workload(mt, ms, name, R, fly, steps, warmup, latency_calls=0):
            "sequences_per_s": spec.batch / (ms_step * 1e-3), "ms_per_step": ms_step, "ms_per_step_one_call_in_flight": ms_serial,
            "gemm_tflops": main_flops / (gemm_ms * 1e-3) / 1e12, "gemm_frac": main_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
            "gemm_launches_per_step": gemm_launches}
+    if spec.precision == "fp8":
+        ent["precision"] = "bf16, feed-forward contractions in FP8 E4M3"
+        for k in ("gemm_ffn1", "gemm_ffn2"):
+            ent[k] = {"tflops": kernels[k]["tflops"], "frac_of_fp8_peak": kernels[k]["tflops"] / PEAK_FP8_MFMA_TFLOPS,
+                      "avg_us": kernels[k]["avg_us"]}
     if latency_calls > 0:
         ent["latency"] = latency_sweep(mt, ms, spec, sv.model, latency_calls)
     sv.close()
@@ -509,6 +519,7 @@ def main():
         torch.cuda.empty_cache()
         side = {}
         side["base_one_request_per_call"] = side_workload(mt, ms, "base", 1, 3, 48, 8)
+        side["base_fp8_ffn"] = side_workload(mt, ms, "base", 8, 2, 24, 8, precision="fp8")
         side["hetero"] = side_workload(mt, ms, "hetero", 4, 2, 16, 4)
         side["large"] = side_workload(mt, ms, "large", 1, 2, 8, 2)
         side["industrial"] = side_workload(mt, ms, "industrial", 8, 2, 64, 8)
