@@ -84,20 +84,34 @@ def host_description():
     return {"logical_cpus": os.cpu_count(), "usable_cpus": usable, "model": model}
 
 
-def stored_traffic(workload_name):
-    """HBM-side bytes per launch of the tiled contraction kernel from the committed counter summary, or None
-    when there is none for this workload or the kernel's source has changed since the counters were taken."""
+TRAFFIC_SOURCES = ("gemm_bf16.hip", "gemm_bf16_persist.hip", "mt_model.cpp")     # kernels and the host code that picks launch shapes
+
+
+def traffic_source_hash():
+    """One hash over the sources that decide the tiled contractions' HBM traffic: both kernels and the scheduler."""
     import hashlib
+    h = hashlib.sha256()
+    for f in TRAFFIC_SOURCES:
+        h.update(open(os.path.join(ROOT, "paper_2107_05377_amd", "csrc", f), "rb").read())
+    return h.hexdigest()
+
+
+def stored_traffic(workload_name, requests_per_call):
+    """HBM-side bytes per launch of the tiled contraction kernels from the committed counter summary (stored, not
+    measured in this run), or None when there is none for this workload and call size or any of TRAFFIC_SOURCES has
+    changed since the counters were taken."""
     path = os.path.join(ROOT, "profiles", f"bench_{workload_name}_hbm_traffic.txt")
-    src = os.path.join(ROOT, "paper_2107_05377_amd", "csrc", "gemm_bf16.hip")
-    if not (os.path.exists(path) and os.path.exists(src)):
+    if not os.path.exists(path):
         return None
     vals = {}
     for line in open(path):
         if " = " in line:
             k, v = line.split(" = ", 1)
             vals[k.strip()] = v.split()[0]
-    if vals.get("kernel_source_sha256") != hashlib.sha256(open(src, "rb").read()).hexdigest():
+    try:
+        if vals.get("kernel_source_sha256") != traffic_source_hash() or int(vals.get("requests_per_call", "1")) != requests_per_call:
+            return None
+    except OSError:
         return None
     return float(vals["traffic_bytes_per_launch"]) if "traffic_bytes_per_launch" in vals else None
 
@@ -261,7 +275,15 @@ class Served:
     def profile(self, steps):
         """Per-kernel-class durations (ms per request batch, event overhead taken off) with one call in flight."""
         import torch
-        ms_serial = self.run_steps(steps, 1) / steps
+        # the chip's clocks settle over the first tenths of a second of load: repeat the (untimed-for-the-headline) pass
+        # until 0.2 s of device time have gone by and keep the last repetition
+        spent, ms_serial = 0.0, 0.0
+        for _ in range(50):
+            t = self.run_steps(steps, 1)
+            spent += t
+            ms_serial = t / steps
+            if spent >= 200.0:
+                break
         self.model.profile_enable(True)
         done = 0
         while done < steps:
@@ -350,8 +372,9 @@ def main():
     ap.add_argument("--config", default="base", help="tiny | base | hetero | latency | large | industrial | wo_kd | mixed | assistant")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--requests-per-call", type=int, default=None,
-                    help="request batches handed to the library per call (mt_forward_multi); 1 = plain mt_forward.  Default: 8 "
-                         "for sequence-level workloads of up to 64 sequences per batch, else 1")
+                    help="request batches handed to the library per call (mt_forward_multi); 1 = plain mt_forward.  Default for "
+                         "sequence-level workloads of up to 64 sequences per batch: the smallest of 8 .. 16 that divides --steps "
+                         "(8 if none does); else 1")
     ap.add_argument("--in-flight", type=int, default=2,
                     help="calls in flight: calls are issued round-robin to this many model replicas (shared "
                          "weights, own workspace) on as many streams; 1 = strictly one call after another")
@@ -388,7 +411,10 @@ def main():
     B = args.batch or spec.batch
     S = spec.seq
     has_tokens = any(getattr(t, "token_level", False) for t in spec.tasks)
-    R = args.requests_per_call if args.requests_per_call else (8 if (B <= 64 and not has_tokens) else 1)
+    # default: calls of 8 request batches; when the timed steps do not fill calls of 8 but do fill calls of 9 .. 16, take that
+    # size, so that every timed call is a full one
+    full = [r for r in range(8, 17) if args.steps % r == 0]
+    R = args.requests_per_call if args.requests_per_call else ((full[0] if full else 8) if (B <= 64 and not has_tokens) else 1)
     if has_tokens:
         R = 1
     sv = Served(mt, ms, spec, B, R, args.in_flight)
@@ -402,15 +428,16 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # Order of the measurements: first the same steps with one call in flight (what the per-kernel figures are measured
+    # on, so that no other call's kernels share the chip with a timed launch) and with HIP events around every launch;
+    # then the headline: W untimed warm-up steps and exactly K timed steps with `n_fly` calls in flight.
+    sv.run_steps(min(args.warmup, 3 * sv.R), 1)
+    ms_serial, prof, dur, kernels, event_overhead_ms = sv.profile(args.steps)
     sv.run_steps(args.warmup, n_fly)
     ms_per_step = sv.run_steps(args.steps, n_fly) / args.steps
     seq_per_s = B / (ms_per_step * 1e-3)
     for o in sv.outs[0][:min(sv.R, args.steps)]:
         assert torch.isfinite(o).all()
-    # the same steps with one call in flight (what the per-kernel figures are measured on, so that no other call's
-    # kernels share the chip with a timed launch), then with HIP events around every launch
-    sv.run_steps(min(args.warmup, 3 * sv.R), 1)
-    ms_serial, prof, dur, kernels, event_overhead_ms = sv.profile(args.steps)
     # ... and call by call with an event pair around every call: median and minimum per request batch
     n_calls = (args.steps + sv.R - 1) // sv.R
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_calls + 1)]
@@ -435,7 +462,7 @@ def main():
     flops, main_flops, gemm_ms, gemm_ms_raw, gemm_launches = gemm_summary(spec, B, rows, prof, dur, kernels, args.steps, peak)
     gemm_tflops = main_flops / (gemm_ms * 1e-3) / 1e12
     kname = ("gemm_bf16_kernel + gemm_bf16_persist_kernel" if rows * sv.R > 256 else "gemm_skinny_bf16_kernel") if bf16 else "gemm_f32_kernel"
-    traffic = stored_traffic(spec.name) if (bf16 and B == spec.batch and rows * sv.R > 256) else None
+    traffic = stored_traffic(spec.name, sv.R) if (bf16 and B == spec.batch and rows * sv.R > 256) else None
     measured_peak = mt.mfma_peak() if bf16 else None
     # per LAUNCH: a launch serves the rows of all request batches of its call
     roofline = {"kernel": kname, "bound": "mfma" if bf16 else "alu",
