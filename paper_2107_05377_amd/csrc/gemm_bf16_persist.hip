@@ -108,7 +108,7 @@ struct TileRef {
 };
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int STAGES, int PARK_COLS, bool OUT_F32, int ACT>
-__global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void gemm_bf16_persist_kernel(GemmGroup g, GemmShape s, int tiles_n)
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void gemm_bf16_persist_kernel(GemmGroup g, GemmShape s, int tiles_n, int band_rows)
 {
     using Cfg = PCfg<BM, BN, WAVES_M, WAVES_N, BK, STAGES, PARK_COLS>;
     constexpr int KK = Cfg::KK;
@@ -148,12 +148,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void gemm_bf16_persist_ke
         const int tile = lo + wi + j * wg_x;
         t.grp = tile / per_problem;
         const int tt = tile - t.grp * per_problem;
-        const int band_sz = kPBand * tiles_n;
+        const int band_sz = band_rows * tiles_n;
         const int band = tt / band_sz;
-        const int rows_in_band = min(kPBand, tiles_m - band * kPBand);
+        const int rows_in_band = min(band_rows, tiles_m - band * band_rows);
         const int tb = tt - band * band_sz;
         const int tn = tb / rows_in_band;
-        const int tm = band * kPBand + tb % rows_in_band;
+        const int tm = band * band_rows + tb % rows_in_band;
         t.m0 = tm * BM;
         t.n0 = tn * BN;
         t.A = static_cast<const unsigned char*>(g.A[t.grp]);
@@ -348,7 +348,8 @@ hipError_t p_launch_one(const GemmGroup& g, const GemmShape& s, int n_wg, hipStr
     static std::atomic<uint64_t> lds_raised{0};
     hipError_t e = ensure_dynamic_lds((const void*)kfn, Cfg::LDS_BYTES, lds_raised);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kfn, dim3(n_wg), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, g, s, tiles_n);
+    // (band heights of 2 .. 16 row-tiles measure the same within noise at these shapes)
+    hipLaunchKernelGGL(kfn, dim3(n_wg), dim3(Cfg::NT), Cfg::LDS_BYTES, stream, g, s, tiles_n, kPBand);
     return hipGetLastError();
 }
 
