@@ -358,8 +358,7 @@ int mt_op_linear_fp8(const void* d_A, int64_t lda, const void* d_W, float scale,
 float mt_debug_e4m3_quantize(const float* h_w, size_t n, uint8_t* h_out);
 
 /* Tuning aid for benchmarks: force one bf16 GEMM tile configuration for all later launches in this
- * process (0 = choose by shape, the default; 1..26 except 13 = a fixed tile configuration, 13 = the few-row kernel, 27..29 = the persistent
- * kernel's three ring shapes;
+ * process (0 = choose by shape, the default; 1..26 except 13 = a fixed tile configuration, 13 = the few-row kernel, 27 = the persistent kernel;
  * any other value resets to 0).  One process-wide setting, not thread-safe: for single-threaded tuning sweeps
  * only, never set while forward passes are being enqueued from other threads.  Returns the previous value. */
 int mt_debug_set_gemm_tile(int32_t sel);

@@ -552,8 +552,8 @@ hipError_t launch_gemm_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t 
     if ((sel == 0 && few_rows) || sel == 13 || s.n_sub > 1 || s.d_sub_rows) {
         return launch_gemm_skinny_bf16(g, s, stream);
     }
-    if (sel >= 27 && sel <= 29) return launch_gemm_bf16_persist(g, s, sel - 27, stream);
-    if (sel == 0 && gemm_bf16_persist_wants(s)) return launch_gemm_bf16_persist(g, s, 0, stream);
+    if (sel == 27) return launch_gemm_bf16_persist(g, s, stream);
+    if (sel == 0 && gemm_bf16_persist_wants(s)) return launch_gemm_bf16_persist(g, s, stream);
     if (sel == 0) {
         // Shape rule from measurements on MI355X (BERT-base widths, 1 and 8 problems, 2304 and 4096 rows).
         // The row bound s.M over-counts when padding is dropped on the device, so the rule keys on the

@@ -34,6 +34,8 @@ constexpr int kPBand = 8;              // row-tiles per raster band
 
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 template <int N>
 __device__ __forceinline__ void p_wait_vmcnt()
@@ -238,6 +240,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void gemm_bf16_persist_ke
     for (int j = 0; j < n_mine; ++j) {
         if (j + 1 < n_mine) locate(j + 1, nxt);
         else nxt = cur;                                 // no next tile: repeat loads of this one, never read
+        // this lane's 4 bias values of the tile, fetched now so that the epilogue does not wait for them
+        static_assert(NCB == 1, "one parked block across the wavefront's sub-tile");
+        float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+        {
+            const float* __restrict__ bias = g.bias[cur.grp];
+            const int nb = cur.n0 + wn0 + c * 4;
+            if (bias && nb < s.N) bv = *reinterpret_cast<const float4*>(bias + nb);
+        }
 #pragma unroll
         for (int i = 0; i < TMI; ++i)
 #pragma unroll
@@ -280,52 +290,82 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64, 1) void gemm_bf16_persist_ke
         for (kt = 1; kt < STAGES; ++kt) MT_P_SLICE(nxt, kt - 1, nxt, kt);
 #undef MT_P_SLICE
 
-        // ---- epilogue of tile `cur`, wavefront-private: park a 32-row x PARK_COLS block of raw accumulators, read it
-        //      back row-contiguously (4 consecutive columns per lane), bias / activation / residual, store row segments
-        const float* __restrict__ res = g.residual[cur.grp];
-        const float* __restrict__ bias = g.bias[cur.grp];
-        unsigned char* __restrict__ Cout = static_cast<unsigned char*>(g.C[cur.grp]);
-        const size_t ldc_b = (size_t)s.ldc * (OUT_F32 ? 4 : 2), ldr_b = (size_t)s.ldr * 4;
+        // ---- epilogue of tile `cur`, wavefront-private: park a 32-row x PARK_COLS block of raw accumulators, read ALL of
+        //      it back row-contiguously (4 consecutive columns per lane) before touching any of it, so that the LDS
+        //      latency is paid once per block, then bias / activation / residual and stores of whole row segments.
+        //      Output and residual go through buffer instructions: a row at or beyond M lies at or beyond the buffer's
+        //      end and is dropped (stores) or read as zero (loads) by the hardware, and a lane whose columns are beyond N
+        //      points beyond the end on purpose; no branch, no 64-bit address arithmetic per row.
+        {
+            const float* __restrict__ res = g.residual[cur.grp];
+            constexpr int ESZ = OUT_F32 ? 4 : 2;
+            const uint32_t ldc_b = (uint32_t)s.ldc * ESZ, ldr_b = (uint32_t)s.ldr * 4;
+            const __amdgpu_buffer_rsrc_t c_rs = __builtin_amdgcn_make_buffer_rsrc(g.C[cur.grp], 0, (int)((uint32_t)M * ldc_b), 0x00020000);
+            const __amdgpu_buffer_rsrc_t r_rs =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(res ? res : (const float*)g.C[cur.grp]), 0, res ? (int)((uint32_t)M * ldr_b) : 0, 0x00020000);
 #pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) {
-            const int n = cur.n0 + wn0 + cb * Cfg::PARK_COLS + c * 4;
-            const bool n_ok = n < s.N;                               // N % 4 == 0
-            float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (bias && n_ok) bv = *reinterpret_cast<const float4*>(bias + n);
+            for (int cb = 0; cb < NCB; ++cb) {
+                const int n = cur.n0 + wn0 + cb * Cfg::PARK_COLS + c * 4;
+                const bool n_ok = n < s.N;                               // N % 4 == 0
+                const uint32_t row0 = (uint32_t)(cur.m0 + wm0 + lane / NCH);
+                // byte offset of this lane's first row in C / in the residual; 0x80000000 (beyond any buffer) if its columns do not exist
+                const uint32_t c_off0 = n_ok ? row0 * ldc_b + (uint32_t)n * ESZ : 0x80000000u;
+                const uint32_t r_off0 = n_ok ? row0 * ldr_b + (uint32_t)n * 4 : 0x80000000u;
 #pragma unroll
-            for (int p = 0; p < TMI; ++p) {
-                const int key_w = (l32 / RPW) & (NCH - 1);
+                for (int p = 0; p < TMI; ++p) {
+                    // rows of the block are handled GRP at a time (all 8 for bf16 output; 4 for float32 output, where the
+                    // residual rows are in registers as well)
+                    constexpr int GRP = OUT_F32 ? NIT / 2 : NIT;
+                    f32x4 rv[GRP];
+                    auto fetch_residual = [&](int it0) {
+                        if constexpr (OUT_F32) {
+                            if (res) {
 #pragma unroll
-                for (int jj = 0; jj < JPB; ++jj)
-#pragma unroll
-                    for (int qq = 0; qq < 4; ++qq) {
-                        const int chunk = (jj * 32 + qq * 8 + half * 4) >> 2;
-                        const f32x16& a = acc[p][cb * JPB + jj];
-                        *reinterpret_cast<float4*>(park + l32 * ROWB + ((chunk ^ key_w) << 4)) =
-                            make_float4(a[qq * 4 + 0], a[qq * 4 + 1], a[qq * 4 + 2], a[qq * 4 + 3]);
-                    }
-                // the same wavefront reads back what it wrote: LDS operations of one wavefront execute in order
-#pragma unroll
-                for (int it = 0; it < NIT; ++it) {
-                    const int ml = it * ROWS_PER_INST + lane / NCH;
-                    const int key = (ml / RPW) & (NCH - 1);
-                    const float4 v = *reinterpret_cast<const float4*>(park + ml * ROWB + ((c ^ key) << 4));
-                    const int mm = cur.m0 + wm0 + p * 32 + ml;
-                    const bool ok = n_ok && mm < M;
-                    float4 o;
-                    o.x = p_act<ACT>(v.x + bv.x);
-                    o.y = p_act<ACT>(v.y + bv.y);
-                    o.z = p_act<ACT>(v.z + bv.z);
-                    o.w = p_act<ACT>(v.w + bv.w);
-                    if constexpr (OUT_F32) {
-                        if (res && ok) {
-                            const float4 rv = *reinterpret_cast<const float4*>(reinterpret_cast<const unsigned char*>(res) + mm * ldr_b + (size_t)n * 4);
-                            o.x += rv.x; o.y += rv.y; o.z += rv.z; o.w += rv.w;
+                                for (int u = 0; u < GRP; ++u)
+                                    rv[u] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                                          r_rs, (int)(r_off0 + (uint32_t)(p * 32 + (it0 + u) * ROWS_PER_INST) * ldr_b), 0, 0));
+                            }
                         }
-                        if (ok) *reinterpret_cast<float4*>(Cout + mm * ldc_b + (size_t)n * 4) = o;
-                    } else {
-                        bf16x4 ob = {(__bf16)o.x, (__bf16)o.y, (__bf16)o.z, (__bf16)o.w};
-                        if (ok) *reinterpret_cast<bf16x4*>(Cout + mm * ldc_b + (size_t)n * 2) = ob;
+                    };
+                    fetch_residual(0);
+                    const int key_w = (l32 / RPW) & (NCH - 1);
+#pragma unroll
+                    for (int jj = 0; jj < JPB; ++jj)
+#pragma unroll
+                        for (int qq = 0; qq < 4; ++qq) {
+                            const int chunk = (jj * 32 + qq * 8 + half * 4) >> 2;
+                            const f32x16& a = acc[p][cb * JPB + jj];
+                            *reinterpret_cast<float4*>(park + l32 * ROWB + ((chunk ^ key_w) << 4)) =
+                                make_float4(a[qq * 4 + 0], a[qq * 4 + 1], a[qq * 4 + 2], a[qq * 4 + 3]);
+                        }
+                    // the same wavefront reads back what it wrote: LDS operations of one wavefront execute in order
+#pragma unroll
+                    for (int it0 = 0; it0 < NIT; it0 += GRP) {
+                        float4 v[GRP];
+#pragma unroll
+                        for (int u = 0; u < GRP; ++u) {
+                            const int ml = (it0 + u) * ROWS_PER_INST + lane / NCH;
+                            const int key = (ml / RPW) & (NCH - 1);
+                            v[u] = *reinterpret_cast<const float4*>(park + ml * ROWB + ((c ^ key) << 4));
+                        }
+#pragma unroll
+                        for (int u = 0; u < GRP; ++u) {
+                            float4 o;
+                            o.x = p_act<ACT>(v[u].x + bv.x);
+                            o.y = p_act<ACT>(v[u].y + bv.y);
+                            o.z = p_act<ACT>(v[u].z + bv.z);
+                            o.w = p_act<ACT>(v[u].w + bv.w);
+                            const int off = (int)(c_off0 + (uint32_t)(p * 32 + (it0 + u) * ROWS_PER_INST) * ldc_b);
+                            if constexpr (OUT_F32) {
+                                if (res) { o.x += rv[u][0]; o.y += rv[u][1]; o.z += rv[u][2]; o.w += rv[u][3]; }
+                                const f32x4 ov = {o.x, o.y, o.z, o.w};
+                                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, ov), c_rs, off, 0, 0);
+                            } else {
+                                const bf16x4 ob = {(__bf16)o.x, (__bf16)o.y, (__bf16)o.z, (__bf16)o.w};
+                                __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, ob), c_rs, off, 0, 0);
+                            }
+                        }
+                        if (it0 + GRP < NIT) fetch_residual(it0 + GRP);
                     }
                 }
             }
@@ -387,6 +427,9 @@ bool gemm_bf16_persist_takes(const GemmShape& s)
 {
     // K slices must outnumber the ring stages (a tile's refills reach at most into the NEXT tile), no K split,
     // no sub-problems; 32-bit byte offsets as in the tiled kernel
+    // (output and residual are addressed through 32-bit buffer offsets with 0x80000000 as the "nowhere" offset)
+    if ((uint64_t)s.M * (uint64_t)s.ldc * (s.out_f32 ? 4 : 2) >= (1ull << 31) || (uint64_t)s.M * (uint64_t)s.ldr * 4 >= (1ull << 31)) return false;
+    if ((uint64_t)s.M * (uint64_t)s.lda * 2 >= (1ull << 32) || (uint64_t)s.N * (uint64_t)(s.ldw ? s.ldw : s.K) * 2 >= (1ull << 32)) return false;
     return s.splits == 1 && s.n_sub <= 1 && !s.d_sub_rows && s.K % 64 == 0 && s.K / 64 >= 4 && s.N % 4 == 0 &&
            (s.act == ACT_NONE || (!s.out_f32 && (s.act == ACT_GELU_ERF || s.act == ACT_GELU_TANH)));
 }
@@ -394,24 +437,23 @@ bool gemm_bf16_persist_takes(const GemmShape& s)
 // Rule from measurements at BERT-base and BERT-large widths (1 and 8 problems, 7 k to 20 k rows): with at least one
 // 256x256 tile per compute unit the persistent form wins by 5-35 % (most where the output is float32 or K is
 // long).  The GELU epilogue is pure vector work that nothing overlaps when one workgroup owns the compute unit, so
-// such launches come here only when a part-filled last round of tiles costs little (8 rounds and more by the row
-// bound).  The row bound over-counts (padding is dropped on the device), so this errs towards the tiled kernel.
+// such launches come here only when a part-filled last round of tiles costs little (4 rounds and more by the row
+// bound, which over-counts by the padding that is dropped on the device: the rule errs towards the tiled kernel).
 bool gemm_bf16_persist_wants(const GemmShape& s)
 {
     if (!gemm_bf16_persist_takes(s)) return false;
     const long tiles = (long)s.G * ((s.M + 255) / 256) * ((s.N + 255) / 256);
     const bool gelu = s.act == ACT_GELU_ERF || s.act == ACT_GELU_TANH;
-    return tiles >= (long)(gelu ? 8 : 1) * cu_count();
+    return tiles >= (long)(gelu ? 4 : 1) * cu_count();
 }
 
-hipError_t launch_gemm_bf16_persist(const GemmGroup& g, const GemmShape& s, int form, hipStream_t stream)
+hipError_t launch_gemm_bf16_persist(const GemmGroup& g, const GemmShape& s, hipStream_t stream)
 {
     if (!gemm_bf16_persist_takes(s)) return hipErrorInvalidValue;
     const long tiles = (long)s.G * ((s.M + 255) / 256) * ((s.N + 255) / 256);
     const int n_wg = (int)std::min<long>(tiles, cu_count());
     if (n_wg < kPXcds) return hipErrorInvalidValue;          // every XCD's tile range needs a workgroup
-    if (form == 1) return p_launch_cfg<256, 256, 2, 4, 64, 2, 32>(g, s, n_wg, stream);      // 128 KB ring of two 64-wide slices
-    if (form == 2) return p_launch_cfg<256, 256, 2, 4, 32, 4, 32>(g, s, n_wg, stream);      // 128 KB ring of four 32-wide slices
+    // (rings of two 64-wide and of four 32-wide slices, with a 32 KB park, were measured equal or slower: not instantiated)
     return p_launch_cfg<256, 256, 2, 4, 32, 3, 64>(g, s, n_wg, stream);                       // 96 KB ring, 64 KB park
 }
 

@@ -28,6 +28,8 @@ typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
 typedef __attribute__((__vector_size__(8 * sizeof(int)))) int i32x8;
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 template <int N>
 __device__ __forceinline__ void f_wait_vmcnt()
@@ -171,6 +173,12 @@ __global__ __launch_bounds__(F_NW * 64, 1) void gemm_fp8_kernel(GemmGroup g, Gem
     for (int j = 0; j < n_mine; ++j) {
         if (j + 1 < n_mine) locate(j + 1, nxt);
         else nxt = cur;                                 // no next tile: repeat loads of this one, never read
+        float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);    // this lane's 4 bias values of the tile, fetched ahead of the epilogue
+        {
+            const float* __restrict__ bias = g.bias[cur.grp];
+            const int nb = cur.n0 + wn0 + c * 4;
+            if (bias && nb < s.N) bv = *reinterpret_cast<const float4*>(bias + nb);
+        }
 #pragma unroll
         for (int i = 0; i < F_TMI; ++i)
 #pragma unroll
@@ -203,52 +211,77 @@ __global__ __launch_bounds__(F_NW * 64, 1) void gemm_fp8_kernel(GemmGroup g, Gem
         for (kt = 0; kt < STAGES; ++kt) MT_F_SLICE(nxt, kt);
 #undef MT_F_SLICE
 
-        // ---- epilogue of tile `cur`, wavefront-private (see gemm_bf16_persist.hip)
-        const float* __restrict__ res = g.residual[cur.grp];
-        const float* __restrict__ bias = g.bias[cur.grp];
-        const float scale = g.scale[cur.grp];
-        unsigned char* __restrict__ Cout = static_cast<unsigned char*>(g.C[cur.grp]);
-        const size_t ldc_b = (size_t)s.ldc * (OUT == 1 ? 4 : (OUT == 0 ? 2 : 1)), ldr_b = (size_t)s.ldr * 4;
-        const int n = cur.n0 + wn0 + c * 4;
-        const bool n_ok = n < s.N;                               // N % 4 == 0
-        float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (bias && n_ok) bv = *reinterpret_cast<const float4*>(bias + n);
+        // ---- epilogue of tile `cur`, wavefront-private (see gemm_bf16_persist.hip): park a 32-row block, read all of it
+        //      back, then scale / bias / activation / residual; output and residual through buffer instructions whose
+        //      bounds check drops rows at or beyond M and lanes whose columns are beyond N
+        {
+            const float* __restrict__ res = g.residual[cur.grp];
+            const float scale = g.scale[cur.grp];
+            constexpr int ESZ = OUT == 1 ? 4 : (OUT == 0 ? 2 : 1);
+            const uint32_t ldc_b = (uint32_t)s.ldc * ESZ, ldr_b = (uint32_t)s.ldr * 4;
+            const __amdgpu_buffer_rsrc_t c_rs = __builtin_amdgcn_make_buffer_rsrc(g.C[cur.grp], 0, (int)((uint32_t)M * ldc_b), 0x00020000);
+            const __amdgpu_buffer_rsrc_t r_rs =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(res ? res : (const float*)g.C[cur.grp]), 0, res ? (int)((uint32_t)M * ldr_b) : 0, 0x00020000);
+            const int n = cur.n0 + wn0 + c * 4;
+            const bool n_ok = n < s.N;                               // N % 4 == 0
+            const uint32_t row0 = (uint32_t)(cur.m0 + wm0 + lane / NCH);
+            const uint32_t c_off0 = n_ok ? row0 * ldc_b + (uint32_t)n * ESZ : 0x80000000u;
+            const uint32_t r_off0 = n_ok ? row0 * ldr_b + (uint32_t)n * 4 : 0x80000000u;
+            const float os = s.out_scale;
 #pragma unroll
-        for (int p = 0; p < F_TMI; ++p) {
-            const int key_w = l32 & (NCH - 1);
+            for (int p = 0; p < F_TMI; ++p) {
+                constexpr int GRP = OUT == 1 ? NIT / 2 : NIT;
+                f32x4 rv[GRP];
+                auto fetch_residual = [&](int it0) {
+                    if constexpr (OUT == 1) {
+                        if (res) {
 #pragma unroll
-            for (int jj = 0; jj < F_TNI; ++jj)
-#pragma unroll
-                for (int qq = 0; qq < 4; ++qq) {
-                    const int chunk = (jj * 32 + qq * 8 + half * 4) >> 2;
-                    const f32x16& a = acc[p][jj];
-                    *reinterpret_cast<float4*>(park + l32 * ROWB + ((chunk ^ key_w) << 4)) =
-                        make_float4(a[qq * 4 + 0], a[qq * 4 + 1], a[qq * 4 + 2], a[qq * 4 + 3]);
-                }
-#pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                const int ml = it * ROWS_PER_INST + lane / NCH;
-                const int key = ml & (NCH - 1);
-                const float4 v = *reinterpret_cast<const float4*>(park + ml * ROWB + ((c ^ key) << 4));
-                const int mm = cur.m0 + wm0 + p * 32 + ml;
-                const bool ok = n_ok && mm < M;
-                float4 o;
-                o.x = f_act<ACT>(fmaf(v.x, scale, bv.x));
-                o.y = f_act<ACT>(fmaf(v.y, scale, bv.y));
-                o.z = f_act<ACT>(fmaf(v.z, scale, bv.z));
-                o.w = f_act<ACT>(fmaf(v.w, scale, bv.w));
-                if constexpr (OUT == 1) {
-                    if (res && ok) {
-                        const float4 rv = *reinterpret_cast<const float4*>(reinterpret_cast<const unsigned char*>(res) + mm * ldr_b + (size_t)n * 4);
-                        o.x += rv.x; o.y += rv.y; o.z += rv.z; o.w += rv.w;
+                            for (int u = 0; u < GRP; ++u)
+                                rv[u] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                                      r_rs, (int)(r_off0 + (uint32_t)(p * 32 + (it0 + u) * ROWS_PER_INST) * ldr_b), 0, 0));
+                        }
                     }
-                    if (ok) *reinterpret_cast<float4*>(Cout + mm * ldc_b + (size_t)n * 4) = o;
-                } else if constexpr (OUT == 0) {
-                    bf16x4 ob = {(__bf16)o.x, (__bf16)o.y, (__bf16)o.z, (__bf16)o.w};
-                    if (ok) *reinterpret_cast<bf16x4*>(Cout + mm * ldc_b + (size_t)n * 2) = ob;
-                } else {
-                    const float os = s.out_scale;
-                    if (ok) *reinterpret_cast<uint32_t*>(Cout + mm * ldc_b + (size_t)n) = pack_e4m3(o.x * os, o.y * os, o.z * os, o.w * os);
+                };
+                fetch_residual(0);
+                const int key_w = l32 & (NCH - 1);
+#pragma unroll
+                for (int jj = 0; jj < F_TNI; ++jj)
+#pragma unroll
+                    for (int qq = 0; qq < 4; ++qq) {
+                        const int chunk = (jj * 32 + qq * 8 + half * 4) >> 2;
+                        const f32x16& a = acc[p][jj];
+                        *reinterpret_cast<float4*>(park + l32 * ROWB + ((chunk ^ key_w) << 4)) =
+                            make_float4(a[qq * 4 + 0], a[qq * 4 + 1], a[qq * 4 + 2], a[qq * 4 + 3]);
+                    }
+#pragma unroll
+                for (int it0 = 0; it0 < NIT; it0 += GRP) {
+                    float4 v[GRP];
+#pragma unroll
+                    for (int u = 0; u < GRP; ++u) {
+                        const int ml = (it0 + u) * ROWS_PER_INST + lane / NCH;
+                        const int key = ml & (NCH - 1);
+                        v[u] = *reinterpret_cast<const float4*>(park + ml * ROWB + ((c ^ key) << 4));
+                    }
+#pragma unroll
+                    for (int u = 0; u < GRP; ++u) {
+                        float4 o;
+                        o.x = f_act<ACT>(fmaf(v[u].x, scale, bv.x));
+                        o.y = f_act<ACT>(fmaf(v[u].y, scale, bv.y));
+                        o.z = f_act<ACT>(fmaf(v[u].z, scale, bv.z));
+                        o.w = f_act<ACT>(fmaf(v[u].w, scale, bv.w));
+                        const int off = (int)(c_off0 + (uint32_t)(p * 32 + (it0 + u) * ROWS_PER_INST) * ldc_b);
+                        if constexpr (OUT == 1) {
+                            if (res) { o.x += rv[u][0]; o.y += rv[u][1]; o.z += rv[u][2]; o.w += rv[u][3]; }
+                            const f32x4 ov = {o.x, o.y, o.z, o.w};
+                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, ov), c_rs, off, 0, 0);
+                        } else if constexpr (OUT == 0) {
+                            const bf16x4 ob = {(__bf16)o.x, (__bf16)o.y, (__bf16)o.z, (__bf16)o.w};
+                            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, ob), c_rs, off, 0, 0);
+                        } else {
+                            __builtin_amdgcn_raw_buffer_store_b32(pack_e4m3(o.x * os, o.y * os, o.z * os, o.w * os), c_rs, off, 0, 0);
+                        }
+                    }
+                    if (it0 + GRP < NIT) fetch_residual(it0 + GRP);
                 }
             }
         }
@@ -298,6 +331,8 @@ hipError_t launch_gemm_fp8(const GemmGroup& g, const GemmShape& s, hipStream_t s
     if ((uint64_t)s.M * (uint64_t)s.lda >= (1ull << 32) || (uint64_t)s.N * (uint64_t)(s.ldw ? s.ldw : s.K) >= (1ull << 32))
         return hipErrorInvalidValue;
     if (s.out_f32 != 1 && g.residual[0]) return hipErrorInvalidValue;
+    // (output and residual are addressed through 32-bit buffer offsets with 0x80000000 as the "nowhere" offset)
+    if ((uint64_t)s.M * (uint64_t)s.ldc * 4 >= (1ull << 31) || (uint64_t)s.M * (uint64_t)s.ldr * 4 >= (1ull << 31)) return hipErrorInvalidValue;
     const long tiles = (long)s.G * ((s.M + F_BM - 1) / F_BM) * ((s.N + F_BN - 1) / F_BN);
     const int n_wg = (int)std::min<long>(tiles, f_cu_count());
     const bool gelu = s.act == ACT_GELU_ERF || s.act == ACT_GELU_TANH;

@@ -58,8 +58,7 @@ hipError_t launch_gemm_fp8(const GemmGroup& g, const GemmShape& s, hipStream_t s
 // its load ring never draining); launch_gemm_bf16 routes to it by itself.  gemm_bf16_persist_takes: shape supported.
 bool gemm_bf16_persist_takes(const GemmShape& s);
 bool gemm_bf16_persist_wants(const GemmShape& s);      // ... and measured faster than the tiled kernel
-// form: ring shape (0: 3 x 32-wide slices, 1: 2 x 64-wide, 2: 4 x 32-wide)
-hipError_t launch_gemm_bf16_persist(const GemmGroup& g, const GemmShape& s, int form, hipStream_t stream);
+hipError_t launch_gemm_bf16_persist(const GemmGroup& g, const GemmShape& s, hipStream_t stream);
 // Few-row variant (M <= 256), memory-parallel instead of tiled; launch_gemm_bf16 routes to it by itself.
 hipError_t launch_gemm_skinny_bf16(const GemmGroup& g, const GemmShape& s, hipStream_t stream);
 // Register-only matrix-core rate measurement: n_cu workgroups of 8 wavefronts, `iters` x 8 MFMAs each; d_out needs

@@ -1647,7 +1647,7 @@ int mt_debug_mfma_peak(int32_t iters, void* d_scratch, size_t scratch_bytes, flo
 int mt_debug_set_gemm_tile(int32_t sel)
 {
     const int prev = mt::g_gemm_bf16_tile_override;
-    mt::g_gemm_bf16_tile_override = (sel >= 0 && sel <= 29) ? sel : 0;
+    mt::g_gemm_bf16_tile_override = (sel >= 0 && sel <= 27) ? sel : 0;
     return prev;
 }
 
