@@ -155,6 +155,17 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
                const uint8_t* h_task_mask, float* d_out_logits, void* hip_stream);
 
 /*
+ * Validation of the one precondition the forward passes do not check themselves (they never wait for the device):
+ * position 0 of every sequence must be a real token, because a sequence-level task head reads the hidden state
+ * of position 0 (Section 3: the students are BERT models).  A sequence whose mask starts with 0 is served from its
+ * first REAL token instead, and a sequence without any real token gets unspecified logits; other sequences are never
+ * affected.  This call counts such sequences on the device, WAITS for the result, writes the count to
+ * *h_bad_sequences and returns MT_OK if it is zero, MT_ERR_SHAPE (with a text) otherwise.  For input pipelines under
+ * test, not for the serving loop.  Errors: NULL, STATE (not bound), SHAPE, HIP.
+ */
+int mt_check_mask(mt_model* m, const int32_t* d_attn_mask, int32_t batch, int32_t seq, int32_t* h_bad_sequences, void* hip_stream);
+
+/*
  * Several request batches in ONE forward pass (dynamic batching across requests: Appendix E's deployment serves a
  * stream of requests, and the merged model is the same function of every sequence whoever sent it).  Request r
  * brings its own device arrays h_d_input_ids[r], h_d_attn_mask[r] ([batch][seq] int32 each) and receives its logits

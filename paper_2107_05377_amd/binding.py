@@ -27,7 +27,7 @@ EXPORTS = ["mt_create", "mt_destroy", "mt_weight_bytes", "mt_workspace_bytes", "
            "mt_forward", "mt_logit_offset", "mt_n_logits", "mt_layer_count", "mt_last_error", "mt_error_name",
            "mt_read_hidden", "mt_profile_enable", "mt_profile_read", "mt_op_linear", "mt_op_attention",
            "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed", "mt_op_linear_sub", "mt_op_first_token_pool", "mt_schedule_steps", "mt_forward_routed",
-           "mt_forward_tokens", "mt_token_logit_offset", "mt_n_token_logits", "mt_forward_static", "mt_forward_multi", "mt_forward_routed_tokens", "mt_op_linear_fp8", "mt_debug_e4m3_quantize"]
+           "mt_forward_tokens", "mt_token_logit_offset", "mt_n_token_logits", "mt_forward_static", "mt_forward_multi", "mt_forward_routed_tokens", "mt_op_linear_fp8", "mt_debug_e4m3_quantize", "mt_check_mask"]
 MT_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 
 
@@ -71,6 +71,7 @@ def lib():
         L.mt_forward_routed.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_tokens.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
         L.mt_forward_routed_tokens.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+        L.mt_check_mask.argtypes = [vp, vp, i32, i32, C.POINTER(C.c_int32), vp]
         L.mt_op_linear_fp8.argtypes = [vp, i64, vp, C.c_float, vp, vp, vp, i64, i32, i32, i32, i32, i32, C.c_float, vp]
         L.mt_debug_e4m3_quantize.argtypes = [vp, sz, vp]
         L.mt_debug_e4m3_quantize.restype = C.c_float
@@ -287,6 +288,15 @@ class Model:
                                                    r.ctypes.data_as(C.c_void_p), _ptr(out) if out is not None and out.numel() else None,
                                                    _ptr(out_tokens) if out_tokens is not None and out_tokens.numel() else None, _stream()))
         return out, out_tokens
+
+    def check_mask(self, mask):
+        """mt_check_mask: number of sequences whose position 0 is padding (waits for the device); raises if any."""
+        n = C.c_int32(-1)
+        b, s = mask.shape
+        rc = lib().mt_check_mask(self.h, _ptr(mask), b, s, C.byref(n), _stream())
+        if rc != MT_OK:
+            raise MTError(rc, lib().mt_last_error(self.h).decode())
+        return int(n.value)
 
     def read_hidden(self, task: int, layer: int, batch: int, seq: int):
         import torch

@@ -78,6 +78,8 @@ struct RowMap {
     int32_t* seq_len;     // [B]  kept rows of sequence b
 };
 hipError_t launch_build_row_map(const int32_t* mask, int B, int S, const RowMap& map, hipStream_t stream);
+// *count = number of sequences whose position 0 is masked off (mask[b][0] == 0; an all-padding sequence is one of them)
+hipError_t launch_count_bad_first_tokens(const int32_t* mask, int B, int S, int32_t* count, hipStream_t stream);
 // out[b*S+s][:] = x[row_of[b*S+s]][:] or 0 (float32, H columns)
 hipError_t launch_unpack_rows(const float* x, const int32_t* row_of, int n_pos, int H, float* out, hipStream_t stream);
 

@@ -122,6 +122,7 @@ struct mt_model {
     std::vector<ClsScratch> task_cls;
     size_t pooled = 0, cls_split = 0;
     size_t rm_n = 0, rm_src = 0, rm_rowof = 0, rm_start = 0, rm_len = 0;   // padding-free row map of the current batch
+    size_t chk_count = 0;                                                   // mt_check_mask: one int32
     size_t mr_ids = 0, mr_mask = 0, mr_logits = 0;                          // mt_forward_multi: the combined batch's ids, mask, logits
     size_t workspace_bytes = 0;
 
@@ -893,6 +894,7 @@ int mt_create(const mt_config* cfg, mt_model** out)
     m->rm_len = sb.take((size_t)cfg->max_batch * 4);
     m->pooled = sb.take(T * (size_t)cfg->max_batch * H * 4);
     m->cls_split = sb.take(T * (size_t)cfg->max_batch * H * 4);   // [hi | lo] bf16 halves, or float32 rows in the validation mode
+    m->chk_count = sb.take(4);
     m->mr_ids = sb.take(M * 4);
     m->mr_mask = sb.take(M * 4);
     m->mr_logits = sb.take((size_t)cfg->max_batch * std::max(m->C_tot, 1) * 4);
@@ -1562,6 +1564,24 @@ int mt_forward_routed_tokens(mt_model* m, const int32_t* d_input_ids, const int3
     if (!h_route) return fail(m, MT_ERR_NULL, "mt_forward_routed_tokens: null routing table");
     return forward_impl(m, d_input_ids, d_token_type_ids, d_attn_mask, batch, seq, nullptr, h_route, d_out_logits, d_out_token_logits,
                         hip_stream);
+}
+
+int mt_check_mask(mt_model* m, const int32_t* d_attn_mask, int32_t batch, int32_t seq, int32_t* h_bad_sequences, void* hip_stream)
+{
+    if (!m) return MT_ERR_NULL;
+    if (!d_attn_mask || !h_bad_sequences) return fail(m, MT_ERR_NULL, "mt_check_mask: null pointer");
+    if (!m->d_ws) return fail(m, MT_ERR_STATE, "mt_check_mask: call mt_bind first");
+    if (batch < 1 || seq < 1) return fail(m, MT_ERR_SHAPE, "mt_check_mask: batch %d x seq %d", batch, seq);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    int32_t* d_count = (int32_t*)(m->d_ws + m->chk_count);
+    hipError_t e = launch_count_bad_first_tokens(d_attn_mask, batch, seq, d_count, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(h_bad_sequences, d_count, 4, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return fail(m, MT_ERR_HIP, "mt_check_mask: %s", hipGetErrorString(e));
+    if (*h_bad_sequences != 0)
+        return fail(m, MT_ERR_SHAPE, "mt_check_mask: %d of %d sequences have no real token at position 0 (the task heads read it)",
+                    *h_bad_sequences, batch);
+    return MT_OK;
 }
 
 int mt_read_hidden(mt_model* m, int32_t task, int32_t layer, float* d_out, size_t out_bytes, void* hip_stream)

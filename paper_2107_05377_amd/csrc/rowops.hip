@@ -650,6 +650,25 @@ hipError_t launch_scatter_logits(const RequestPtrs& rq, int n_req, int batch, in
     return hipGetLastError();
 }
 
+// One workgroup: counts the sequences whose first position is padding.
+__global__ __launch_bounds__(256) void count_bad_first_tokens_kernel(const int32_t* __restrict__ mask, int B, int S, int32_t* __restrict__ count)
+{
+    __shared__ int part[4];
+    int n = 0;
+    for (int b = threadIdx.x; b < B; b += 256) n += mask[(size_t)b * S] == 0 ? 1 : 0;
+    n = wave_sum_int(n);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = n;
+    __syncthreads();
+    if (threadIdx.x == 0) *count = part[0] + part[1] + part[2] + part[3];
+}
+
+hipError_t launch_count_bad_first_tokens(const int32_t* mask, int B, int S, int32_t* count, hipStream_t stream)
+{
+    if (B <= 0 || S <= 0 || !mask || !count) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(count_bad_first_tokens_kernel, dim3(1), dim3(256), 0, stream, mask, B, S, count);
+    return hipGetLastError();
+}
+
 hipError_t launch_build_row_map(const int32_t* mask, int B, int S, const RowMap& map, hipStream_t stream)
 {
     if (B <= 0 || S <= 0) return hipSuccess;

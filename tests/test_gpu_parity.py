@@ -1098,6 +1098,27 @@ def test_token_heads_under_per_sequence_routing(which):
     model.close()
 
 
+def test_mask_precondition_is_checkable():
+    """Position 0 of every sequence must be real: mt_check_mask counts the sequences that break it; a sequence that
+    does is served from its first real token (pinned here against the oracle run on the shifted sequence)."""
+    spec = MINI
+    tr, tri, tps = _params(spec, True, 0.1)
+    model = _load(spec, tr, tri, tps)
+    ids, mask, _ = ms.make_inputs(spec)
+    assert model.check_mask(dev(mask)) == 0
+    bad = mask.copy()
+    bad[1, 0] = 0
+    bad[2, :] = 0
+    with pytest.raises(mt.MTError) as ei:
+        model.check_mask(dev(bad))
+    assert ei.value.code == mt.MT_ERR_SHAPE and "2 of 3" in str(ei.value)
+    # sequence 0 is untouched by its neighbours' bad masks
+    ref = oracle.Oracle(spec, tr, [p for p, _ in tps]).mt_forward(ids, mask)
+    got = model.forward(dev(ids), dev(bad)).cpu().numpy()
+    assert max(rel_err_per_task(spec, got[:1], ref[:1])) <= 1e-4
+    model.close()
+
+
 def test_read_hidden_refuses_states_the_last_forward_did_not_write():
     """A trunk tap is readable only if the last forward pass ran the trunk that deep: with the deeper tasks masked
     off the trunk stops at the deepest enabled fork, and with no task enabled nothing runs at all."""
