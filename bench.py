@@ -100,20 +100,19 @@ def stored_traffic(workload_name, requests_per_call):
     """HBM-side bytes per launch of the tiled contraction kernels from the committed counter summary (stored, not
     measured in this run), or None when there is none for this workload and call size or any of TRAFFIC_SOURCES has
     changed since the counters were taken."""
-    path = os.path.join(ROOT, "profiles", f"bench_{workload_name}_hbm_traffic.txt")
-    if not os.path.exists(path):
-        return None
-    vals = {}
-    for line in open(path):
-        if " = " in line:
-            k, v = line.split(" = ", 1)
-            vals[k.strip()] = v.split()[0]
-    try:
-        if vals.get("kernel_source_sha256") != traffic_source_hash() or int(vals.get("requests_per_call", "1")) != requests_per_call:
-            return None
-    except OSError:
-        return None
-    return float(vals["traffic_bytes_per_launch"]) if "traffic_bytes_per_launch" in vals else None
+    import glob
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", f"bench_{workload_name}_hbm_traffic*.txt"))):
+        vals = {}
+        for line in open(path):
+            if " = " in line:
+                k, v = line.split(" = ", 1)
+                vals[k.strip()] = v.split()[0]
+        if "traffic_bytes_per_launch" not in vals or int(vals.get("requests_per_call", "1")) != requests_per_call:
+            continue
+        if vals.get("kernel_source_sha256") != traffic_source_hash():
+            continue
+        return float(vals["traffic_bytes_per_launch"])
+    return None
 
 
 def latency_sweep(mt, ms, spec, model, calls):
