@@ -138,8 +138,36 @@ def latency_sweep(mt, ms, spec, model, calls):
             forward(model, sets[i % 8], out, tok)
             torch.cuda.synchronize()
             t[i] = time.perf_counter() - t0
-        res.append({"batch": b, "calls": calls, "p50_ms": float(np.percentile(t, 50) * 1e3), "p99_ms": float(np.percentile(t, 99) * 1e3),
-                    "mean_ms": float(t.mean() * 1e3), "sequences_per_s": float(b / t.mean())})
+        ent = {"batch": b, "calls": calls, "p50_ms": float(np.percentile(t, 50) * 1e3), "p99_ms": float(np.percentile(t, 99) * 1e3),
+               "mean_ms": float(t.mean() * 1e3), "sequences_per_s": float(b / t.mean())}
+        # the same forward captured once as a HIP graph and replayed (the forward only enqueues kernels: nothing in it
+        # allocates, copies, clears or waits); every replay is checked against the launched result
+        forward(model, sets[0], out, tok)
+        torch.cuda.synchronize()
+        launched = out.clone()
+        out_g = torch.zeros_like(out)
+        tok_g = torch.zeros_like(tok) if tok is not None else None
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            forward(model, sets[0], out_g, tok_g)
+        same = True
+        n_rep = max(50, calls // 4)
+        tg = np.empty(n_rep)
+        for i in range(n_rep):
+            if i < 3:
+                out_g.zero_()
+                forward(model, sets[1], out, tok)          # launched work between the replays
+                torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            graph.replay()
+            torch.cuda.synchronize()
+            tg[i] = time.perf_counter() - t0
+            if i < 3:
+                same = same and bool(torch.equal(out_g, launched))
+        ent["graph_replay"] = {"calls": n_rep, "p50_ms": float(np.percentile(tg, 50) * 1e3), "p99_ms": float(np.percentile(tg, 99) * 1e3),
+                               "bit_identical_to_launched": same}
+        del graph
+        res.append(ent)
     return res
 
 

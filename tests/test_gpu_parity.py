@@ -1147,3 +1147,37 @@ def test_read_hidden_refuses_states_the_last_forward_did_not_write():
         model.read_hidden(-1, 0, *ids.shape)
     assert ei.value.code == mt.MT_ERR_STATE
     model.close()
+
+
+def test_forward_is_capture_safe_and_replays_bit_identically():
+    """mt_forward only enqueues kernels (no allocation, copy, memset or wait inside), so a caller may capture it in a HIP
+    graph.  Each of several replays, with launched work and synchronisations between them, must equal the launched
+    result bit for bit, also after the captured input buffers have been refilled."""
+    spec = ms.get_config("latency")
+    model, _ = mt.load_synthetic(spec)
+    for b in (1, 8):
+        ids_h, mask_h, _ = ms.make_inputs(spec, batch=b)
+        ids, mask = dev(ids_h), dev(mask_h)
+        launched = model.forward(ids, mask).clone()
+        torch.cuda.synchronize()
+        out_g = torch.zeros_like(launched)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            model.forward(ids, mask, out=out_g)
+        other_h = ms.make_inputs(spec, batch=b, batch_index=5)
+        for rep in range(3):
+            out_g.zero_()
+            model.forward(dev(other_h[0]), dev(other_h[1]))          # launched work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out_g, launched), f"replay {rep} at batch {b} differs from the launched forward"
+        ids.copy_(dev(other_h[0]))
+        mask.copy_(dev(other_h[1]))
+        graph.replay()
+        torch.cuda.synchronize()
+        want = model.forward(dev(other_h[0]), dev(other_h[1]))
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, want)
+        del graph
+    model.close()
