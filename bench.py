@@ -46,7 +46,7 @@ def gemm_flops_per_forward(spec, rows, batch):
     projection and feed-forward layers on one row."""
     H, F, A = spec.hidden, spec.ffn, spec.heads
     n_full, n_first = layer_kinds(spec)
-    kvfree = spec.precision == "bf16" and A <= 16
+    kvfree = spec.precision in ("bf16", "fp8", "fp8_all") and A <= 16
     first = 2.0 * batch * (2 * H * H + 2 * H * F)                      # query, output projection, FFN1, FFN2
     qkv_last = 0.0
     if kvfree:
@@ -378,9 +378,10 @@ def side_workload(mt, ms, name, R, fly, steps, warmup, latency_calls=0, precisio
            "sequences_per_s": spec.batch / (ms_step * 1e-3), "ms_per_step": ms_step, "ms_per_step_one_call_in_flight": ms_serial,
            "gemm_tflops": main_flops / (gemm_ms * 1e-3) / 1e12, "gemm_frac": main_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
            "gemm_launches_per_step": gemm_launches}
-    if spec.precision == "fp8":
-        ent["precision"] = "bf16, feed-forward contractions in FP8 E4M3"
-        for k in ("gemm_ffn1", "gemm_ffn2"):
+    if spec.precision in ("fp8", "fp8_all"):
+        ent["precision"] = ("bf16, feed-forward contractions in FP8 E4M3" if spec.precision == "fp8" else
+                            "bf16, all four contractions of a layer in FP8 E4M3")
+        for k in (("gemm_ffn1", "gemm_ffn2") if spec.precision == "fp8" else ("gemm_qkv", "gemm_out", "gemm_ffn1", "gemm_ffn2")):
             ent[k] = {"tflops": kernels[k]["tflops"], "frac_of_fp8_peak": kernels[k]["tflops"] / PEAK_FP8_MFMA_TFLOPS,
                       "avg_us": kernels[k]["avg_us"]}
     if latency_calls > 0:
@@ -574,6 +575,7 @@ def main():
         side = {}
         side["base_one_request_per_call"] = side_workload(mt, ms, "base", 1, 3, 192, 24)
         side["base_fp8_ffn"] = side_workload(mt, ms, "base", 8, 2, 48, 8, precision="fp8")
+        side["base_fp8_layer"] = side_workload(mt, ms, "base", 8, 2, 48, 8, precision="fp8_all")
         side["hetero"] = side_workload(mt, ms, "hetero", 4, 2, 32, 4)
         side["large"] = side_workload(mt, ms, "large", 1, 2, 16, 2)
         side["industrial"] = side_workload(mt, ms, "industrial", 8, 2, 128, 8)

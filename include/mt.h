@@ -40,7 +40,7 @@ enum {
     MT_ERR_HIP = -6      /* a HIP runtime call failed */
 };
 
-enum { MT_BF16 = 0, MT_FP32_CHECK = 1, MT_FP8_FFN = 2 };     /* mt_config.precision */
+enum { MT_BF16 = 0, MT_FP32_CHECK = 1, MT_FP8_FFN = 2, MT_FP8_LAYER = 3 };     /* mt_config.precision */
 enum { MT_GELU_ERF = 0, MT_GELU_TANH = 1 };  /* mt_config.gelu */
 enum { MT_HEAD_SEQUENCE = 0, MT_HEAD_TOKEN = 1 };  /* mt_task_desc.head */
 
@@ -80,6 +80,11 @@ typedef struct {
  * LayerNorm output that feeds the first contraction and the GELU output that feeds the second are rounded to E4M3
  * (unit scale, saturating at +-448) instead of bfloat16.  Everything else, including the first-token-only last
  * layer of every branch, is as in MT_BF16.  Needs hidden >= 192 and ffn >= 192 on top of MT_BF16's conditions.
+ * MT_FP8_LAYER: MT_FP8_FFN with the other two contractions of such a layer in E4M3 as well: the query/key/value
+ * projection (the three matrices stored as one [3H, H] matrix under ONE storage scale; its operand is the layer
+ * input's bfloat16 copy rounded to E4M3) and the attention output projection (its operand, the attention context, is
+ * written as E4M3 by the attention kernel).  Queries, keys, values, the softmax and the float32 residual stream stay as
+ * in MT_BF16.
  * max_batch*max_seq bounds the workspace; max_seq <= max_pos.
  */
 typedef struct {

@@ -11,8 +11,8 @@ because the forward pass is shape-, not value-, dependent.
 """
 from .spec import MTSpec, TaskSpec, CONFIGS, get_config, trunk_tensors, task_tensors, layer_tensors
 from .gen import (splitmix64, uniform01, normal, make_trunk_params, make_task_params,
-                  make_inputs, round_to_bf16_grid, round_to_e4m3_grid, e4m3_scale)
+                  make_inputs, round_to_bf16_grid, round_to_e4m3_grid, round_group_to_e4m3_grid, e4m3_scale)
 
 __all__ = ["MTSpec", "TaskSpec", "CONFIGS", "get_config", "trunk_tensors", "task_tensors",
            "layer_tensors", "splitmix64", "uniform01", "normal", "make_trunk_params",
-           "make_task_params", "make_inputs", "round_to_bf16_grid", "round_to_e4m3_grid", "e4m3_scale"]
+           "make_task_params", "make_inputs", "round_to_bf16_grid", "round_to_e4m3_grid", "round_group_to_e4m3_grid", "e4m3_scale"]

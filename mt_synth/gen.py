@@ -9,7 +9,9 @@ beta 0.  `stress=True` instead draws biases and beta ~ N(0, 0.02) and gamma ~ 1 
 bias/gamma/beta code paths carry signal.  `bf16_grid=True` snaps matrices and embedding tables to
 values representable in bfloat16 (round to nearest even), so a consumer that stores them as
 bfloat16 and one that keeps float32 see identical numbers.  A spec of precision "fp8" additionally snaps the
-two feed-forward matrices of every layer to the FP8 E4M3 grid under their power-of-two storage scale.
+two feed-forward matrices of every layer to the FP8 E4M3 grid under their power-of-two storage scale; precision
+"fp8_all" snaps the attention output matrix Wo likewise, and Wq, Wk, Wv of a layer under ONE scale taken over the three
+(a consumer may store them as one [3H, H] matrix).
 
 Input recipe: sequence lengths uniform on the inclusive range [len_lo, len_hi]; the attention mask
 is a prefix of ones; token ids are uniform in [0, vocab) at every position, padded ones included.
@@ -127,9 +129,35 @@ def round_to_e4m3_grid(x: np.ndarray, scale: float | None = None) -> np.ndarray:
     return x
 
 
-def _fill(flat: np.ndarray, tensors, seed: int, scope_id: int, std: float, stress: bool, bf16_grid: bool, fp8_ffn: bool = False):
+def round_group_to_e4m3_grid(views) -> float:
+    """Snap several float32 arrays, in place, to the E4M3 grid under ONE storage scale: that of their union, chosen so
+    that the snapped union has the same storage scale again (see round_to_e4m3_grid).  Returns the scale."""
+    def joint(arrs):
+        return min(e4m3_scale(a) for a in arrs)      # the union's largest entry decides
+    s = joint(views)
+    snapped = [_snap_e4m3(v, s) for v in views]
+    for _ in range(4):
+        s2 = joint(snapped)
+        if s2 == s:
+            break
+        s = s2
+        snapped = [_snap_e4m3(v, s) for v in views]
+    assert joint(snapped) == s
+    for v, y in zip(views, snapped):
+        v[...] = y
+    return s
+
+
+def _fp8_flags(precision: str):
+    """(feed-forward matrices on the E4M3 grid, attention matrices on the E4M3 grid) for a spec's precision."""
+    return precision in ("fp8", "fp8_all"), precision == "fp8_all"
+
+
+def _fill(flat: np.ndarray, tensors, seed: int, scope_id: int, std: float, stress: bool, bf16_grid: bool, fp8_ffn: bool = False,
+          fp8_attn: bool = False):
     off = 0
     index = []
+    held = {}                                     # Wq, Wk of the layer being filled, until its Wv arrives
     for ti, (name, shape) in enumerate(tensors):
         n = int(np.prod(shape))
         view = flat[off:off + n]
@@ -138,8 +166,12 @@ def _fill(flat: np.ndarray, tensors, seed: int, scope_id: int, std: float, stres
         if len(shape) == 2:                       # matrices and embedding tables
             normal(key, n, out=view)
             view *= np.float32(std)
-            if fp8_ffn and base in ("W1", "W2"):
+            if (fp8_ffn and base in ("W1", "W2")) or (fp8_attn and base == "Wo"):
                 round_to_e4m3_grid(view)          # E4M3 values (times a power of two) are bfloat16 values too
+            elif fp8_attn and base in ("Wq", "Wk"):
+                held[base] = view
+            elif fp8_attn and base == "Wv":
+                round_group_to_e4m3_grid([held.pop("Wq"), held.pop("Wk"), view])
             elif bf16_grid:
                 round_to_bf16_grid(view)
         elif base.endswith("_g"):                 # LayerNorm gamma
@@ -163,20 +195,20 @@ def _count(tensors) -> int:
 def make_trunk_params(spec: MTSpec, *, stress: bool = False, bf16_grid: bool | None = None,
                       seed: int | None = None, std: float = 0.02):
     """Flat float32 parameter vector of the trunk scope (canonical order) and its (name, shape, offset) index."""
-    bf16_grid = (spec.precision in ("bf16", "fp8")) if bf16_grid is None else bf16_grid
+    bf16_grid = (spec.precision in ("bf16", "fp8", "fp8_all")) if bf16_grid is None else bf16_grid
     tensors = trunk_tensors(spec)
     flat = np.empty(_count(tensors), dtype=np.float32)
-    index = _fill(flat, tensors, spec.weights_seed if seed is None else seed, 0, std, stress, bf16_grid, spec.precision == "fp8")
+    index = _fill(flat, tensors, spec.weights_seed if seed is None else seed, 0, std, stress, bf16_grid, *_fp8_flags(spec.precision))
     return flat, index
 
 
 def make_task_params(spec: MTSpec, t: int, *, stress: bool = False, bf16_grid: bool | None = None,
                      seed: int | None = None, std: float = 0.02):
     """Flat float32 parameter vector of task t's scope (canonical order) and its index."""
-    bf16_grid = (spec.precision in ("bf16", "fp8")) if bf16_grid is None else bf16_grid
+    bf16_grid = (spec.precision in ("bf16", "fp8", "fp8_all")) if bf16_grid is None else bf16_grid
     tensors = task_tensors(spec, t)
     flat = np.empty(_count(tensors), dtype=np.float32)
-    index = _fill(flat, tensors, spec.weights_seed if seed is None else seed, 1 + t, std, stress, bf16_grid, spec.precision == "fp8")
+    index = _fill(flat, tensors, spec.weights_seed if seed is None else seed, 1 + t, std, stress, bf16_grid, *_fp8_flags(spec.precision))
     return flat, index
 
 

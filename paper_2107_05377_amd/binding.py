@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmt_hip.so")
 
 MT_OK, MT_ERR_NULL, MT_ERR_CONFIG, MT_ERR_SHAPE, MT_ERR_STATE, MT_ERR_BLOB, MT_ERR_HIP = 0, -1, -2, -3, -4, -5, -6
-MT_BF16, MT_FP32_CHECK, MT_FP8_FFN = 0, 1, 2
+MT_BF16, MT_FP32_CHECK, MT_FP8_FFN, MT_FP8_LAYER = 0, 1, 2, 3
 MT_GELU_ERF, MT_GELU_TANH = 0, 1
 MT_ABI_VERSION = 2
 MT_HEAD_SEQUENCE, MT_HEAD_TOKEN = 0, 1
@@ -114,7 +114,7 @@ def make_config(spec, *, max_batch=None, max_seq=None, precision=None):
     tasks = (mt_task_desc * len(spec.tasks))(*[mt_task_desc(t.fork_layer, t.n_layers, t.n_classes,
                                                             MT_HEAD_TOKEN if getattr(t, "token_level", False) else MT_HEAD_SEQUENCE)
                                                for t in spec.tasks])
-    prec = precision if precision is not None else {"bf16": MT_BF16, "fp8": MT_FP8_FFN}.get(spec.precision, MT_FP32_CHECK)
+    prec = precision if precision is not None else {"bf16": MT_BF16, "fp8": MT_FP8_FFN, "fp8_all": MT_FP8_LAYER}.get(spec.precision, MT_FP32_CHECK)
     cfg = mt_config(C.sizeof(mt_config), MT_ABI_VERSION, spec.vocab, spec.hidden, spec.heads, spec.ffn, spec.max_pos,
                     spec.type_vocab, spec.n_trunk_layers, len(spec.tasks), tasks, prec,
                     MT_GELU_TANH if spec.gelu == "tanh" else MT_GELU_ERF, spec.ln_eps,

@@ -46,7 +46,7 @@ constexpr int CB = MT_ATTN_CB;        // 32-key blocks per online-softmax chunk
 __global__ __launch_bounds__(256, MT_ATTN_MINW) void attention_bf16_kernel(AttnGroup g, const int32_t* __restrict__ mask,
                                                              const int32_t* __restrict__ seq_start,
                                                              const int32_t* __restrict__ seq_len, int B, int S, int H, int Sk_max,
-                                                             float scale_log2e)
+                                                             float scale_log2e, int ctx_fmt)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int grp = blockIdx.z / B, b = blockIdx.z % B, a = blockIdx.y;
@@ -232,7 +232,16 @@ __global__ __launch_bounds__(256, MT_ATTN_MINW) void attention_bf16_kernel(AttnG
         }
     }
 
-    if (q < n_tok) {
+    if (q < n_tok && ctx_fmt == 1) {             // E4M3 at unit scale: one byte per element
+        const float inv = 1.0f / l_run;
+        unsigned char* out = static_cast<unsigned char*>(g.ctx[grp]) + ((size_t)row0 + q) * H + a * 64;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq)
+                *reinterpret_cast<uint32_t*>(out + dt * 32 + qq * 8 + half * 4) =
+                    pack_e4m3(o[dt][qq * 4 + 0] * inv, o[dt][qq * 4 + 1] * inv, o[dt][qq * 4 + 2] * inv, o[dt][qq * 4 + 3] * inv);
+    } else if (q < n_tok) {
         const float inv = 1.0f / l_run;
         __bf16* out = static_cast<__bf16*>(g.ctx[grp]) + ((size_t)row0 + q) * H + a * 64;
 #pragma unroll
@@ -482,11 +491,11 @@ hipError_t launch_attention_cls(const AttnClsGroup& g, int G, int is_bf16, const
 }
 
 hipError_t launch_attention_bf16(const AttnGroup& g, int G, const int32_t* mask, const int32_t* seq_start,
-                                 const int32_t* seq_len, int B, int S, int H, int A, hipStream_t stream)
+                                 const int32_t* seq_len, int B, int S, int H, int A, hipStream_t stream, int ctx_fmt)
 {
     if (!mask && !(seq_start && seq_len)) return hipErrorInvalidValue;
     if (G <= 0 || B <= 0 || S <= 0) return hipSuccess;
-    if (H != A * 64 || G > kMaxGroup || S > kAttnBf16MaxSeq) return hipErrorInvalidValue;
+    if (H != A * 64 || G > kMaxGroup || S > kAttnBf16MaxSeq || (ctx_fmt != 0 && ctx_fmt != 1)) return hipErrorInvalidValue;
     const int Sk = (S + 31) / 32 * 32;
     const size_t lds = (size_t)Sk * 128 + (size_t)64 * (Sk + 4) * 2 + (size_t)Sk * 4 + (size_t)(Sk / 32) * 4;
     static_assert(kAttnBf16MaxSeq % 32 == 0 &&
@@ -502,7 +511,7 @@ hipError_t launch_attention_bf16(const AttnGroup& g, int G, const int32_t* mask,
     }
     dim3 grid((S + 127) / 128, A, B * G), block(256);
     const float scale_log2e = (1.0f / sqrtf(64.0f)) * kLog2e;
-    hipLaunchKernelGGL(attention_bf16_kernel, grid, block, lds, stream, g, mask, seq_start, seq_len, B, S, H, Sk, scale_log2e);
+    hipLaunchKernelGGL(attention_bf16_kernel, grid, block, lds, stream, g, mask, seq_start, seq_len, B, S, H, Sk, scale_log2e, ctx_fmt);
     return hipGetLastError();
 }
 

@@ -80,6 +80,12 @@ struct RowMap {
 hipError_t launch_build_row_map(const int32_t* mask, int B, int S, const RowMap& map, hipStream_t stream);
 // *count = number of sequences whose position 0 is masked off (mask[b][0] == 0; an all-padding sequence is one of them)
 hipError_t launch_count_bad_first_tokens(const int32_t* mask, int B, int S, int32_t* count, hipStream_t stream);
+// bfloat16 [M][H] -> E4M3 [M][H] (unit scale, saturating) for up to kMaxGroup arrays in one launch; rows past *d_M are left alone
+struct CastGroup {
+    const void* src[kMaxGroup];
+    void* dst[kMaxGroup];
+};
+hipError_t launch_cast_bf16_to_e4m3(const CastGroup& g, int G, int M, const int32_t* d_M, int H, hipStream_t stream);
 // out[b*S+s][:] = x[row_of[b*S+s]][:] or 0 (float32, H columns)
 hipError_t launch_unpack_rows(const float* x, const int32_t* row_of, int n_pos, int H, float* out, hipStream_t stream);
 
@@ -92,8 +98,9 @@ struct AttnGroup {
 };
 // Sequence b owns rows seq_start[b] .. +seq_len[b]-1 (all real tokens) when the two arrays are given;
 // otherwise rows b*S .. b*S+S-1 with `mask` ([B][S], 1 = real) marking the keys.  S bounds the length.
+// ctx_fmt 0: the context is written as bfloat16; 1: as E4M3 at unit scale (one byte per element, same row order)
 hipError_t launch_attention_bf16(const AttnGroup& g, int G, const int32_t* mask, const int32_t* seq_start,
-                                 const int32_t* seq_len, int B, int S, int H, int A, hipStream_t stream);
+                                 const int32_t* seq_len, int B, int S, int H, int A, hipStream_t stream, int ctx_fmt = 0);
 hipError_t launch_attention_f32(const AttnGroup& g, int G, const int32_t* mask, const int32_t* seq_start,
                                 const int32_t* seq_len, int B, int S, int H, int A, hipStream_t stream);
 

@@ -70,6 +70,9 @@ struct LayerW {   // byte offsets into the weight arena
     // keeps s * max|W| <= 448; inv_s (set when the checkpoint is loaded) undoes it in the contraction's epilogue
     size_t W1q = 0, W2q = 0;
     float inv_s1 = 1.f, inv_s2 = 1.f;
+    // MT_FP8_LAYER: likewise [3H][H] of Wq, Wk, Wv under one scale, and Wo
+    size_t Wqkvq = 0, Woq = 0;
+    float inv_sqkv = 1.f, inv_so = 1.f;
 };
 struct TaskW {
     std::vector<LayerW> layers;
@@ -100,7 +103,8 @@ struct mt_model {
     mt_config cfg;
     std::vector<mt_task_desc> tasks;
     bool bf16 = true;
-    bool fp8 = false;   // MT_FP8_FFN: bf16 everywhere, the two feed-forward contractions of every all-rows layer in E4M3
+    bool fp8 = false;   // MT_FP8_FFN / MT_FP8_LAYER: bf16 everywhere, the two feed-forward contractions of every all-rows layer in E4M3
+    bool fp8_attn = false;   // MT_FP8_LAYER: the QKV and attention output projections of such a layer too
     size_t esz = 2;   // bytes per matrix / activation element
     int C_tot = 0, C_tok = 0;            // widths of the per-sequence and of the per-token logit row
     std::vector<int> logit_off;          // task -> first column inside the row of its kind
@@ -174,7 +178,7 @@ struct Bump {
     }
 };
 
-LayerW layout_layer(Bump& b, size_t H, size_t F, size_t esz, bool fp8 = false)
+LayerW layout_layer(Bump& b, size_t H, size_t F, size_t esz, bool fp8 = false, bool fp8_attn = false)
 {
     LayerW L;
     L.Wqkv = b.take(3 * H * H * esz);
@@ -192,6 +196,10 @@ LayerW layout_layer(Bump& b, size_t H, size_t F, size_t esz, bool fp8 = false)
     if (fp8) {
         L.W1q = b.take(F * H);
         L.W2q = b.take(H * F);
+    }
+    if (fp8_attn) {
+        L.Wqkvq = b.take(3 * H * H);
+        L.Woq = b.take(H * H);
     }
     return L;
 }
@@ -295,13 +303,31 @@ size_t stage_layer(const mt_model* m, LayerW& L, const float* p, unsigned char* 
             put_matrix(at(L.WkT) + n * H * 2, col.data(), H, true);
         }
     }
+    if (L.Wqkvq) {                  // one storage scale over Wq, Wk, Wv: the largest of the three maxima decides
+        float sc = e4m3_scale_for(p, H * H);
+        sc = std::min(sc, e4m3_scale_for(p + (H * H + H), H * H));
+        sc = std::min(sc, e4m3_scale_for(p + 2 * (H * H + H), H * H));
+        for (int i = 0; i < 3; ++i) {
+            const float* w = p + (size_t)i * (H * H + H);
+            uint8_t* q = at(L.Wqkvq) + (size_t)i * H * H;
+            for (size_t e = 0; e < H * H; ++e) q[e] = f32_to_e4m3_rne(w[e] * sc);
+        }
+        L.inv_sqkv = 1.0f / sc;
+    }
     for (int i = 0; i < 3; ++i) {   // Wq bq Wk bk Wv bv -> one [3H,H] matrix and one [3H] bias
         put_matrix(at(L.Wqkv) + (size_t)i * H * H * m->esz, p, H * H, m->bf16);
         p += H * H;
         memcpy(at(L.bqkv) + (size_t)i * H * 4, p, H * 4);
         p += H;
     }
-    put_matrix(at(L.Wo), p, H * H, m->bf16); p += H * H;
+    put_matrix(at(L.Wo), p, H * H, m->bf16);
+    if (L.Woq) {
+        const float sc = e4m3_scale_for(p, H * H);
+        uint8_t* q = at(L.Woq);
+        for (size_t e = 0; e < H * H; ++e) q[e] = f32_to_e4m3_rne(p[e] * sc);
+        L.inv_so = 1.0f / sc;
+    }
+    p += H * H;
     memcpy(at(L.bo), p, H * 4); p += H;
     memcpy(at(L.ln1g), p, H * 4); p += H;
     memcpy(at(L.ln1b), p, H * 4); p += H;
@@ -405,16 +431,47 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& 
     GemmShape s;
 
     // QKV projection: [M,H] x [3H,H]^T + b -> [M,3H]
+    const bool f8a = m->fp8_attn;
+    if (f8a) {
+        // E4M3 operand copies of the layer inputs, into the head of each problem's FFN buffer u (free until FFN1 writes
+        // it); problems that read the same input (branches forking at one tap) share the first one's copy
+        CastGroup cg;
+        memset(&cg, 0, sizeof cg);
+        int n_cast = 0;
+        for (int i = 0; i < n; ++i) {
+            int same = -1;
+            for (int j = 0; j < i && same < 0; ++j)
+                if (io[j].in_b == io[i].in_b) same = j;
+            if (same >= 0) {
+                g.A[i] = g.A[same];
+                continue;
+            }
+            cg.src[n_cast] = io[i].in_b;
+            cg.dst[n_cast] = ws + io[i].scr->u;
+            g.A[i] = ws + io[i].scr->u;
+            ++n_cast;
+        }
+        L.begin(MT_K_LN);
+        L.check(launch_cast_bf16_to_e4m3(cg, n_cast, M, rm.n_rows, H, L.st));
+        L.end();
+    }
     for (int i = 0; i < n; ++i) {
-        g.A[i] = bf ? io[i].in_b : (const void*)io[i].in_f;
-        g.W[i] = W + io[i].w->Wqkv;
+        if (!f8a) g.A[i] = bf ? io[i].in_b : (const void*)io[i].in_f;
+        g.W[i] = W + (f8a ? io[i].w->Wqkvq : io[i].w->Wqkv);
         g.bias[i] = (const float*)(W + io[i].w->bqkv);
         g.residual[i] = nullptr;
         g.C[i] = ws + io[i].scr->qkv;
         g.N[i] = 3 * H;
+        g.scale[i] = io[i].w->inv_sqkv;
     }
     s = GemmShape{n, M, 3 * H, H, H, 3 * H, 0, ACT_NONE, bf ? 0 : 1, rm.n_rows, 1, 0};
-    L.gemm(MT_K_GEMM_QKV, g, s, false);
+    if (f8a) {
+        L.begin(MT_K_GEMM_QKV);
+        L.check(launch_gemm_fp8(g, s, L.st));
+        L.end();
+    } else {
+        L.gemm(MT_K_GEMM_QKV, g, s, false);
+    }
 
     // attention
     AttnGroup ag;
@@ -424,7 +481,8 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& 
         ag.ctx[i] = ws + io[i].scr->ctx;
     }
     L.begin(MT_K_ATTN);
-    L.check(bf ? launch_attention_bf16(ag, n, nullptr, rm.seq_start, rm.seq_len, B, S, H, A, L.st)
+    // (MT_FP8_LAYER: the context is written as E4M3, one byte per element, into the same buffer)
+    L.check(bf ? launch_attention_bf16(ag, n, nullptr, rm.seq_start, rm.seq_len, B, S, H, A, L.st, f8a ? 1 : 0)
                : launch_attention_f32(ag, n, nullptr, rm.seq_start, rm.seq_len, B, S, H, A, L.st));
     L.end();
 
@@ -437,7 +495,7 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& 
     const bool f8 = m->fp8;
     auto pick_splits = [&](int K, int N, int max_splits, int max_splits_few) {
         if (!bf || n != 1 || io[0].scr->y_parts < 2) return 1;
-        if (f8 && K == F) return 1;                                  // the FP8 contraction has no K split
+        if ((f8 && K == F) || f8a) return 1;                         // the FP8 contraction has no K split
         const long tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
         if (tiles128 >= 256) return 1;
         // a launch of at most MT_FEW_TILES 64x128 tiles leaves most CUs idle: there the K ranges pay
@@ -452,14 +510,21 @@ void run_layer_group(Launcher& L, const std::vector<LayerIO>& io, const RowMap& 
     const int sp_o = pick_splits(H, H, MT_MAX_SPLITS_OUT, MT_FEW_SPLITS_OUT);
     for (int i = 0; i < n; ++i) {
         g.A[i] = ws + io[i].scr->ctx;
-        g.W[i] = W + io[i].w->Wo;
+        g.W[i] = W + (f8a ? io[i].w->Woq : io[i].w->Wo);
         g.bias[i] = (fuse_res && sp_o == 1) ? (const float*)(W + io[i].w->bo) : nullptr;
         g.residual[i] = (fuse_res && sp_o == 1) ? io[i].in_f : nullptr;
         g.C[i] = ws + io[i].scr->y;
         g.N[i] = H;
+        g.scale[i] = io[i].w->inv_so;
     }
     s = GemmShape{n, M, H, H, H, H, H, ACT_NONE, 1, rm.n_rows, sp_o, (int64_t)m->Mmax * H};
-    L.gemm(MT_K_GEMM_OUT, g, s, false);
+    if (f8a) {
+        L.begin(MT_K_GEMM_OUT);
+        L.check(launch_gemm_fp8(g, s, L.st));
+        L.end();
+    } else {
+        L.gemm(MT_K_GEMM_OUT, g, s, false);
+    }
 
     LnGroup lg;
     memset(&lg, 0, sizeof lg);
@@ -768,11 +833,12 @@ int mt_create(const mt_config* cfg, mt_model** out)
         cfg->n_trunk_layers < 0 || cfg->max_batch < 1 || cfg->max_seq < 1)
         return MT_ERR_CONFIG;
     if (cfg->hidden % cfg->heads != 0 || cfg->max_seq > cfg->max_pos) return MT_ERR_CONFIG;
-    if (cfg->precision != MT_BF16 && cfg->precision != MT_FP32_CHECK && cfg->precision != MT_FP8_FFN) return MT_ERR_CONFIG;
+    if (cfg->precision != MT_BF16 && cfg->precision != MT_FP32_CHECK && cfg->precision != MT_FP8_FFN && cfg->precision != MT_FP8_LAYER)
+        return MT_ERR_CONFIG;
     if (cfg->gelu != MT_GELU_ERF && cfg->gelu != MT_GELU_TANH) return MT_ERR_CONFIG;
     if (!(cfg->ln_eps >= 0.0f)) return MT_ERR_CONFIG;
     // (the FP8 contraction walks K in slices of 64 through a 3-stage ring: K >= 192 for both feed-forward matrices)
-    if (cfg->precision == MT_FP8_FFN && (cfg->hidden < 192 || cfg->ffn < 192)) return MT_ERR_CONFIG;
+    if ((cfg->precision == MT_FP8_FFN || cfg->precision == MT_FP8_LAYER) && (cfg->hidden < 192 || cfg->ffn < 192)) return MT_ERR_CONFIG;
     if (cfg->precision != MT_FP32_CHECK &&
         (cfg->hidden != cfg->heads * 64 || cfg->hidden % 64 != 0 || cfg->ffn % 64 != 0 || cfg->max_seq > kAttnBf16MaxSeq))
         return MT_ERR_CONFIG;
@@ -792,7 +858,8 @@ int mt_create(const mt_config* cfg, mt_model** out)
     m->tasks.assign(cfg->tasks, cfg->tasks + cfg->n_tasks);
     m->cfg.tasks = m->tasks.data();
     m->bf16 = cfg->precision != MT_FP32_CHECK;
-    m->fp8 = cfg->precision == MT_FP8_FFN;
+    m->fp8 = cfg->precision == MT_FP8_FFN || cfg->precision == MT_FP8_LAYER;
+    m->fp8_attn = cfg->precision == MT_FP8_LAYER;
     m->esz = m->bf16 ? 2 : 4;
     const size_t H = cfg->hidden, F = cfg->ffn, T = cfg->n_tasks, D = cfg->n_trunk_layers;
     for (const auto& d : m->tasks) {
@@ -808,13 +875,13 @@ int mt_create(const mt_config* cfg, mt_model** out)
     m->w_type = wb.take((size_t)cfg->type_vocab * H * m->esz);
     m->w_embg = wb.take(H * 4);
     m->w_embb = wb.take(H * 4);
-    for (size_t l = 0; l < D; ++l) m->trunk.push_back(layout_layer(wb, H, F, m->esz, m->fp8));
+    for (size_t l = 0; l < D; ++l) m->trunk.push_back(layout_layer(wb, H, F, m->esz, m->fp8, m->fp8_attn));
     m->w_trunk_end = wb.off;
     m->taskw.resize(T);
     for (size_t t = 0; t < T; ++t) {
         TaskW& tw = m->taskw[t];
         tw.begin = wb.off;
-        for (int l = 0; l < m->tasks[t].n_layers; ++l) tw.layers.push_back(layout_layer(wb, H, F, m->esz, m->fp8));
+        for (int l = 0; l < m->tasks[t].n_layers; ++l) tw.layers.push_back(layout_layer(wb, H, F, m->esz, m->fp8, m->fp8_attn));
         const bool seq_head = m->tasks[t].head == MT_HEAD_SEQUENCE;
         if (m->bf16 && seq_head && !tw.layers.empty()) tw.layers.back().WkT = wb.take(H * H * 2);
         tw.Wp = seq_head ? wb.take(H * H * m->esz * (m->bf16 ? 2 : 1)) : 0;
@@ -995,11 +1062,15 @@ int mt_share_weights(mt_model* m, const mt_model* owner)
     for (size_t l = 0; l < m->trunk.size(); ++l) {                 // the storage scales live beside the layout
         m->trunk[l].inv_s1 = owner->trunk[l].inv_s1;
         m->trunk[l].inv_s2 = owner->trunk[l].inv_s2;
+        m->trunk[l].inv_sqkv = owner->trunk[l].inv_sqkv;
+        m->trunk[l].inv_so = owner->trunk[l].inv_so;
     }
     for (size_t t = 0; t < m->taskw.size(); ++t)
         for (size_t l = 0; l < m->taskw[t].layers.size(); ++l) {
             m->taskw[t].layers[l].inv_s1 = owner->taskw[t].layers[l].inv_s1;
             m->taskw[t].layers[l].inv_s2 = owner->taskw[t].layers[l].inv_s2;
+            m->taskw[t].layers[l].inv_sqkv = owner->taskw[t].layers[l].inv_sqkv;
+            m->taskw[t].layers[l].inv_so = owner->taskw[t].layers[l].inv_so;
         }
     return MT_OK;
 }

@@ -650,6 +650,37 @@ hipError_t launch_scatter_logits(const RequestPtrs& rq, int n_req, int batch, in
     return hipGetLastError();
 }
 
+// bfloat16 rows -> OCP FP8 E4M3 rows at unit scale (round to nearest even, saturating): the operand copy of a layer
+// input for the FP8 form of the QKV projection.  One thread converts 8 consecutive elements (16 bytes in, 8 out).
+__global__ __launch_bounds__(256) void cast_bf16_to_e4m3_kernel(CastGroup g, int M, const int32_t* __restrict__ d_M, int H)
+{
+    if (d_M) M = min(M, *d_M);
+    const size_t n8 = (size_t)M * H / 8;
+    const uint4* __restrict__ src = static_cast<const uint4*>(g.src[blockIdx.y]);
+    uint2* __restrict__ dst = static_cast<uint2*>(g.dst[blockIdx.y]);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+        const uint4 v = src[i];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        float f[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            f[2 * e] = __uint_as_float(w[e] << 16);
+            f[2 * e + 1] = __uint_as_float(w[e] & 0xFFFF0000u);
+        }
+        dst[i] = make_uint2(pack_e4m3(f[0], f[1], f[2], f[3]), pack_e4m3(f[4], f[5], f[6], f[7]));
+    }
+}
+
+hipError_t launch_cast_bf16_to_e4m3(const CastGroup& g, int G, int M, const int32_t* d_M, int H, hipStream_t stream)
+{
+    if (G <= 0 || M <= 0) return hipSuccess;
+    if (G > kMaxGroup || H % 8 != 0) return hipErrorInvalidValue;
+    const size_t n8 = (size_t)M * H / 8;
+    const int blocks = (int)std::min<size_t>((n8 + 255) / 256, 8192);
+    hipLaunchKernelGGL(cast_bf16_to_e4m3_kernel, dim3(blocks, G), dim3(256), 0, stream, g, M, d_M, H);
+    return hipGetLastError();
+}
+
 // One workgroup: counts the sequences whose first position is padding.
 __global__ __launch_bounds__(256) void count_bad_first_tokens_kernel(const int32_t* __restrict__ mask, int B, int S, int32_t* __restrict__ count)
 {

@@ -351,3 +351,44 @@ def test_fp8_variant_configuration_rules():
     L.mt_destroy(h2)
     small = dataclasses.replace(spec, hidden=128, heads=2, ffn=256)          # K of the first contraction below the 3-slice ring
     assert _create(small)[0] == mt.MT_ERR_CONFIG
+
+
+def test_fp8_layer_precision_generator_and_configuration():
+    """MT_FP8_LAYER: the generator puts Wq, Wk, Wv of a layer on the E4M3 grid of ONE storage scale (that of the three
+    together, as the library stores them in one matrix) and Wo, W1, W2 on their own; the library's rule applied to the
+    stacked matrix reproduces the values exactly; the arena grows by the four E4M3 copies per layer."""
+    torch = pytest.importorskip("torch")
+    small = ms.MTSpec("fp8_all_host", vocab=100, hidden=256, heads=4, ffn=512, max_pos=32, n_trunk_layers=2,
+                      tasks=(ms.TaskSpec(2, 1, 2),), precision="fp8_all", batch=2, seq=16, len_lo=4, len_hi=16)
+    flat, index = ms.make_trunk_params(small)
+    named = {n: flat[o:o + int(np.prod(sh))] for n, sh, o in index}
+    for layer in range(small.n_trunk_layers):
+        names = [n for n in named if n.endswith(".Wq") or n == "Wq"]
+        pre = sorted({n.rsplit("Wq", 1)[0] for n in names})[layer]
+        qkv = np.concatenate([named[pre + "Wq"], named[pre + "Wk"], named[pre + "Wv"]])
+        s, codes = mt.e4m3_quantize(qkv)
+        assert s == ms.e4m3_scale(qkv)
+        assert np.array_equal(torch.from_numpy(codes).view(torch.float8_e4m3fn).float().numpy() / np.float32(s), qkv)
+        for one in ("Wo", "W1", "W2"):
+            w = named[pre + one]
+            s1, c1 = mt.e4m3_quantize(w)
+            assert np.array_equal(torch.from_numpy(c1).view(torch.float8_e4m3fn).float().numpy() / np.float32(s1), w)
+    # the bf16 and fp8 precisions draw the same numbers before snapping, and "fp8" leaves the attention matrices on the bf16 grid
+    flat_b, _ = ms.make_trunk_params(dataclasses.replace(small, precision="bf16"))
+    flat_f, _ = ms.make_trunk_params(dataclasses.replace(small, precision="fp8"))
+    n0, sh0, o0 = next((n, sh, o) for n, sh, o in index if n.endswith("Wq"))
+    sl = slice(o0, o0 + int(np.prod(sh0)))
+    assert np.array_equal(flat_b[sl], flat_f[sl]) and not np.array_equal(flat_b[sl], flat[sl])
+    assert np.abs(flat[sl] - flat_b[sl]).max() <= 2.0 ** -4 * np.abs(flat_b[sl]).max()
+    # configuration: accepted, and the arena holds 3HH + HH + 2FH more bytes per layer than the bf16 one
+    base = ms.get_config("base")
+    L = mt.lib()
+    rc, h, _ = _create(dataclasses.replace(base, precision="fp8_all"))
+    rc2, h2, _ = _create(base)
+    assert rc == mt.MT_OK and rc2 == mt.MT_OK
+    n_layers = base.n_trunk_layers + sum(t.n_layers for t in base.tasks)
+    per_layer = 4 * 768 * 768 + 2 * 768 * 3072
+    diff = L.mt_weight_bytes(h) - L.mt_weight_bytes(h2)
+    assert n_layers * per_layer <= diff <= n_layers * (per_layer + 4 * 256)
+    L.mt_destroy(h)
+    L.mt_destroy(h2)

@@ -1,4 +1,5 @@
-"""The FP8 variant (MT_FP8_FFN: the two feed-forward contractions of every all-rows layer in OCP E4M3) against the oracle.
+"""The FP8 variants (MT_FP8_FFN: the two feed-forward contractions of every all-rows layer in OCP E4M3; MT_FP8_LAYER: the
+query/key/value and attention output projections too) against the oracle.
 
 What each side consumes: the generator snaps the feed-forward matrices to the E4M3 grid under their power-of-two
 storage scale (and everything else to the bfloat16 grid), so the float32 oracle and the library hold identical
@@ -9,7 +10,10 @@ Tolerance.  The bf16 path's measured error is about 2e-3 for a bar of 2e-2.  Two
 operands are now 32 times coarser, and they belong to the block whose output is a fraction (about a third at these
 weights) of the residual stream it is added to: expected error about 32 * 0.5 * 2e-3 = 3e-2.  Bar: max |delta logit|
 <= 8e-2 (four times the bf16 bar), and identical argmax on every (sequence, task) pair whose oracle margin exceeds
-twice that.
+twice that.  MT_FP8_LAYER rounds all four contraction operands of a layer to E4M3 (the layer input, the attention
+context, the LayerNorm output, the GELU output).  Independent roundings add in quadrature, so twice as many coarse
+operands raise the expectation by sqrt(2), to about 4.2e-2: the same bar of 8e-2 is kept for both (relative to the
+largest logit when that exceeds 1).
 """
 import dataclasses
 import sys
@@ -25,7 +29,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 import paper_2107_05377_amd as mt  # noqa: E402
 
-TOL = 8e-2
+TOL = {"fp8": 8e-2, "fp8_all": 8e-2}
 
 
 def say(*a):
@@ -113,11 +117,12 @@ def _safe_agreement(spec, got, ref, margin):
     return n, agree
 
 
+@pytest.mark.parametrize("precision", ["fp8", "fp8_all"])
 @pytest.mark.parametrize("stress", [False, True])
-def test_fp8_small_model_whole_batches(stress):
+def test_fp8_small_model_whole_batches(stress, precision):
     """Heterogeneous forks, a task without own layers, a tagging task (all its layers on all rows, so its last layer is
     FP8 too), sequence tasks (last layer first-token-only, bf16), whole batches against the oracle."""
-    spec = SMALL8
+    spec = dataclasses.replace(SMALL8, precision=precision)
     model, orc = _model(spec, stress, 0.05)
     for bi in range(3):
         ids, mask, _ = ms.make_inputs(spec, batch_index=bi)
@@ -126,8 +131,8 @@ def test_fp8_small_model_whole_batches(stress):
         got, tok = got.cpu().numpy(), tok.cpu().numpy()
         real = mask.astype(bool)
         err = max(float(np.abs(got - ref).max()), float(np.abs(tok[real] - ref_tok[real]).max()))
-        bar = TOL * max(1.0, float(np.abs(ref).max()), float(np.abs(ref_tok[real]).max()))
-        say(f"  fp8 small model stress={stress} batch {bi}: max |dlogit| {err:.4g} (bar {bar:.3g})")
+        bar = TOL[precision] * max(1.0, float(np.abs(ref).max()), float(np.abs(ref_tok[real]).max()))
+        say(f"  {precision} small model stress={stress} batch {bi}: max |dlogit| {err:.4g} (bar {bar:.3g})")
         assert err <= bar
         n, agree = _safe_agreement(spec, got, ref, 2 * bar)
         assert agree == n
@@ -144,17 +149,18 @@ def test_fp8_small_model_whole_batches(stress):
     ref = orc.mt_forward(ids, mask)
     e_b = float(np.abs(mb.forward_tokens(dev(ids), dev(mask))[0].cpu().numpy() - ref).max())
     e_8 = float(np.abs(model.forward_tokens(dev(ids), dev(mask))[0].cpu().numpy() - ref).max())
-    say(f"  same checkpoints: bf16 mode {e_b:.4g}, fp8 mode {e_8:.4g}")
+    say(f"  same checkpoints: bf16 mode {e_b:.4g}, {precision} mode {e_8:.4g}")
     assert e_b <= 2e-2 and e_8 > e_b
     mb.close()
     model.close()
 
 
-def test_fp8_base_workload_sampled_and_served():
+@pytest.mark.parametrize("precision", ["fp8", "fp8_all"])
+def test_fp8_base_workload_sampled_and_served(precision):
     """`base` shapes (B = 32, S = 128, 8 tasks) with E4M3 feed-forward matrices: sampled sequences against the oracle
     through mt_forward and through mt_forward_multi (8 request batches per call, the benchmark's configuration),
     replicas share the storage scales."""
-    spec = dataclasses.replace(ms.get_config("base"), name="base_fp8", precision="fp8")
+    spec = dataclasses.replace(ms.get_config("base"), name="base_" + precision, precision=precision)
     model, orc = _model(spec, max_batch=8 * 32)
     ids, mask, lengths = ms.make_inputs(spec)
     rows = [0, int(np.argmin(lengths)), int(np.argmax(lengths)), 17]
@@ -171,10 +177,10 @@ def test_fp8_base_workload_sampled_and_served():
     err_m = float(np.abs(multi[rows] - ref).max())
     rep = model.replica()
     again = rep.forward(dev(ids), dev(mask)).cpu().numpy()
-    say(f"  fp8 base: max |dlogit| {err:.4g} (one request), {err_m:.4g} (eight per call); bar {TOL}")
-    assert err <= TOL and err_m <= TOL
+    say(f"  {precision} base: max |dlogit| {err:.4g} (one request), {err_m:.4g} (eight per call); bar {TOL[precision]}")
+    assert err <= TOL[precision] and err_m <= TOL[precision]
     assert np.array_equal(again, got)
-    n, agree = _safe_agreement(spec, got[rows], ref, 2 * TOL)
+    n, agree = _safe_agreement(spec, got[rows], ref, 2 * TOL[precision])
     assert agree == n
     rep.close()
     model.close()
