@@ -4,7 +4,7 @@
 // memory parallelism instead of operand reuse:
 //   - a workgroup owns a 32-row x 32-column output block; its 4 wavefronts each take a quarter of the
 //     K range and multiply straight from global memory (every lane fetches its own 16-byte MFMA
-//     fragments of A and W, 8 K-steps in flight), so every weight byte is fetched exactly once per
+//     fragments of A and W, 12 K-steps in flight: a quarter of K = 768 in one round trip), so every weight byte is fetched exactly once per
 //     32-row block and there are N/32 x G (x splits) workgroups to spread the stream over the chip;
 //   - the four partial 32x32 tiles meet in LDS, are added in a fixed order, and all 256 threads apply
 //     bias / activation / residual to 4 consecutive columns each and store whole row segments.
@@ -17,7 +17,7 @@ namespace mt {
 namespace {
 
 constexpr int SK_BM = 32, SK_BN = 32;
-constexpr int SK_UNROLL = 8;          // K steps (of 16) in flight per wavefront
+constexpr int SK_UNROLL = 12;          // K steps (of 16) in flight per wavefront
 constexpr int SK_LDP = SK_BN + 4;     // padded row of the float32 partial tile in LDS
 
 __device__ __forceinline__ float skinny_act(float v, int act)
@@ -69,13 +69,26 @@ __global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmGroup g, Gemm
             af[u] = *reinterpret_cast<const bf16x8*>(a_row + (st + u) * 16);
             wf[u] = *reinterpret_cast<const bf16x8*>(w_row + (st + u) * 16);
         }
+        // nothing moves across this point: without it the scheduler sinks the loads between the matrix instructions and
+        // keeps only five of them in flight (seen in the kernel's own assembly), i.e. a third of the bytes per round trip
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < SK_UNROLL; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], af[u], acc, 0, 0, 0);
     }
-    for (; st < steps; ++st) {
-        const bf16x8 af = *reinterpret_cast<const bf16x8*>(a_row + st * 16);
-        const bf16x8 wf = *reinterpret_cast<const bf16x8*>(w_row + st * 16);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, af, acc, 0, 0, 0);
+    if (st < steps) {      // the last, shorter batch (nb is uniform over the workgroup): again one round trip
+        const int nb = steps - st;
+        bf16x8 af[SK_UNROLL], wf[SK_UNROLL];
+#pragma unroll
+        for (int u = 0; u < SK_UNROLL - 1; ++u) {
+            if (u < nb) {
+                af[u] = *reinterpret_cast<const bf16x8*>(a_row + (st + u) * 16);
+                wf[u] = *reinterpret_cast<const bf16x8*>(w_row + (st + u) * 16);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < SK_UNROLL - 1; ++u)
+            if (u < nb) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], af[u], acc, 0, 0, 0);
     }
     // lane holds row m = l32, columns n = 8q + 4*half + {0..3}
 #pragma unroll
