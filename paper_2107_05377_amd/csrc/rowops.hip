@@ -25,10 +25,11 @@ __device__ inline float4 load4<__bf16>(const __bf16* p)
     return make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
 }
 
-// Normalise NV float4 per lane held in registers and store.
+// Normalise NV float4 per lane held in registers and store.  gamma and beta arrive in registers: their loads are issued
+// with the row's, ahead of the two reductions.
 template <int NV>
-__device__ inline void ln_finish_store(float4 (&v)[NV], int lane, int H, const float* gamma, const float* beta,
-                                       float eps, float* out_f32, __bf16* out_bf16, int low_fmt = 0)
+__device__ inline void ln_finish_store(float4 (&v)[NV], const float4 (&g)[NV], const float4 (&b)[NV], int lane, int H, float eps,
+                                       float* out_f32, __bf16* out_bf16, int low_fmt = 0)
 {
     float s = 0.f;
 #pragma unroll
@@ -37,20 +38,18 @@ __device__ inline void ln_finish_store(float4 (&v)[NV], int lane, int H, const f
     float q = 0.f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        float a = v[i].x - mean, b = v[i].y - mean, c = v[i].z - mean, d = v[i].w - mean;
-        q += (a * a + b * b) + (c * c + d * d);
+        float a = v[i].x - mean, bb = v[i].y - mean, c = v[i].z - mean, d = v[i].w - mean;
+        q += (a * a + bb * bb) + (c * c + d * d);
     }
     const float inv = 1.0f / sqrtf(wave_sum(q) / (float)H + eps);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int col = (i * 64 + lane) * 4;
-        const float4 g = *reinterpret_cast<const float4*>(gamma + col);
-        const float4 b = *reinterpret_cast<const float4*>(beta + col);
         float4 o;
-        o.x = g.x * ((v[i].x - mean) * inv) + b.x;
-        o.y = g.y * ((v[i].y - mean) * inv) + b.y;
-        o.z = g.z * ((v[i].z - mean) * inv) + b.z;
-        o.w = g.w * ((v[i].w - mean) * inv) + b.w;
+        o.x = g[i].x * ((v[i].x - mean) * inv) + b[i].x;
+        o.y = g[i].y * ((v[i].y - mean) * inv) + b[i].y;
+        o.z = g[i].z * ((v[i].z - mean) * inv) + b[i].z;
+        o.w = g[i].w * ((v[i].w - mean) * inv) + b[i].w;
         if (out_f32) *reinterpret_cast<float4*>(out_f32 + col) = o;
         if (out_bf16 && low_fmt == 1) {                   // E4M3, one byte per element
             *reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(out_bf16) + col) = pack_e4m3(o.x, o.y, o.z, o.w);
@@ -61,7 +60,20 @@ __device__ inline void ln_finish_store(float4 (&v)[NV], int lane, int H, const f
     }
 }
 
-// H == NV*256: the whole row lives in registers.
+template <int NV>
+__device__ inline void ln_load_gamma_beta(const float* gamma, const float* beta, int lane, float4 (&g)[NV], float4 (&b)[NV])
+{
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int col = (i * 64 + lane) * 4;
+        g[i] = *reinterpret_cast<const float4*>(gamma + col);
+        b[i] = *reinterpret_cast<const float4*>(beta + col);
+    }
+}
+
+// H == NV*256: the whole row lives in registers.  All of a lane's loads (row, residual, bias, gamma, beta: 5 NV
+// 16-byte loads) are issued before the first use, in blocks without uses of their own, so that a wavefront pays one
+// memory round trip per row (loads guarded one by one, each followed by its add, were waited for one at a time).
 template <int NV>
 __global__ __launch_bounds__(256) void layernorm_fast(LnGroup g, int M, const int32_t* __restrict__ d_M, int H, float eps,
                                                       int n_parts, int64_t part_stride, int low_fmt)
@@ -74,29 +86,44 @@ __global__ __launch_bounds__(256) void layernorm_fast(LnGroup g, int M, const in
     const float* x = g.x[grp] + (size_t)row * H;
     const float* res = g.residual[grp] ? g.residual[grp] + (size_t)row * H : nullptr;
     const float* bias = g.bias[grp];
-    float4 v[NV];
+    float4 v[NV], rv[NV], bv[NV], gm[NV], bt[NV];
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const int col = (i * 64 + lane) * 4;
-        v[i] = *reinterpret_cast<const float4*>(x + col);
-        for (int p = 1; p < n_parts; ++p) {                       // fixed order: deterministic
-            const float4 t = *reinterpret_cast<const float4*>(x + (size_t)p * part_stride + col);
+    for (int i = 0; i < NV; ++i) v[i] = *reinterpret_cast<const float4*>(x + (i * 64 + lane) * 4);
+    if (res) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) rv[i] = *reinterpret_cast<const float4*>(res + (i * 64 + lane) * 4);
+    } else {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) rv[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (bias) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) bv[i] = *reinterpret_cast<const float4*>(bias + (i * 64 + lane) * 4);
+    } else {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) bv[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    ln_load_gamma_beta<NV>(g.gamma[grp], g.beta[grp], lane, gm, bt);
+    __builtin_amdgcn_sched_barrier(0);
+    for (int p = 1; p < n_parts; ++p) {                           // fixed order: deterministic
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const float4 t = *reinterpret_cast<const float4*>(x + (size_t)p * part_stride + (i * 64 + lane) * 4);
             v[i].x += t.x; v[i].y += t.y; v[i].z += t.z; v[i].w += t.w;
         }
-        if (bias) {
-            const float4 t = *reinterpret_cast<const float4*>(bias + col);
-            v[i].x += t.x; v[i].y += t.y; v[i].z += t.z; v[i].w += t.w;
-        }
-        if (res) {
-            const float4 t = *reinterpret_cast<const float4*>(res + col);
-            v[i].x += t.x; v[i].y += t.y; v[i].z += t.z; v[i].w += t.w;
-        }
+    }
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {                                // (sum of partial products + bias) + residual, as before
+        v[i].x = (v[i].x + bv[i].x) + rv[i].x;
+        v[i].y = (v[i].y + bv[i].y) + rv[i].y;
+        v[i].z = (v[i].z + bv[i].z) + rv[i].z;
+        v[i].w = (v[i].w + bv[i].w) + rv[i].w;
     }
     float* of = g.out_f32[grp] ? g.out_f32[grp] + (size_t)row * H : nullptr;
     // the low-precision copy's row is H elements of 2 bytes (bf16) or 1 byte (E4M3)
     __bf16* ob = g.out_bf16[grp] ? reinterpret_cast<__bf16*>(reinterpret_cast<unsigned char*>(g.out_bf16[grp]) + (size_t)row * H * (low_fmt == 1 ? 1 : 2))
                                  : nullptr;
-    ln_finish_store<NV>(v, lane, H, g.gamma[grp], g.beta[grp], eps, of, ob, low_fmt);
+    ln_finish_store<NV>(v, gm, bt, lane, H, eps, of, ob, low_fmt);
 }
 
 // Any H: three strided passes over the row (it stays in cache between passes).
@@ -164,7 +191,9 @@ __global__ __launch_bounds__(256) void embed_ln_fast(const int32_t* ids, const i
         float4 a = load4<TE>(w + col), b = load4<TE>(p + col), c = load4<TE>(type + col);
         v[i] = make_float4((a.x + b.x) + c.x, (a.y + b.y) + c.y, (a.z + b.z) + c.z, (a.w + b.w) + c.w);
     }
-    ln_finish_store<NV>(v, lane, H, gamma, beta, eps, out_f32 ? out_f32 + (size_t)row * H : nullptr,
+    float4 gm[NV], bt[NV];
+    ln_load_gamma_beta<NV>(gamma, beta, lane, gm, bt);
+    ln_finish_store<NV>(v, gm, bt, lane, H, eps, out_f32 ? out_f32 + (size_t)row * H : nullptr,
                         out_bf16 ? out_bf16 + (size_t)row * H : nullptr);
 }
 
