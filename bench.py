@@ -578,7 +578,7 @@ def main():
         side["base_fp8_layer"] = side_workload(mt, ms, "base", 8, 2, 48, 8, precision="fp8_all")
         side["hetero"] = side_workload(mt, ms, "hetero", 4, 2, 32, 4)
         side["large"] = side_workload(mt, ms, "large", 1, 2, 16, 2)
-        side["industrial"] = side_workload(mt, ms, "industrial", 8, 2, 128, 8)
+        side["industrial"] = side_workload(mt, ms, "industrial", 32, 2, 256, 64)   # short utterances: 32 requests fill a call
         side["latency"] = side_workload(mt, ms, "latency", 1, 1, 64, 8, latency_calls=args.latency_calls)
         line["workloads"] = side
     print(json.dumps(line))

@@ -181,7 +181,7 @@ int mt_check_mask(mt_model* m, const int32_t* d_attn_mask, int32_t batch, int32_
  * back, the columns of enabled tasks only (others are left untouched, as in mt_forward).  Same shapes for every
  * request; sequences of different requests never interact.  Results equal mt_forward per request up to the
  * rounding differences between launch shapes (the contraction kernel is chosen by row count).
- * Needs 1 <= n_requests <= 16, n_requests * batch <= max_batch, sequence-level heads only, C_tot <= 1024.
+ * Needs 1 <= n_requests <= 64, n_requests * batch <= max_batch, sequence-level heads only, C_tot <= 1024.
  * Enqueues on hip_stream only.  Errors: NULL, SHAPE, CONFIG (token-level task enabled), STATE, HIP.
  */
 int mt_forward_multi(mt_model* m, int32_t n_requests, const int32_t* const* h_d_input_ids, const int32_t* const* h_d_attn_mask,

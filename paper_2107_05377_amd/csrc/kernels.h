@@ -202,7 +202,7 @@ hipError_t launch_token_classifier(const TokGroup& g, int G, int n_pos, int H, i
 // Several request batches served by one forward pass: request r's ids and mask ([batch][seq] each) are copied behind
 // one another into contiguous staging arrays, and afterwards the logits rows of the combined batch go back to each
 // request's own [batch][ldo] array, only the columns whose bit is set in col_on (bit c of word c/32).
-constexpr int kMaxRequests = 16;
+constexpr int kMaxRequests = 64;
 constexpr int kMaxLogitCols = 1024;
 struct RequestPtrs {
     const int32_t* ids[kMaxRequests];

@@ -1181,3 +1181,26 @@ def test_forward_is_capture_safe_and_replays_bit_identically():
         assert torch.equal(out_g, want)
         del graph
     model.close()
+
+
+def test_sixty_four_requests_in_one_forward_and_one_too_many():
+    """The largest request count of mt_forward_multi (64): single-sequence requests of a small bf16 model, each against
+    the oracle; 65 requests are refused."""
+    spec = dataclasses.replace(SMALL, batch=1)
+    tr, tri, tps = _params(spec, True, 0.05)
+    orc = oracle.Oracle(spec, tr, [p for p, _ in tps])
+    model = _load(spec, tr, tri, tps, max_batch=65)
+    reqs, refs = [], []
+    for r in range(65):
+        ids, mask, _ = ms.make_inputs(spec, batch=1, batch_index=100 + r)
+        reqs.append((dev(ids), dev(mask)))
+        if r < 64:
+            refs.append(orc.mt_forward(ids, mask))
+    outs = model.forward_multi(reqs[:64])
+    worst = max(float(np.abs(outs[r].cpu().numpy() - refs[r]).max()) for r in range(64))
+    say(f"  64 single-sequence requests in one forward: max |dlogit| {worst:.4g}")
+    assert worst <= 2e-2
+    with pytest.raises(mt.MTError) as ei:
+        model.forward_multi(reqs)
+    assert ei.value.code == mt.MT_ERR_SHAPE and "at most 64" in str(ei.value)
+    model.close()
