@@ -186,6 +186,12 @@ int mt_check_mask(mt_model* m, const int32_t* d_attn_mask, int32_t batch, int32_
  */
 int mt_forward_multi(mt_model* m, int32_t n_requests, const int32_t* const* h_d_input_ids, const int32_t* const* h_d_attn_mask,
                      int32_t batch, int32_t seq, const uint8_t* h_task_mask, float* const* h_d_out_logits, void* hip_stream);
+/* The same with a sequence count of its own per request: h_batch is a HOST array [n_requests], request r's arrays are
+ * [h_batch[r]][seq] and [h_batch[r]][C_tot]; the sum of h_batch must not exceed max_batch.  (mt_forward_multi is this
+ * call with equal counts.)  Errors as above; an error message names the call it came through. */
+int mt_forward_requests(mt_model* m, int32_t n_requests, const int32_t* const* h_d_input_ids, const int32_t* const* h_d_attn_mask,
+                        const int32_t* h_batch, int32_t seq, const uint8_t* h_task_mask, float* const* h_d_out_logits,
+                        void* hip_stream);
 
 /*
  * mt_forward for callers that cannot allocate device memory or let a library do so on their behalf: code under

@@ -27,7 +27,7 @@ EXPORTS = ["mt_create", "mt_destroy", "mt_weight_bytes", "mt_workspace_bytes", "
            "mt_forward", "mt_logit_offset", "mt_n_logits", "mt_layer_count", "mt_last_error", "mt_error_name",
            "mt_read_hidden", "mt_profile_enable", "mt_profile_read", "mt_op_linear", "mt_op_attention",
            "mt_op_layernorm", "mt_op_linear_batched", "mt_debug_set_gemm_tile", "mt_share_weights", "mt_debug_mfma_peak", "mt_forward_typed", "mt_op_linear_sub", "mt_op_first_token_pool", "mt_schedule_steps", "mt_forward_routed",
-           "mt_forward_tokens", "mt_token_logit_offset", "mt_n_token_logits", "mt_forward_static", "mt_forward_multi", "mt_forward_routed_tokens", "mt_op_linear_fp8", "mt_debug_e4m3_quantize", "mt_check_mask"]
+           "mt_forward_tokens", "mt_token_logit_offset", "mt_n_token_logits", "mt_forward_static", "mt_forward_multi", "mt_forward_requests", "mt_forward_routed_tokens", "mt_op_linear_fp8", "mt_debug_e4m3_quantize", "mt_check_mask"]
 MT_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 
 
@@ -67,6 +67,7 @@ def lib():
         L.mt_forward.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_static.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_multi.argtypes = [vp, i32, vp, vp, i32, i32, vp, vp, vp]
+        L.mt_forward_requests.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, vp]
         L.mt_forward_typed.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_routed.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.mt_forward_tokens.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
@@ -241,6 +242,25 @@ class Model:
         p_mask = (C.c_void_p * n)(*[r[1].data_ptr() for r in requests])
         p_out = (C.c_void_p * n)(*[o.data_ptr() for o in outs])
         self._check(lib().mt_forward_multi(self.h, n, p_ids, p_mask, b, s, tm, p_out, _stream()))
+        return outs
+
+    def forward_requests(self, requests, outs=None, task_mask=None):
+        """mt_forward_requests: `requests` is a list of (ids, mask) int32 CUDA tensor pairs [B_r, S] of one S and any B_r;
+        returns the list of float32 CUDA tensors [B_r, C_tot], one per request (enqueued, not synced)."""
+        import torch
+        n = len(requests)
+        s = requests[0][0].shape[1]
+        sizes = [int(r[0].shape[0]) for r in requests]
+        if outs is None:
+            outs = [torch.zeros((b, self.n_logits), dtype=torch.float32, device=requests[0][0].device) for b in sizes]
+        tm = None
+        if task_mask is not None:
+            tm = (C.c_uint8 * len(task_mask))(*[1 if v else 0 for v in task_mask])
+        p_ids = (C.c_void_p * n)(*[r[0].data_ptr() for r in requests])
+        p_mask = (C.c_void_p * n)(*[r[1].data_ptr() for r in requests])
+        p_out = (C.c_void_p * n)(*[o.data_ptr() for o in outs])
+        p_b = (C.c_int32 * n)(*sizes)
+        self._check(lib().mt_forward_requests(self.h, n, p_ids, p_mask, p_b, s, tm, p_out, _stream()))
         return outs
 
     def forward_static(self, ids, mask, out, task_mask=None):

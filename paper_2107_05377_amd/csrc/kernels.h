@@ -208,10 +208,12 @@ struct RequestPtrs {
     const int32_t* ids[kMaxRequests];
     const int32_t* mask[kMaxRequests];
     float* out[kMaxRequests];
+    int32_t first[kMaxRequests + 1];     // request r owns sequences first[r] .. first[r+1]-1 of the combined batch
     uint32_t col_on[kMaxLogitCols / 32];
 };
-hipError_t launch_gather_requests(const RequestPtrs& rq, int n_req, int n_per_req, int32_t* ids_all, int32_t* mask_all, hipStream_t stream);
-hipError_t launch_scatter_logits(const RequestPtrs& rq, int n_req, int batch, int n_cols, const float* logits_all, hipStream_t stream);
+// max_batch: the largest request's sequence count (sizes the grids)
+hipError_t launch_gather_requests(const RequestPtrs& rq, int n_req, int max_batch, int seq, int32_t* ids_all, int32_t* mask_all, hipStream_t stream);
+hipError_t launch_scatter_logits(const RequestPtrs& rq, int n_req, int max_batch, int n_cols, const float* logits_all, hipStream_t stream);
 
 // Per-sequence task routing: a sub-batch of the sequences, as a padding-free row order of its own.
 // idx lists the chosen sequences (ascending batch indices), passed by value with the launch.

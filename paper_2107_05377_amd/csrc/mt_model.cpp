@@ -1531,23 +1531,33 @@ int mt_forward(mt_model* m, const int32_t* d_input_ids, const int32_t* d_attn_ma
     return forward_impl(m, d_input_ids, nullptr, d_attn_mask, batch, seq, h_task_mask, nullptr, d_out_logits, nullptr, hip_stream);
 }
 
-int mt_forward_multi(mt_model* m, int32_t n_requests, const int32_t* const* h_d_input_ids, const int32_t* const* h_d_attn_mask,
-                     int32_t batch, int32_t seq, const uint8_t* h_task_mask, float* const* h_d_out_logits, void* hip_stream)
+int mt_forward_requests(mt_model* m, int32_t n_requests, const int32_t* const* h_d_input_ids, const int32_t* const* h_d_attn_mask,
+                        const int32_t* h_batch, int32_t seq, const uint8_t* h_task_mask, float* const* h_d_out_logits, void* hip_stream)
 {
     if (!m) return MT_ERR_NULL;
-    if (!h_d_input_ids || !h_d_attn_mask || !h_d_out_logits) return fail(m, MT_ERR_NULL, "mt_forward_multi: null pointer table");
+    if (!h_d_input_ids || !h_d_attn_mask || !h_d_out_logits || !h_batch) return fail(m, MT_ERR_NULL, "mt_forward_requests: null table");
     if (n_requests < 1 || n_requests > kMaxRequests)
-        return fail(m, MT_ERR_SHAPE, "mt_forward_multi: %d requests, at most %d per call", n_requests, kMaxRequests);
-    if (batch < 1 || seq < 1 || (int64_t)n_requests * batch > m->cfg.max_batch || seq > m->cfg.max_seq)
-        return fail(m, MT_ERR_SHAPE, "mt_forward_multi: %d requests x batch %d x seq %d outside max_batch %d x max_seq %d", n_requests, batch,
-                    seq, m->cfg.max_batch, m->cfg.max_seq);
-    if (m->C_tot > kMaxLogitCols) return fail(m, MT_ERR_CONFIG, "mt_forward_multi: more than %d logit columns", kMaxLogitCols);
-    if (!m->d_w || !m->d_ws) return fail(m, MT_ERR_STATE, "mt_forward_multi: call mt_bind first");
+        return fail(m, MT_ERR_SHAPE, "mt_forward_requests: %d requests, at most %d per call", n_requests, kMaxRequests);
     RequestPtrs rq;
     memset(&rq, 0, sizeof rq);
+    int64_t total = 0;
+    int largest = 0;
+    for (int r = 0; r < n_requests; ++r) {
+        if (h_batch[r] < 1) return fail(m, MT_ERR_SHAPE, "mt_forward_requests: request %d has batch %d", r, h_batch[r]);
+        rq.first[r] = (int32_t)total;
+        total += h_batch[r];
+        largest = std::max(largest, (int)h_batch[r]);
+        if (total > m->cfg.max_batch) break;
+    }
+    if (seq < 1 || total > m->cfg.max_batch || seq > m->cfg.max_seq)
+        return fail(m, MT_ERR_SHAPE, "mt_forward_requests: %d requests with %lld sequences in all x seq %d outside max_batch %d x max_seq %d",
+                    n_requests, (long long)total, seq, m->cfg.max_batch, m->cfg.max_seq);
+    rq.first[n_requests] = (int32_t)total;
+    if (m->C_tot > kMaxLogitCols) return fail(m, MT_ERR_CONFIG, "mt_forward_requests: more than %d logit columns", kMaxLogitCols);
+    if (!m->d_w || !m->d_ws) return fail(m, MT_ERR_STATE, "mt_forward_requests: call mt_bind first");
     for (int r = 0; r < n_requests; ++r) {
         if (!h_d_input_ids[r] || !h_d_attn_mask[r] || !h_d_out_logits[r])
-            return fail(m, MT_ERR_NULL, "mt_forward_multi: request %d has a null device pointer", r);
+            return fail(m, MT_ERR_NULL, "mt_forward_requests: request %d has a null device pointer", r);
         rq.ids[r] = h_d_input_ids[r];
         rq.mask[r] = h_d_attn_mask[r];
         rq.out[r] = h_d_out_logits[r];
@@ -1555,20 +1565,32 @@ int mt_forward_multi(mt_model* m, int32_t n_requests, const int32_t* const* h_d_
     for (size_t t = 0; t < m->tasks.size(); ++t) {
         if (h_task_mask && !h_task_mask[t]) continue;
         if (m->tasks[t].head == MT_HEAD_TOKEN)
-            return fail(m, MT_ERR_CONFIG, "mt_forward_multi: task %zu has a token-level head (use mt_forward_tokens per request)", t);
+            return fail(m, MT_ERR_CONFIG, "mt_forward_requests: task %zu has a token-level head (use mt_forward_tokens per request)", t);
         for (int c = m->logit_off[t]; c < m->logit_off[t] + m->tasks[t].n_classes; ++c) rq.col_on[c >> 5] |= 1u << (c & 31);
     }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     int32_t* ids_all = (int32_t*)(m->d_ws + m->mr_ids);
     int32_t* mask_all = (int32_t*)(m->d_ws + m->mr_mask);
     float* logits_all = (float*)(m->d_ws + m->mr_logits);
-    hipError_t e = launch_gather_requests(rq, n_requests, batch * seq, ids_all, mask_all, st);
-    if (e != hipSuccess) return fail(m, MT_ERR_HIP, "mt_forward_multi: %s", hipGetErrorString(e));
-    const int rc = forward_impl(m, ids_all, nullptr, mask_all, n_requests * batch, seq, h_task_mask, nullptr, logits_all, nullptr, hip_stream);
+    hipError_t e = launch_gather_requests(rq, n_requests, largest, seq, ids_all, mask_all, st);
+    if (e != hipSuccess) return fail(m, MT_ERR_HIP, "mt_forward_requests: %s", hipGetErrorString(e));
+    const int rc = forward_impl(m, ids_all, nullptr, mask_all, (int)total, seq, h_task_mask, nullptr, logits_all, nullptr, hip_stream);
     if (rc != MT_OK) return rc;
-    e = launch_scatter_logits(rq, n_requests, batch, m->C_tot, logits_all, st);
-    if (e != hipSuccess) return fail(m, MT_ERR_HIP, "mt_forward_multi: %s", hipGetErrorString(e));
+    e = launch_scatter_logits(rq, n_requests, largest, m->C_tot, logits_all, st);
+    if (e != hipSuccess) return fail(m, MT_ERR_HIP, "mt_forward_requests: %s", hipGetErrorString(e));
     return MT_OK;
+}
+
+int mt_forward_multi(mt_model* m, int32_t n_requests, const int32_t* const* h_d_input_ids, const int32_t* const* h_d_attn_mask,
+                     int32_t batch, int32_t seq, const uint8_t* h_task_mask, float* const* h_d_out_logits, void* hip_stream)
+{
+    if (!m) return MT_ERR_NULL;
+    if (n_requests < 1 || n_requests > kMaxRequests)
+        return fail(m, MT_ERR_SHAPE, "mt_forward_multi: %d requests, at most %d per call", n_requests, kMaxRequests);
+    if (batch < 1) return fail(m, MT_ERR_SHAPE, "mt_forward_multi: batch %d", batch);
+    int32_t sizes[kMaxRequests];
+    for (int r = 0; r < n_requests; ++r) sizes[r] = batch;
+    return mt_forward_requests(m, n_requests, h_d_input_ids, h_d_attn_mask, sizes, seq, h_task_mask, h_d_out_logits, hip_stream);
 }
 
 // ---- the forward pass for callers that must not allocate: its workspace is a fixed array in device memory that is

@@ -639,43 +639,46 @@ hipError_t launch_token_classifier(const TokGroup& g, int G, int n_pos, int H, i
     return hipGetLastError();
 }
 
-// ids_all[r * n + i] = ids_r[i], mask_all likewise (n = batch * seq of one request)
-__global__ __launch_bounds__(256) void gather_requests_kernel(RequestPtrs rq, int n, int32_t* __restrict__ ids_all,
+// Request r's [batch_r][seq] ids and mask go to rows first[r] .. of the combined [sum batch][seq] arrays.
+__global__ __launch_bounds__(256) void gather_requests_kernel(RequestPtrs rq, int seq, int32_t* __restrict__ ids_all,
                                                               int32_t* __restrict__ mask_all)
 {
     const int r = blockIdx.y;
     const int32_t* __restrict__ ids = rq.ids[r];
     const int32_t* __restrict__ mask = rq.mask[r];
+    const size_t base = (size_t)rq.first[r] * seq;
+    const int n = (rq.first[r + 1] - rq.first[r]) * seq;
     for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) {
-        ids_all[(size_t)r * n + i] = ids[i];
-        mask_all[(size_t)r * n + i] = mask[i];
+        ids_all[base + i] = ids[i];
+        mask_all[base + i] = mask[i];
     }
 }
 
-// out_r[b][c] = logits_all[r * batch + b][c] for the enabled columns c; one workgroup per (row, request)
-__global__ __launch_bounds__(64) void scatter_logits_kernel(RequestPtrs rq, int batch, int n_cols, const float* __restrict__ logits_all)
+// out_r[b][c] = logits_all[first[r] + b][c] for the enabled columns c; one workgroup per (row, request)
+__global__ __launch_bounds__(64) void scatter_logits_kernel(RequestPtrs rq, int n_cols, const float* __restrict__ logits_all)
 {
     const int b = blockIdx.x, r = blockIdx.y;
-    const float* __restrict__ src = logits_all + ((size_t)r * batch + b) * n_cols;
+    if (b >= rq.first[r + 1] - rq.first[r]) return;
+    const float* __restrict__ src = logits_all + ((size_t)rq.first[r] + b) * n_cols;
     float* __restrict__ dst = rq.out[r] + (size_t)b * n_cols;
     for (int c = threadIdx.x; c < n_cols; c += 64)
         if ((rq.col_on[c >> 5] >> (c & 31)) & 1u) dst[c] = src[c];
 }
 
-hipError_t launch_gather_requests(const RequestPtrs& rq, int n_req, int n_per_req, int32_t* ids_all, int32_t* mask_all, hipStream_t stream)
+hipError_t launch_gather_requests(const RequestPtrs& rq, int n_req, int max_batch, int seq, int32_t* ids_all, int32_t* mask_all, hipStream_t stream)
 {
-    if (n_req <= 0 || n_per_req <= 0) return hipSuccess;
+    if (n_req <= 0 || max_batch <= 0 || seq <= 0) return hipSuccess;
     if (n_req > kMaxRequests) return hipErrorInvalidValue;
-    const int bx = std::min(64, (n_per_req + 255) / 256);
-    hipLaunchKernelGGL(gather_requests_kernel, dim3(bx, n_req), dim3(256), 0, stream, rq, n_per_req, ids_all, mask_all);
+    const int bx = (int)std::min<long>(64, ((long)max_batch * seq + 255) / 256);
+    hipLaunchKernelGGL(gather_requests_kernel, dim3(bx, n_req), dim3(256), 0, stream, rq, seq, ids_all, mask_all);
     return hipGetLastError();
 }
 
-hipError_t launch_scatter_logits(const RequestPtrs& rq, int n_req, int batch, int n_cols, const float* logits_all, hipStream_t stream)
+hipError_t launch_scatter_logits(const RequestPtrs& rq, int n_req, int max_batch, int n_cols, const float* logits_all, hipStream_t stream)
 {
-    if (n_req <= 0 || batch <= 0 || n_cols <= 0) return hipSuccess;
+    if (n_req <= 0 || max_batch <= 0 || n_cols <= 0) return hipSuccess;
     if (n_req > kMaxRequests || n_cols > kMaxLogitCols) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(scatter_logits_kernel, dim3(batch, n_req), dim3(64), 0, stream, rq, batch, n_cols, logits_all);
+    hipLaunchKernelGGL(scatter_logits_kernel, dim3(max_batch, n_req), dim3(64), 0, stream, rq, n_cols, logits_all);
     return hipGetLastError();
 }
 

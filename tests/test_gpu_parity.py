@@ -1204,3 +1204,40 @@ def test_sixty_four_requests_in_one_forward_and_one_too_many():
         model.forward_multi(reqs)
     assert ei.value.code == mt.MT_ERR_SHAPE and "at most 64" in str(ei.value)
     model.close()
+
+
+@pytest.mark.parametrize("which", ["fp32", "bf16"])
+def test_requests_of_different_sizes_in_one_forward(which):
+    """mt_forward_requests: requests bring their own sequence counts (1, 3, 2, 7, 1, 4 here); every request gets the
+    oracle's logits for its own sequences, a masked-off task's columns stay untouched, totals beyond max_batch and
+    empty requests are refused."""
+    spec = MINI if which == "fp32" else SMALL
+    tr, tri, tps = _params(spec, True, 0.1 if which == "fp32" else 0.05)
+    orc = oracle.Oracle(spec, tr, [p for p, _ in tps])
+    sizes = [1, 3, 2, 7, 1, 4]
+    model = _load(spec, tr, tri, tps, max_batch=sum(sizes))
+    reqs, refs = [], []
+    for r, b in enumerate(sizes):
+        ids, mask, _ = ms.make_inputs(spec, batch=b, batch_index=40 + r)
+        reqs.append((dev(ids), dev(mask)))
+        refs.append(orc.mt_forward(ids, mask))
+    tm = [1] * spec.n_tasks
+    tm[1] = 0
+    outs = [torch.full((b, model.n_logits), 7.0, device="cuda") for b in sizes]
+    model.forward_requests(reqs, outs=outs, task_mask=tm)
+    off = spec.logit_offset(1)
+    dead = slice(off, off + spec.tasks[1].n_classes)
+    for r in range(len(sizes)):
+        got = outs[r].cpu().numpy()
+        assert (got[:, dead] == 7.0).all()
+        live = np.ones(got.shape[1], dtype=bool)
+        live[dead] = False
+        if which == "fp32":
+            assert np.abs(got[:, live] - refs[r][:, live]).max() <= 1e-4 * max(np.abs(refs[r]).max(), 1e-3)
+        else:
+            assert np.abs(got[:, live] - refs[r][:, live]).max() <= 2e-2
+    extra = ms.make_inputs(spec, batch=1, batch_index=77)
+    with pytest.raises(mt.MTError) as ei:
+        model.forward_requests(reqs + [(dev(extra[0]), dev(extra[1]))])
+    assert ei.value.code == mt.MT_ERR_SHAPE
+    model.close()
